@@ -1,0 +1,151 @@
+/*
+ * l4q.h - C ABI of the MI355X (gfx950) implementation of the L4Q quantization-aware
+ * LoRA linear layer (arXiv 2402.04902, Sec. 3.2 and App. A).
+ *
+ * Orientation.  The paper writes Y = Wq X with X in R^{i x s x b}.  This library uses the
+ * row-major "tokens first" statement of the same product:
+ *
+ *     Y[T,o] = X[T,i] . Wq[o,i]^T ,   T = batch * sequence.
+ *
+ * Symbols (paper's notation): i / o in- and out-features, r LoRA rank, n bit width,
+ * g quantization group size (g consecutive elements along i within one weight row),
+ * G = i / g groups per row, gamma = alpha / r the merge constant (the paper's "alpha"),
+ * Q_N = -2^(n-1), Q_P = 2^(n-1) - 1.
+ *
+ * Tensors.  All pointers are DEVICE pointers, row-major, contiguous, 16-byte aligned.
+ *   X [T,i], dY [T,o], Y [T,o], dX [T,i], W0 [o,i], A [r,i], B [o,r] :
+ *       float (dtype = L4Q_DTYPE_F32) or bfloat16 (dtype = L4Q_DTYPE_BF16; upper half of
+ *       an IEEE binary32).
+ *   scale, zero, dscale, dzero [o,G] : float always.  "zero" is the real-valued additive
+ *       bias b of Eq. (quant): w = (W - b) / s, Wq = w~ s + b.  It is not an integer zero point.
+ *   dA [r,i], dB [o,r] : float always.
+ * Outputs are overwritten, never accumulated into.
+ *
+ * Ownership.  The caller owns every buffer, workspace included.  The library allocates
+ * nothing, keeps no pointer after a call returns and has no global state, so calls on
+ * different streams may run concurrently as long as their output and workspace buffers are
+ * distinct.
+ *
+ * Streams.  `hip_stream` is a hipStream_t (NULL = the default stream).  All work is
+ * enqueued on it; no entry point synchronises with the host.
+ *
+ * Errors.  Every entry point validates its arguments before it launches anything and
+ * returns L4Q_OK (0) or a negative l4q_status.  Nothing is printed and nothing aborts.
+ * scale <= 0, NaN or Inf inputs are not detected: results are then undefined.
+ *
+ * Arithmetic contract for the discrete part (codes and straight-through mask).  All kernels
+ * evaluate, in IEEE binary32 with one rounding per written operation and no fused
+ * multiply-add,
+ *     acc = 0;  for k = 0..r-1: acc = acc + B[p,k] * A[k,j]
+ *     Wc  = W0[p,j] + gamma * acc           gamma = (float)alpha / (float)r
+ *     w   = (Wc - zero[p,q]) / scale[p,q]   correctly rounded divide
+ *     w~  = rint(min(max(w, Q_N), Q_P))     ties to even
+ *     m   = (Q_N <= w) && (w <= Q_P)
+ * so codes and masks are reproducible bit for bit on any IEEE machine.
+ */
+#ifndef L4Q_H
+#define L4Q_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define L4Q_VERSION 100
+
+typedef enum l4q_status {
+  L4Q_OK = 0,
+  L4Q_ERR_NULL = -1,      /* a required pointer is NULL */
+  L4Q_ERR_SHAPE = -2,     /* non-positive dimension, i % g != 0, or a divisibility rule below */
+  L4Q_ERR_BITS = -3,      /* bits outside 2..8 */
+  L4Q_ERR_DTYPE = -4,     /* dtype not F32 / BF16, or flags has unknown bits */
+  L4Q_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned */
+  L4Q_ERR_WORKSPACE = -6, /* workspace NULL or smaller than l4q_workspace_bytes reports */
+  L4Q_ERR_LAUNCH = -7,    /* a kernel launch failed (hipGetLastError was not hipSuccess) */
+  L4Q_ERR_METHOD = -8     /* unknown initialisation method */
+} l4q_status;
+
+enum { L4Q_DTYPE_F32 = 0, L4Q_DTYPE_BF16 = 1 };
+
+/* flags */
+enum {
+  L4Q_FLAG_NONE = 0,
+  /* bf16 only: run the backward pass through the unfused kernels (dWq written to the
+   * workspace in binary32, quantizer gradients in a separate pass).  Slower; exists so the
+   * fused epilogue can be cross-checked and as the path for group sizes the fused kernel
+   * does not cover. */
+  L4Q_FLAG_UNFUSED_BACKWARD = 1
+};
+
+/* Shape rules: tokens, in_features, out_features, rank >= 1; group_size >= 4, group_size % 4
+ * == 0, in_features % group_size == 0; 2 <= bits <= 8; rank <= 256.
+ * BF16 additionally: group_size % 8 == 0 and out_features % 8 == 0 (16-byte rows). */
+typedef struct l4q_desc {
+  int64_t tokens;       /* T */
+  int64_t in_features;  /* i */
+  int64_t out_features; /* o */
+  int32_t rank;         /* r */
+  int32_t bits;         /* n */
+  int32_t group_size;   /* g */
+  float alpha;          /* LoRA alpha; the merge uses gamma = alpha / rank */
+  int32_t dtype;        /* L4Q_DTYPE_* */
+  int32_t flags;        /* L4Q_FLAG_* */
+} l4q_desc;
+
+/* Bytes of device workspace l4q_forward and l4q_backward need for this descriptor.
+ * Either output pointer may be NULL.  The workspace must be 256-byte aligned. */
+int l4q_workspace_bytes(const l4q_desc* desc, size_t* forward_bytes, size_t* backward_bytes);
+
+/* Forward pass (Sec. 3.2, Eqs. l4q_Wcombine, l4q_Wquant, l4q_Wdequant, l4q_forward):
+ *   Wc = W0 + gamma B A;  w~ = round(clamp((Wc - zero)/scale, Q_N, Q_P));  Wq = w~ scale + zero;
+ *   Y = X Wq^T.
+ * Nothing is kept for the backward pass: the workspace content is dead when the call's work
+ * has finished. */
+int l4q_forward(const l4q_desc* desc, const void* X, const void* W0, const void* A, const void* B,
+                const float* scale, const float* zero, void* Y,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward pass (Sec. 3.2 "Memory Efficient QAT" / "Efficient LoRA Training"; App. A.1, A.2).
+ * Takes only the forward INPUTS plus dY; Wq, w and the mask are recomputed (App. D.2).
+ *   dX     = dY Wq
+ *   dWq    = dY^T X                                       (Eq. appen_wq; never returned)
+ *   dscale = sum over the group of dWq * (m ? w~ - w : w~) (Eq. quant_lsq_s, App. A.1 cases)
+ *   dzero  = sum over the group of dWq * (m ? 0 : 1)       (Eq. appen_lsq_b)
+ *   dA     = gamma B^T (m * dWq),  dB = gamma (m * dWq) A^T (Eqs. appen_l4q_a, appen_l4q_b)
+ * with m the straight-through mask on the pre-round w (Eq. appen_ste). */
+int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void* W0,
+                 const void* A, const void* B, const float* scale, const float* zero,
+                 void* dX, float* dA, float* dB, float* dscale, float* dzero,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Integer codes of the fully quantized layer (what inference consumes; Sec. 3.2, Eq. l4q_Wquant).
+ *   codes [o,i] int8 in [Q_N, Q_P] (may be NULL);
+ *   wcomb [o,i] float: the binary32 merged weight Wc the codes were taken from (may be NULL);
+ *   mask  [o,i] uint8: 1 where Q_N <= w <= Q_P (may be NULL).
+ * `tokens` of the descriptor is ignored.  Needs no workspace. */
+int l4q_export_codes(const l4q_desc* desc, const void* W0, const void* A, const void* B,
+                     const float* scale, const float* zero,
+                     int8_t* codes, float* wcomb, uint8_t* mask, void* hip_stream);
+
+/* Quantization-parameter initialisation from the merged weight (Sec. 3.3, Eq. l4q_quant_init;
+ * App. B, Eq. quant_inits).  Writes scale, zero [o,G].
+ *   L4Q_INIT_ASYMM : s = (max - min) / (Q_P - Q_N),  b = min - s Q_N
+ *   L4Q_INIT_SYMM  : s = max|W| / 2^(n-1),           b = 0
+ *   L4Q_INIT_L4Q   : s = max(|min / Q_N|, |max / Q_P|), b = 0
+ * evaluated in binary32, one rounding per written operation.  `tokens` is ignored. */
+enum { L4Q_INIT_ASYMM = 0, L4Q_INIT_SYMM = 1, L4Q_INIT_L4Q = 2 };
+int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const void* B,
+                     int method, float* scale, float* zero, void* hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char* l4q_status_string(int status);
+
+/* L4Q_VERSION the library was built from. */
+int l4q_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* L4Q_H */

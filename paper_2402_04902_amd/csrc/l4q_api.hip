@@ -1,0 +1,252 @@
+// C ABI of the library: argument validation, workspace carving and kernel sequencing.
+// See include/l4q.h for the contract of every entry point.
+#include "../../include/l4q.h"
+
+#include "l4q_kernels.h"
+
+namespace {
+
+using l4q::bf16_t;
+using l4q::LayerDims;
+
+constexpr size_t kWsAlign = 256;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int check_desc(const l4q_desc* d, bool need_tokens) {
+  if (!d) return L4Q_ERR_NULL;
+  if (d->dtype != L4Q_DTYPE_F32 && d->dtype != L4Q_DTYPE_BF16) return L4Q_ERR_DTYPE;
+  if (d->flags & ~(int32_t)L4Q_FLAG_UNFUSED_BACKWARD) return L4Q_ERR_DTYPE;
+  if (d->bits < 2 || d->bits > 8) return L4Q_ERR_BITS;
+  if (d->in_features < 1 || d->out_features < 1 || d->rank < 1 || d->rank > 256) return L4Q_ERR_SHAPE;
+  if (need_tokens && d->tokens < 1) return L4Q_ERR_SHAPE;
+  if (d->in_features >= (1ll << 30) || d->out_features >= (1ll << 30) || d->tokens >= (1ll << 30)) return L4Q_ERR_SHAPE;
+  if (d->group_size < 4 || !is_pow2(d->group_size) || d->in_features % d->group_size != 0) return L4Q_ERR_SHAPE;
+  if (d->dtype == L4Q_DTYPE_BF16) {
+    if (d->group_size % 8 != 0 || d->out_features % 8 != 0) return L4Q_ERR_SHAPE;
+  }
+  if (!(d->alpha == d->alpha)) return L4Q_ERR_SHAPE;
+  return L4Q_OK;
+}
+
+LayerDims dims_of(const l4q_desc* d) {
+  LayerDims L;
+  L.T = d->tokens;
+  L.i = d->in_features;
+  L.o = d->out_features;
+  L.r = d->rank;
+  L.bits = d->bits;
+  L.g = d->group_size;
+  L.gamma = d->alpha / (float)d->rank;
+  L.qn = -(float)(1 << (d->bits - 1));
+  L.qp = (float)((1 << (d->bits - 1)) - 1);
+  return L;
+}
+
+struct Carver {
+  unsigned char* base;
+  size_t used = 0;
+  explicit Carver(void* p) : base(static_cast<unsigned char*>(p)) {}
+  template <class T> T* take(size_t count) {
+    T* p = base ? reinterpret_cast<T*>(base + used) : nullptr;
+    used += align_up(count * sizeof(T), kWsAlign);
+    return p;
+  }
+};
+
+struct FwdWs {
+  void* wq;  // [o,i] storage type
+  size_t bytes;
+};
+struct BwdWs {
+  void* wq;        // [o,i] storage type
+  bf16_t* wqT;     // [i,o]          (bf16 only)
+  bf16_t* xT;      // [i,Tpad]       (bf16 only)
+  bf16_t* dyT;     // [o,Tpad]       (bf16 only)
+  float* dwq;      // [o,i]
+  float* dA_part;  // [ceil(o/kDaRowBlock), r, i]
+  int64_t Tpad;
+  size_t bytes;
+};
+
+FwdWs carve_fwd(const l4q_desc* d, void* ws) {
+  Carver c(ws);
+  FwdWs w;
+  const size_t n = (size_t)d->out_features * (size_t)d->in_features;
+  w.wq = d->dtype == L4Q_DTYPE_BF16 ? (void*)c.take<bf16_t>(n) : (void*)c.take<float>(n);
+  w.bytes = c.used;
+  return w;
+}
+
+BwdWs carve_bwd(const l4q_desc* d, void* ws) {
+  Carver c(ws);
+  BwdWs w = {};
+  const size_t o = (size_t)d->out_features, i = (size_t)d->in_features;
+  const size_t n = o * i;
+  w.Tpad = (int64_t)align_up((size_t)d->tokens, 8);
+  if (d->dtype == L4Q_DTYPE_BF16) {
+    w.wq = c.take<bf16_t>(n);
+    w.wqT = c.take<bf16_t>(n);
+    w.xT = c.take<bf16_t>(i * (size_t)w.Tpad);
+    w.dyT = c.take<bf16_t>(o * (size_t)w.Tpad);
+  } else {
+    w.wq = c.take<float>(n);
+  }
+  w.dwq = c.take<float>(n);
+  const size_t nrb = (o + l4q::kDaRowBlock - 1) / l4q::kDaRowBlock;
+  w.dA_part = c.take<float>(nrb * (size_t)d->rank * i);
+  w.bytes = c.used;
+  return w;
+}
+
+int launch_status() { return hipGetLastError() == hipSuccess ? L4Q_OK : L4Q_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+int l4q_version(void) { return L4Q_VERSION; }
+
+const char* l4q_status_string(int status) {
+  switch (status) {
+    case L4Q_OK: return "ok";
+    case L4Q_ERR_NULL: return "a required pointer is NULL";
+    case L4Q_ERR_SHAPE: return "invalid shape (dimension, group size or divisibility rule)";
+    case L4Q_ERR_BITS: return "bits must be in 2..8";
+    case L4Q_ERR_DTYPE: return "unknown dtype or flags";
+    case L4Q_ERR_ALIGN: return "pointer not sufficiently aligned";
+    case L4Q_ERR_WORKSPACE: return "workspace missing or too small";
+    case L4Q_ERR_LAUNCH: return "kernel launch failed";
+    case L4Q_ERR_METHOD: return "unknown initialisation method";
+    default: return "unknown status";
+  }
+}
+
+int l4q_workspace_bytes(const l4q_desc* desc, size_t* forward_bytes, size_t* backward_bytes) {
+  const int st = check_desc(desc, true);
+  if (st != L4Q_OK) return st;
+  if (forward_bytes) *forward_bytes = carve_fwd(desc, nullptr).bytes;
+  if (backward_bytes) *backward_bytes = carve_bwd(desc, nullptr).bytes;
+  return L4Q_OK;
+}
+
+int l4q_forward(const l4q_desc* desc, const void* X, const void* W0, const void* A, const void* B,
+                const float* scale, const float* zero, void* Y, void* workspace, size_t workspace_bytes,
+                void* hip_stream) {
+  const int st = check_desc(desc, true);
+  if (st != L4Q_OK) return st;
+  if (!X || !W0 || !A || !B || !scale || !zero || !Y) return L4Q_ERR_NULL;
+  if (!aligned(X, 16) || !aligned(W0, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(scale, 16) ||
+      !aligned(zero, 16) || !aligned(Y, 16))
+    return L4Q_ERR_ALIGN;
+  const FwdWs w = carve_fwd(desc, workspace);
+  if (!workspace || workspace_bytes < w.bytes) return L4Q_ERR_WORKSPACE;
+  if (!aligned(workspace, kWsAlign)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16) {
+    bf16_t* wq = static_cast<bf16_t*>(w.wq);
+    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, wq,
+                                    nullptr, nullptr, nullptr, stream);
+    l4q::launch_gemm_bf16_nt((const bf16_t*)X, d.i, wq, d.i, d.T, d.o, d.i, (bf16_t*)Y, nullptr, d.o, stream);
+  } else {
+    float* wq = static_cast<float*>(w.wq);
+    l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, wq, nullptr,
+                                   nullptr, nullptr, stream);
+    // Y[t,p] = sum_j X[t,j] Wq[p,j]
+    l4q::launch_sgemm((const float*)X, d.i, 1, wq, 1, d.i, (float*)Y, d.o, d.T, d.o, d.i, 1.f, stream);
+  }
+  return launch_status();
+}
+
+int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void* W0, const void* A,
+                 const void* B, const float* scale, const float* zero, void* dX, float* dA, float* dB,
+                 float* dscale, float* dzero, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int st = check_desc(desc, true);
+  if (st != L4Q_OK) return st;
+  if (!X || !dY || !W0 || !A || !B || !scale || !zero || !dX || !dA || !dB || !dscale || !dzero) return L4Q_ERR_NULL;
+  const void* ptrs[] = {X, dY, W0, A, B, scale, zero, dX, dA, dB, dscale, dzero};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  const BwdWs w = carve_bwd(desc, workspace);
+  if (!workspace || workspace_bytes < w.bytes) return L4Q_ERR_WORKSPACE;
+  if (!aligned(workspace, kWsAlign)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16) {
+    const bf16_t* W0b = (const bf16_t*)W0;
+    const bf16_t* Ab = (const bf16_t*)A;
+    const bf16_t* Bb = (const bf16_t*)B;
+    bf16_t* wq = static_cast<bf16_t*>(w.wq);
+    // recompute Wq (nothing was kept from the forward pass), then dX = dY . Wq
+    l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, wq, nullptr, nullptr, nullptr, stream);
+    l4q::launch_transpose_u16(wq, d.o, d.i, w.wqT, d.o, stream);
+    l4q::launch_gemm_bf16_nt((const bf16_t*)dY, d.o, w.wqT, d.o, d.T, d.i, d.o, (bf16_t*)dX, nullptr, d.i, stream);
+    // dWq = dY^T . X with the token axis made contiguous (and zero-padded to a multiple of 8)
+    l4q::launch_transpose_u16((const bf16_t*)X, d.T, d.i, w.xT, w.Tpad, stream);
+    l4q::launch_transpose_u16((const bf16_t*)dY, d.T, d.o, w.dyT, w.Tpad, stream);
+    l4q::launch_gemm_bf16_nt(w.dyT, w.Tpad, w.xT, w.Tpad, d.o, d.i, w.Tpad, nullptr, w.dwq, d.i, stream);
+    l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);
+    l4q::launch_dA<bf16_t>(d, Bb, w.dwq, w.dA_part, dA, stream);
+  } else {
+    const float* W0f = (const float*)W0;
+    const float* Af = (const float*)A;
+    const float* Bf = (const float*)B;
+    float* wq = static_cast<float*>(w.wq);
+    l4q::launch_merge_quant<float>(d, W0f, Af, Bf, scale, zero, wq, nullptr, nullptr, nullptr, stream);
+    // dX[t,j] = sum_p dY[t,p] Wq[p,j]
+    l4q::launch_sgemm((const float*)dY, d.o, 1, wq, d.i, 1, (float*)dX, d.i, d.T, d.i, d.o, 1.f, stream);
+    // dWq[p,j] = sum_t dY[t,p] X[t,j]
+    l4q::launch_sgemm((const float*)dY, 1, d.o, (const float*)X, d.i, 1, w.dwq, d.i, d.o, d.i, d.T, 1.f, stream);
+    l4q::launch_quant_grads<float>(d, W0f, Af, Bf, scale, zero, w.dwq, dscale, dzero, dB, stream);
+    l4q::launch_dA<float>(d, Bf, w.dwq, w.dA_part, dA, stream);
+  }
+  return launch_status();
+}
+
+int l4q_export_codes(const l4q_desc* desc, const void* W0, const void* A, const void* B, const float* scale,
+                     const float* zero, int8_t* codes, float* wcomb, uint8_t* mask, void* hip_stream) {
+  const int st = check_desc(desc, false);
+  if (st != L4Q_OK) return st;
+  if (!W0 || !A || !B || !scale || !zero) return L4Q_ERR_NULL;
+  const void* ptrs[] = {W0, A, B, scale, zero, codes, wcomb, mask};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16)
+    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, nullptr,
+                                    codes, wcomb, mask, stream);
+  else
+    l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, nullptr,
+                                   codes, wcomb, mask, stream);
+  return launch_status();
+}
+
+int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const void* B, int method, float* scale,
+                     float* zero, void* hip_stream) {
+  const int st = check_desc(desc, false);
+  if (st != L4Q_OK) return st;
+  if (method != L4Q_INIT_ASYMM && method != L4Q_INIT_SYMM && method != L4Q_INIT_L4Q) return L4Q_ERR_METHOD;
+  if (!W0 || !A || !B || !scale || !zero) return L4Q_ERR_NULL;
+  const void* ptrs[] = {W0, A, B, scale, zero};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16)
+    l4q::launch_init_qparams<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, method, scale, zero,
+                                     stream);
+  else
+    l4q::launch_init_qparams<float>(d, (const float*)W0, (const float*)A, (const float*)B, method, scale, zero,
+                                    stream);
+  return launch_status();
+}
+
+}  // extern "C"

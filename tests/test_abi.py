@@ -1,0 +1,112 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes its workspace sensibly and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2402_04902_amd import binding, inputs
+from paper_2402_04902_amd.inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2402_04902_amd import build
+        build.build_library()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "l4q.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(l4q_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(binding.EXPORTED) <= set(names)
+    assert len(names) >= 7
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.l4q_version() == 100
+
+
+def test_status_strings(lib):
+    seen = set()
+    for st in range(0, -9, -1):
+        s = binding.status_string(st)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 9
+    assert binding.status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    spec = inputs.config3()[0]
+    f, b = binding.l4q_workspace_bytes(binding.make_desc(spec))
+    o, i, T = spec.out_features, spec.in_features, spec.tokens
+    assert f >= 2 * o * i and f < 2 * o * i + 4096          # one transient bf16 Wq
+    assert b >= f
+    assert b < 8 * (o * i + T * i + T * o)                  # no token-sized fp32 buffers, no 2nd fp32 weight copy
+    f32 = binding.make_desc(inputs.config1()[0])
+    f1, b1 = binding.l4q_workspace_bytes(f32)
+    assert f1 >= 4 * 256 * 256 and b1 >= 2 * 4 * 256 * 256
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("tokens", 0, -2), ("in_features", 0, -2), ("out_features", -1, -2), ("rank", 0, -2), ("rank", 257, -2),
+    ("group_size", 96, -2), ("group_size", 2, -2), ("group_size", 4096 * 2, -2),
+    ("bits", 1, -3), ("bits", 9, -3), ("dtype", 2, -4), ("flags", 8, -4), ("out_features", 4100, -2),
+])
+def test_bad_descriptors_are_rejected(lib, field, value, status):
+    spec = LayerSpec("x", 64, 4096, 4096, 16, 32.0, 4, 128, DTYPE_BF16)
+    d = binding.make_desc(spec)
+    setattr(d, field, value)
+    f = ctypes.c_size_t(0)
+    assert lib.l4q_workspace_bytes(ctypes.byref(d), ctypes.byref(f), None) == status
+    # the compute entry points validate before touching the GPU
+    assert lib.l4q_forward(ctypes.byref(d), 16, 16, 16, 16, 16, 16, 16, 256, 1 << 40, None) == status
+    assert lib.l4q_backward(ctypes.byref(d), 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 256, 1 << 40,
+                            None) == status
+
+
+def test_null_alignment_and_workspace_errors(lib):
+    spec = LayerSpec("x", 64, 256, 256, 8, 16.0, 4, 64, DTYPE_F32)
+    d = binding.make_desc(spec)
+    r = ctypes.byref(d)
+    assert lib.l4q_forward(None, 16, 16, 16, 16, 16, 16, 16, 256, 1 << 40, None) == -1
+    assert lib.l4q_forward(r, None, 16, 16, 16, 16, 16, 16, 256, 1 << 40, None) == -1
+    assert lib.l4q_forward(r, 16, 16, 16, 16, 16, 16, None, 256, 1 << 40, None) == -1
+    assert lib.l4q_forward(r, 16, 24, 16, 16, 16, 16, 16, 256, 1 << 40, None) == -5
+    assert lib.l4q_forward(r, 16, 16, 16, 16, 16, 16, 16, None, 1 << 40, None) == -6
+    assert lib.l4q_forward(r, 16, 16, 16, 16, 16, 16, 16, 256, 1024, None) == -6
+    assert lib.l4q_forward(r, 16, 16, 16, 16, 16, 16, 16, 128, 1 << 40, None) == -5
+    assert lib.l4q_backward(r, 16, 16, 16, 16, 16, 16, 16, 16, None, 16, 16, 16, 256, 1 << 40, None) == -1
+    assert lib.l4q_backward(r, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 16, 256, 8, None) == -6
+    assert lib.l4q_export_codes(r, None, 16, 16, 16, 16, None, None, None, None) == -1
+    assert lib.l4q_export_codes(r, 16, 16, 16, 16, 16, 8, None, None, None) == -5
+    assert lib.l4q_init_qparams(r, 16, 16, 16, 7, 16, 16, None) == -8
+    assert lib.l4q_init_qparams(r, 16, 16, 16, 0, None, 16, None) == -1
+
+
+def test_descriptor_layout_matches_header():
+    assert ctypes.sizeof(binding.L4QDesc) == 48
+    assert binding.L4QDesc.alpha.offset == 36 and binding.L4QDesc.flags.offset == 44
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2402_04902_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.lower(), (fn, "mentions the oracle")
+    bench = open(os.path.join(ROOT, "bench.py")).read() if os.path.exists(os.path.join(ROOT, "bench.py")) else ""
+    # the benchmark may touch the oracle only inside its cpu_baseline leg
+    for line_no, line in enumerate(bench.splitlines(), 1):
+        if "import" in line and "oracle" in line:
+            assert line.startswith("    "), f"bench.py:{line_no} imports the oracle at module level"

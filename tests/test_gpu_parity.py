@@ -1,0 +1,168 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Integer codes, masks and the merged weight must match bit for bit;
+floating-point outputs within 1e-4 (binary32 mode) / 2e-2 (bfloat16 I/O) Frobenius-relative."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from paper_2402_04902_amd import inputs
+from paper_2402_04902_amd.inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
+
+from parity_util import check_discrete, check_float_outputs, host_qparams, oracle_all
+
+pytestmark = pytest.mark.gpu
+
+REPORT = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "parity_report.jsonl")
+
+
+def run_case(spec, seed=0, method="asymm", shrink=1.0, flags=0, mutate=None, discrete=True):
+    import torch
+    from paper_2402_04902_amd import binding
+    print(f"case {spec.name} T={spec.tokens} i={spec.in_features} o={spec.out_features} r={spec.rank} "
+          f"n={spec.bits} g={spec.group_size} dtype={spec.dtype} seed={seed} init={method} shrink={shrink} "
+          f"flags={flags}", flush=True)
+    arrs = inputs.make_layer_inputs(spec, seed)
+    if mutate is not None:
+        mutate(arrs)
+    s, b = host_qparams(spec, arrs, method, shrink)
+    dec, Wc32, w32, Y, gr = oracle_all(spec, arrs, s, b)
+    layer = binding.upload(spec, arrs, s, b, flags=flags)
+    rep = {"case": spec.name, "init": method, "shrink": shrink, "flags": flags,
+           "clipped": int((~dec.mask).sum()), "elements": int(dec.mask.size)}
+    if discrete:
+        rep.update(check_discrete(spec, layer, arrs, s, b, dec, Wc32))
+    layer.forward()
+    layer.backward()
+    torch.cuda.synchronize()
+    check_float_outputs(spec, layer, Y, gr, rep)
+    try:
+        os.makedirs(os.path.dirname(REPORT), exist_ok=True)
+        with open(REPORT, "a") as f:
+            f.write(json.dumps(rep) + "\n")
+    except OSError:
+        pass
+    print("   ", rep, flush=True)
+    return rep, layer, gr
+
+
+# ------------------------------------------------------------------ configuration 1 (binary32)
+
+@pytest.mark.parametrize("method,shrink", [("asymm", 1.0), ("asymm", 0.8), ("l4q", 1.0)])
+def test_config1_fp32(method, shrink):
+    rep, _, _ = run_case(inputs.config1()[0], seed=0, method=method, shrink=shrink)
+    if shrink < 1.0:
+        assert rep["clipped"] > 0
+
+
+def test_fp32_ragged_shapes():
+    run_case(LayerSpec("f32_ragged", 37, 96, 50, 3, 6.0, 4, 32, DTYPE_F32, outliers=False), seed=3, shrink=0.7)
+    run_case(LayerSpec("f32_rank20", 130, 192, 70, 20, 10.0, 3, 64, DTYPE_F32), seed=4, shrink=0.8)
+    run_case(LayerSpec("f32_one_token", 1, 64, 9, 1, 2.0, 8, 4, DTYPE_F32), seed=5, shrink=0.9)
+
+
+# ------------------------------------------------------------------ bfloat16, several tiles + ragged tails
+
+@pytest.mark.parametrize("T,i,o,r,bits,g", [
+    (300, 640, 264, 16, 4, 128),     # nothing a multiple of the 256 tile; T not a multiple of 8
+    (1000, 1024, 520, 4, 3, 64),
+    (513, 768, 1032, 20, 4, 256),    # rank above one register chunk
+    (64, 512, 8, 1, 2, 32),          # one row block, rank 1, 2 bits
+    (777, 2048, 776, 8, 8, 2048),    # one group per row
+])
+@pytest.mark.parametrize("shrink", [1.0, 0.8])
+def test_bf16_small_shapes(T, i, o, r, bits, g, shrink):
+    spec = LayerSpec(f"bf16_{T}x{i}x{o}", T, i, o, r, 2.0 * r, bits, g, DTYPE_BF16)
+    rep, _, _ = run_case(spec, seed=T, shrink=shrink)
+    if shrink < 1.0:
+        assert rep["clipped"] > 0
+
+
+def test_bf16_zero_B_is_plain_qat_and_kills_dA():
+    """The paper initialises B = 0: the layer is then plain group-wise QAT of W0 and dA vanishes."""
+    def zero_b(arrs):
+        arrs["B"][...] = 0.0
+    spec = LayerSpec("bf16_zeroB", 256, 512, 256, 8, 16.0, 4, 128, DTYPE_BF16)
+    _, layer, _ = run_case(spec, seed=11, shrink=0.8, mutate=zero_b)
+    assert float(layer.dA.abs().max()) == 0.0
+
+
+def test_bf16_fully_clipped_groups():
+    """A tiny scale clips every element of some groups: only the Q_N / Q_P branches contribute."""
+    spec = LayerSpec("bf16_allclip", 128, 256, 64, 4, 8.0, 4, 64, DTYPE_BF16)
+    rep, layer, gr = run_case(spec, seed=12, shrink=1e-3)
+    assert rep["clipped"] > 0.9 * rep["elements"]
+
+
+# ------------------------------------------------------------------ full sizes (whole tensors)
+
+def test_config2_full_size():
+    run_case(inputs.config2()[0], seed=0, shrink=1.0)
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_config3_full_size_clipped_state(idx):
+    rep, _, _ = run_case(inputs.config3()[idx], seed=idx, shrink=0.8)
+    assert rep["clipped"] > 0
+
+
+@pytest.mark.parametrize("g", [64, 256])
+def test_config4_three_bit_group_sweep(g):
+    spec = inputs.config3()[0].with_(bits=3, group_size=g, tokens=1024, name=f"c4_3bit_g{g}_T1024")
+    run_case(spec, seed=g, shrink=0.8)
+
+
+def test_config4_three_bit_down_projection():
+    spec = inputs.config3()[1].with_(bits=3, tokens=1024, name="c4_3bit_down_T1024")
+    run_case(spec, seed=7, shrink=0.8)
+
+
+def test_config5_mistral_kv_and_gate():
+    layers = inputs.config5()
+    run_case(layers[1], seed=1, shrink=0.8)                                  # k: [1024 x 4096], T = 8192
+    run_case(layers[4].with_(tokens=2048, name="mistral7b_gate_T2048"), seed=2, shrink=0.8)
+    run_case(layers[6].with_(tokens=2048, name="mistral7b_down_T2048"), seed=3, shrink=1.0)
+
+
+# ------------------------------------------------------------------ initialisation kernel
+
+@pytest.mark.parametrize("dtype", [DTYPE_F32, DTYPE_BF16])
+@pytest.mark.parametrize("method,mid", [("asymm", 0), ("symm", 1), ("l4q", 2)])
+def test_init_qparams_bit_exact(dtype, method, mid):
+    import torch
+    from oracle import l4q_oracle as O
+    from paper_2402_04902_amd import binding
+    for g in (32, 128, 512):
+        spec = LayerSpec(f"init_{method}_g{g}", 8, 1024, 72, 8, 16.0, 4, g, dtype)
+        print("case", spec.name, "dtype", dtype, flush=True)
+        arrs = inputs.make_layer_inputs(spec, seed=g)
+        layer = binding.upload(spec, arrs)
+        binding.l4q_init_qparams(layer.desc, layer.W0, layer.A, layer.B, mid, layer.scale, layer.zero)
+        torch.cuda.synchronize()
+        Wc32 = O.merge_f32(arrs["W0"], arrs["A"], arrs["B"], spec.alpha)
+        s, b = O.init_qparams(Wc32, spec.bits, g, method, dtype=np.float32)
+        assert np.array_equal(layer.scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
+        assert np.array_equal(layer.zero.cpu().numpy().view(np.uint32), b.view(np.uint32))
+        # and the float64 formulas within rounding
+        s64, b64 = O.init_qparams(O.merge(arrs["W0"], arrs["A"], arrs["B"], spec.alpha), spec.bits, g, method)
+        assert np.allclose(s, s64, rtol=1e-5, atol=0) and np.allclose(b, b64, rtol=1e-4, atol=1e-7)
+
+
+# ------------------------------------------------------------------ run-to-run reproducibility
+
+def test_backward_is_bit_reproducible():
+    import torch
+    from paper_2402_04902_amd import binding
+    spec = LayerSpec("repro", 512, 1024, 512, 16, 32.0, 4, 128, DTYPE_BF16)
+    arrs = inputs.make_layer_inputs(spec, 21)
+    s, b = host_qparams(spec, arrs, "asymm", 0.8)
+    layer = binding.upload(spec, arrs, s, b)
+    outs = []
+    for _ in range(2):
+        layer.forward()
+        layer.backward()
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (layer.Y, layer.dX, layer.dA, layer.dB, layer.dscale, layer.dzero)])
+    for a, c in zip(*outs):
+        assert torch.equal(a, c)
