@@ -1,0 +1,136 @@
+#!/usr/bin/env python3
+"""Benchmark of the L4Q layer on one MI355X.
+
+A step is one forward + backward pass of the L4Q linear layer over both LLaMA-7B MLP
+projections (up/gate [11008 x 4096] and down [4096 x 11008]) at T = 4096 tokens, 4-bit,
+group 128, rank 16, bf16 I/O with binary32 accumulation.  Inputs are seeded synthetic tensors,
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+
+
+def cpu_baseline(specs, host_inputs):
+    """Time the CPU oracle (as it stands) on the same workload, forward + backward."""
+    import numpy as np
+    from oracle import l4q_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    flops = 0.0
+    seconds = 0.0
+    for spec, arrs in zip(specs, host_inputs):
+        Wc = O.merge(arrs["W0"], arrs["A"], arrs["B"], spec.alpha)
+        s, b = O.init_qparams(Wc, spec.bits, spec.group_size, "asymm")
+        s, b = s.astype(np.float32), b.astype(np.float32)
+        del Wc
+        t0 = time.perf_counter()
+        O.forward(arrs["X"], arrs["W0"], arrs["A"], arrs["B"], s, b, spec.bits, spec.group_size, spec.alpha)
+        O.backward(arrs["X"], arrs["dY"], arrs["W0"], arrs["A"], arrs["B"], s, b, spec.bits, spec.group_size,
+                   spec.alpha)
+        seconds += time.perf_counter() - t0
+        flops += spec.gemm_flops()
+    return {"value": flops / seconds / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "seconds": seconds,
+            "sample": "whole workload: one fwd+bwd of both layers at T=4096 (float64 numpy oracle, OpenBLAS matmul)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tokens", type=int, default=4096, help=argparse.SUPPRESS)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2402_04902_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    binding.load_library()  # fails loudly if the HIP library is missing
+
+    specs = [s.with_(tokens=args.tokens) for s in inputs.config3()]
+    host_inputs = [inputs.make_layer_inputs(s, seed=k) for k, s in enumerate(specs)]
+    layers = []
+    for spec, arrs in zip(specs, host_inputs):
+        layer = binding.upload(spec, arrs)
+        # scale / zero from per-group min/max of the merged weight, computed on the GPU
+        binding.l4q_init_qparams(layer.desc, layer.W0, layer.A, layer.B, binding.INIT_ASYMM, layer.scale, layer.zero)
+        layers.append(layer)
+    torch.cuda.synchronize()
+
+    def step():
+        for layer in layers:
+            layer.forward()
+        for layer in reversed(layers):
+            layer.backward()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.l4q_profile_gemm(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    gemm_ms, gemm_launches, gemm_flops = binding.l4q_profile_gemm_read()
+    binding.l4q_profile_gemm(False)
+
+    flops_per_step = sum(s.gemm_flops() for s in specs)
+    ms_per_step = elapsed * 1e3 / args.steps
+    tflops = flops_per_step / (ms_per_step * 1e-3) / 1e12
+    gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+
+    kept = sum(s.tokens * s.in_features * 2 for s in specs)
+    lora_kept = sum(s.tokens * (s.in_features + s.rank) * 2 for s in specs)
+    out = {
+        "metric": "L4Q linear fwd+bwd TFLOP/s & % bf16 MFMA peak (LLaMA-7B MLP, 4-bit g128)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "pct_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
+        "config": {"workload": "LLaMA-7B MLP up [11008x4096] + down [4096x11008], T=%d, r=16, alpha=32, "
+                               "4-bit, g=128, fwd+bwd of both layers" % args.tokens,
+                   "flops_per_step": flops_per_step,
+                   "activation_bytes_kept_fwd_to_bwd": kept, "plain_lora_would_keep": lora_kept,
+                   "workspace_bytes_fwd": max(l.fwd_bytes for l in layers),
+                   "workspace_bytes_bwd": max(l.bwd_bytes for l in layers)},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel", "achieved": gemm_tflops,
+                     "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": None, "launches": gemm_launches,
+                     "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
+                     "gemm_share_of_step": gemm_ms / args.steps / ms_per_step},
+    }
+    if not args.no_cpu_baseline:
+        del layers
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(specs, host_inputs)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

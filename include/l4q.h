@@ -22,7 +22,8 @@
  * Outputs are overwritten, never accumulated into.
  *
  * Ownership.  The caller owns every buffer, workspace included.  The library allocates
- * nothing, keeps no pointer after a call returns and has no global state, so calls on
+ * nothing, keeps no pointer after a call returns and has no global state (the opt-in
+ * benchmark switch l4q_profile_gemm aside), so calls on
  * different streams may run concurrently as long as their output and workspace buffers are
  * distinct.
  *
@@ -138,6 +139,16 @@ int l4q_export_codes(const l4q_desc* desc, const void* W0, const void* A, const 
 enum { L4Q_INIT_ASYMM = 0, L4Q_INIT_SYMM = 1, L4Q_INIT_L4Q = 2 };
 int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const void* B,
                      int method, float* scale, float* zero, void* hip_stream);
+
+/* Opt-in timing of the bf16 GEMM launches, for benchmarks (not for use under graph capture:
+ * it creates HIP events).  While enabled, every GEMM the library enqueues is bracketed by two
+ * events recorded on the caller's stream.  This switch and its event list are the library's only
+ * process-wide state.  l4q_profile_gemm(1) clears earlier records and starts recording,
+ * l4q_profile_gemm(0) stops and clears.  l4q_profile_gemm_read waits for the recorded events
+ * (host-blocking) and returns the summed kernel time in milliseconds, the number of launches and
+ * their algorithmic FLOPs (2 M N K each, with the unpadded K); any pointer may be NULL. */
+int l4q_profile_gemm(int enable);
+int l4q_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops);
 
 /* Static, NUL-terminated description of a status code. */
 const char* l4q_status_string(int status);

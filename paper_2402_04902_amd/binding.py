@@ -18,7 +18,7 @@ FLAG_UNFUSED_BACKWARD = 1
 INIT_ASYMM, INIT_SYMM, INIT_L4Q = 0, 1, 2
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
-            "l4q_export_codes", "l4q_init_qparams"]
+            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read"]
 
 
 class L4QDesc(ctypes.Structure):
@@ -59,6 +59,11 @@ def load_library() -> ctypes.CDLL:
     lib.l4q_export_codes.argtypes = [dp, vp, vp, vp, fp, fp, vp, vp, vp, vp]
     lib.l4q_init_qparams.restype = ctypes.c_int
     lib.l4q_init_qparams.argtypes = [dp, vp, vp, vp, ctypes.c_int, fp, fp, vp]
+    lib.l4q_profile_gemm.restype = ctypes.c_int
+    lib.l4q_profile_gemm.argtypes = [ctypes.c_int]
+    lib.l4q_profile_gemm_read.restype = ctypes.c_int
+    lib.l4q_profile_gemm_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
+                                          ctypes.POINTER(ctypes.c_double)]
     _lib = lib
     return lib
 
@@ -116,6 +121,18 @@ def l4q_export_codes(desc: L4QDesc, W0, A, B, scale, zero, codes=None, wcomb=Non
 def l4q_init_qparams(desc: L4QDesc, W0, A, B, method: int, scale, zero) -> None:
     _check(load_library().l4q_init_qparams(ctypes.byref(desc), _ptr(W0), _ptr(A), _ptr(B), int(method), _ptr(scale),
                                            _ptr(zero), _stream()), "l4q_init_qparams")
+
+
+def l4q_profile_gemm(enable: bool) -> None:
+    _check(load_library().l4q_profile_gemm(1 if enable else 0), "l4q_profile_gemm")
+
+
+def l4q_profile_gemm_read() -> Tuple[float, int, float]:
+    """(summed GEMM kernel milliseconds, launches, algorithmic FLOPs) since profiling was enabled."""
+    ms, n, fl = ctypes.c_double(0), ctypes.c_int64(0), ctypes.c_double(0)
+    _check(load_library().l4q_profile_gemm_read(ctypes.byref(ms), ctypes.byref(n), ctypes.byref(fl)),
+           "l4q_profile_gemm_read")
+    return ms.value, n.value, fl.value
 
 
 # ---------------------------------------------------------------------------

@@ -4,6 +4,10 @@
 
 #include "l4q_kernels.h"
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 namespace {
 
 using l4q::bf16_t;
@@ -103,6 +107,36 @@ BwdWs carve_bwd(const l4q_desc* d, void* ws) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? L4Q_OK : L4Q_ERR_LAUNCH; }
 
+// ---- opt-in timing of the GEMM launches (l4q_profile_gemm) ----
+struct GemmProfile {
+  std::mutex mu;
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+  double flops = 0.0;
+} g_prof;
+
+// Enqueue one bf16 GEMM; when profiling is on, bracket it with events on the same stream.
+void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+             int64_t K_algorithmic, bf16_t* C_bf16, float* C_f32, int64_t ldc, hipStream_t stream) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool timed = false;
+  {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (g_prof.on && hipEventCreate(&e0) == hipSuccess) {
+      if (hipEventCreate(&e1) == hipSuccess) timed = true;
+      else (void)hipEventDestroy(e0);
+    }
+  }
+  if (timed) (void)hipEventRecord(e0, stream);
+  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, C_bf16, C_f32, ldc, stream);
+  if (timed) {
+    (void)hipEventRecord(e1, stream);
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.events.emplace_back(e0, e1);
+    g_prof.flops += 2.0 * (double)M * (double)N * (double)K_algorithmic;
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -151,7 +185,7 @@ int l4q_forward(const l4q_desc* desc, const void* X, const void* W0, const void*
     bf16_t* wq = static_cast<bf16_t*>(w.wq);
     l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, wq,
                                     nullptr, nullptr, nullptr, stream);
-    l4q::launch_gemm_bf16_nt((const bf16_t*)X, d.i, wq, d.i, d.T, d.o, d.i, (bf16_t*)Y, nullptr, d.o, stream);
+    gemm_nt((const bf16_t*)X, d.i, wq, d.i, d.T, d.o, d.i, d.i, (bf16_t*)Y, nullptr, d.o, stream);
   } else {
     float* wq = static_cast<float*>(w.wq);
     l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, wq, nullptr,
@@ -185,11 +219,11 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     // recompute Wq (nothing was kept from the forward pass), then dX = dY . Wq
     l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, wq, nullptr, nullptr, nullptr, stream);
     l4q::launch_transpose_u16(wq, d.o, d.i, w.wqT, d.o, stream);
-    l4q::launch_gemm_bf16_nt((const bf16_t*)dY, d.o, w.wqT, d.o, d.T, d.i, d.o, (bf16_t*)dX, nullptr, d.i, stream);
+    gemm_nt((const bf16_t*)dY, d.o, w.wqT, d.o, d.T, d.i, d.o, d.o, (bf16_t*)dX, nullptr, d.i, stream);
     // dWq = dY^T . X with the token axis made contiguous (and zero-padded to a multiple of 8)
     l4q::launch_transpose_u16((const bf16_t*)X, d.T, d.i, w.xT, w.Tpad, stream);
     l4q::launch_transpose_u16((const bf16_t*)dY, d.T, d.o, w.dyT, w.Tpad, stream);
-    l4q::launch_gemm_bf16_nt(w.dyT, w.Tpad, w.xT, w.Tpad, d.o, d.i, w.Tpad, nullptr, w.dwq, d.i, stream);
+    gemm_nt(w.dyT, w.Tpad, w.xT, w.Tpad, d.o, d.i, w.Tpad, d.T, nullptr, w.dwq, d.i, stream);
     l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);
     l4q::launch_dA<bf16_t>(d, Bb, w.dwq, w.dA_part, dA, stream);
   } else {
@@ -247,6 +281,33 @@ int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const 
     l4q::launch_init_qparams<float>(d, (const float*)W0, (const float*)A, (const float*)B, method, scale, zero,
                                     stream);
   return launch_status();
+}
+
+int l4q_profile_gemm(int enable) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  for (auto& ev : g_prof.events) {
+    (void)hipEventDestroy(ev.first);
+    (void)hipEventDestroy(ev.second);
+  }
+  g_prof.events.clear();
+  g_prof.flops = 0.0;
+  g_prof.on = enable != 0;
+  return L4Q_OK;
+}
+
+int l4q_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  double ms = 0.0;
+  for (auto& ev : g_prof.events) {
+    if (hipEventSynchronize(ev.second) != hipSuccess) return L4Q_ERR_LAUNCH;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, ev.first, ev.second) != hipSuccess) return L4Q_ERR_LAUNCH;
+    ms += t;
+  }
+  if (total_ms) *total_ms = ms;
+  if (launches) *launches = (int64_t)g_prof.events.size();
+  if (total_flops) *total_flops = g_prof.flops;
+  return L4Q_OK;
 }
 
 }  // extern "C"
