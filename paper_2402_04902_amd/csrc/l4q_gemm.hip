@@ -15,42 +15,70 @@
 // on a contiguous band of tiles, and inside a band tiles are walked in groups of GROUP_M rows
 // so that concurrently running workgroups share A and B panels in their XCD's L2.
 #include "l4q_device.h"
+#include "l4q_gemm_core.h"
 #include "l4q_kernels.h"
 
 namespace l4q {
 
 namespace {
 
+// ---------------------------------------------------------------------------------------------
+// Fast path: direct-to-LDS ring pipeline (l4q_gemm_core.h) + plain store epilogue.
+// Needs K % BK == 0 and operands below 2 GiB; anything else takes the generic kernel below.
+// ---------------------------------------------------------------------------------------------
+template <class T, bool OUT_BF16>
+__global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                   const bf16_t* __restrict__ B, int64_t ldb, int M,
+                                                                   int N, int K, void* __restrict__ Cout,
+                                                                   int64_t ldc, int tiles_m, int tiles_n) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+  int tile_m, tile_n;
+  gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * T::BM, n0 = tile_n * T::BN;
+  gemm::Accum<T> acc;
+#pragma unroll
+  for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
+  gemm::mainloop<T>(A, lda, B, ldb, M, N, K, m0, n0, lds, acc);
+#pragma unroll
+  for (int a = 0; a < T::TM; ++a) {
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) {
+#pragma unroll
+      for (int eg = 0; eg < 4; ++eg) {
+        int m, n;
+        gemm::acc_coords<T>(a, b, eg, m, n);
+        m += m0;
+        n += n0;
+        if (m < M && n < N) {  // N % 4 == 0: the 4 consecutive columns are all inside
+          const float v[4] = {acc.v[a][b][4 * eg], acc.v[a][b][4 * eg + 1], acc.v[a][b][4 * eg + 2],
+                              acc.v[a][b][4 * eg + 3]};
+          if (OUT_BF16) store4(reinterpret_cast<bf16_t*>(Cout) + (int64_t)m * ldc + n, v);
+          else store4(reinterpret_cast<float*>(Cout) + (int64_t)m * ldc + n, v);
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic kernel: register-staged, bounds-checked loads; any K % 8 == 0.
+// ---------------------------------------------------------------------------------------------
+
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;            // k extent of one LDS stage (bf16 elements)
 constexpr int ROW_BYTES = BK * 2; // 128
-constexpr int NUM_XCD = 8;
-constexpr int GROUP_M = 8;
 
 __device__ __forceinline__ int swizzled_offset(int row, int chunk) {
   return row * ROW_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
-// Map the hardware workgroup id to a tile so that XCD x owns the x-th contiguous band of tiles.
-__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
-  const int total = tiles_m * tiles_n;
-  const int xcd = pid % NUM_XCD;
-  const int local = pid / NUM_XCD;
-  const int per = (total + NUM_XCD - 1) / NUM_XCD;
-  const int tall = total % NUM_XCD;  // number of XCDs that own `per` tiles when total is not a multiple
-  int id;
-  if (tall == 0 || xcd < tall) id = xcd * per + local;
-  else id = tall * per + (xcd - tall) * (per - 1) + local;
-  const int in_group = GROUP_M * tiles_n;
-  const int group = id / in_group;
-  const int first_m = group * GROUP_M;
-  const int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
-  const int rem = id - group * in_group;
-  tm = first_m + rem % gsz;
-  tn = rem / gsz;
-}
+using gemm::tile_of_block;
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 struct Cfg {
@@ -179,6 +207,20 @@ struct CfgT : Cfg<BM, BN, WAVES_M, WAVES_N> {
 
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
                          int64_t K, bf16_t* C_bf16, float* C_f32, int64_t ldc, hipStream_t stream) {
+  typedef gemm::Tile<256, 256, 32, 4> F;
+  const bool fast = K % F::BK == 0 && N % 4 == 0 && ldc % 4 == 0 && M * lda * 2 < (1ll << 30) &&
+                    N * ldb * 2 < (1ll << 30);
+  if (fast) {
+    const int tiles_m = (int)((M + F::BM - 1) / F::BM), tiles_n = (int)((N + F::BN - 1) / F::BN);
+    dim3 grid((unsigned)(tiles_m * tiles_n));
+    if (C_bf16)
+      hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true>), grid, dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M,
+                         (int)N, (int)K, (void*)C_bf16, ldc, tiles_m, tiles_n);
+    else
+      hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, false>), grid, dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M,
+                         (int)N, (int)K, (void*)C_f32, ldc, tiles_m, tiles_n);
+    return;
+  }
   typedef CfgT<256, 256, 2, 2> C;
   const int tiles_m = (int)((M + C::BM_ - 1) / C::BM_), tiles_n = (int)((N + C::BN_ - 1) / C::BN_);
   dim3 grid((unsigned)(tiles_m * tiles_n));

@@ -1,0 +1,244 @@
+// Main loop of the bf16 MFMA GEMM for gfx950:  acc[M,N] += A[M,K] . B[N,K]^T  (binary32 accumulate).
+//
+// One workgroup = 4 wavefronts (2 x 2) computes a BM x BN macro tile; each wavefront owns a
+// (BM/2) x (BN/2) block of 32 x 32 accumulator tiles fed by v_mfma_f32_32x32x16_bf16.
+//
+// Operand path.  Both operands are K-contiguous in memory.  Tiles of BK k-values travel
+// HBM/L2 -> LDS with buffer_load_dwordx4 ... lds (no VGPR staging): one wave instruction fills
+// 1 KiB of LDS, lane l writing bytes [16 l, 16 l + 16).  Rows past the matrix edge are given an
+// out-of-range buffer offset, for which the hardware returns zeros, so the loop has no branches.
+// LDS holds a ring of NS stages; loads run D = NS - 1 stages ahead of the MFMAs and are waited
+// for with a partial s_waitcnt vmcnt(), so HBM latency is covered by D stages of matrix work.
+//
+// LDS layout.  A stage is BM + BN rows of BK bf16 (64 or 128 bytes).  The 16-byte chunk c of
+// row r is stored at chunk position c ^ ((r / RW) % CPR) with CPR chunks per row and RW rows per
+// 256 bytes (one sweep over the 64 banks).  The DMA writes (consecutive lanes = consecutive
+// positions of a row) and the MFMA fragment reads (consecutive lanes = consecutive rows, same
+// logical chunk) both cover all 64 banks once per 16 lanes.
+//
+// Operand order.  The MFMA is issued as D = Bfrag . Afrag^T, i.e. the accumulator tile holds
+// C^T: lane l owns column m = l % 32 of C^T (a row of C) and its 16 registers hold
+// n = 8 (e / 4) + 4 (l / 32) + (e % 4).  Four consecutive registers are four consecutive
+// n (contiguous in memory for row-major C), which gives 8/16-byte stores and, for the weight
+// gradient, makes a lane the owner of one weight row.
+#pragma once
+
+#include "l4q_device.h"
+
+namespace l4q {
+namespace gemm {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+constexpr int NUM_XCD = 8;
+constexpr int GROUP_M = 8;
+// Operands are below 1 GiB.  A row outside the matrix gets OOB_OFFSET; a stage past the end of K adds
+// PAST_END_OFFSET.  Either one, or both together, lands beyond num_records without wrapping 32 bits.
+constexpr unsigned OOB_OFFSET = 0x80000000u;
+constexpr unsigned PAST_END_OFFSET = 0x40000000u;
+
+// gfx9 s_waitcnt immediate for "vmcnt(n)" only
+constexpr int waitcnt_vm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+constexpr int waitcnt_lgkm0() { return 15 | (3 << 14) | (7 << 4) | (0 << 8); }
+
+// Hardware workgroup id -> tile.  Ids go round-robin over the 8 XCDs; XCD x gets the x-th
+// contiguous band of tile ids, and ids walk GROUP_M tile rows at a time.
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int total = tiles_m * tiles_n;
+  const int xcd = pid % NUM_XCD;
+  const int local = pid / NUM_XCD;
+  const int per = (total + NUM_XCD - 1) / NUM_XCD;
+  const int tall = total % NUM_XCD;
+  int id;
+  if (tall == 0 || xcd < tall) id = xcd * per + local;
+  else id = tall * per + (xcd - tall) * (per - 1) + local;
+  const int in_group = GROUP_M * tiles_n;
+  const int group = id / in_group;
+  const int first_m = group * GROUP_M;
+  const int gsz = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+  const int rem = id - group * in_group;
+  tm = first_m + rem % gsz;
+  tn = rem / gsz;
+}
+
+template <int BM_, int BN_, int BK_, int NS_>
+struct Tile {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_;
+  static constexpr int NT = 256;                      // 4 wavefronts, 2 x 2
+  static constexpr int WTM = BM / 2, WTN = BN / 2;    // wave tile
+  static constexpr int TM = WTM / 32, TN = WTN / 32;  // 32 x 32 accumulator tiles per wave
+  static constexpr int CPR = BK / 8;                  // 16-byte chunks per LDS row
+  static constexpr int ROWB = BK * 2;                 // bytes per LDS row
+  static constexpr int RW = 256 / ROWB;               // rows per 256 bytes
+  static constexpr int RPI = 64 / CPR;                // rows filled by one wave-wide load
+  static constexpr int A_INSTR = BM / RPI / 4;        // loads per wave per stage, operand A
+  static constexpr int B_INSTR = BN / RPI / 4;
+  static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
+  static constexpr int STAGE = A_BYTES + B_BYTES;
+  static constexpr int KK = BK / 16;                  // MFMA k-steps per stage
+  static constexpr int D = NS - 1;                    // prefetch distance in stages
+  static constexpr int LDS_BYTES = NS * STAGE;
+  static_assert(BK == 32 || BK == 64, "BK");
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
+  static_assert(BM % (RPI * 4) == 0 && BN % (RPI * 4) == 0, "load split");
+  static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-steps");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+};
+
+template <class T>
+struct Accum {
+  f32x16_t v[T::TM][T::TN];
+};
+
+// Runs the whole K loop for the tile (m0, n0).  K must be a multiple of T::BK; lda, ldb in
+// elements (multiples of 8).  Rows m >= M of A and n >= N of B read as zeros.
+// On return every wave has passed a barrier after its last LDS read, so LDS may be reused.
+template <class T>
+__device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                                         int64_t ldb, int M, int N, int K, int m0, int n0, unsigned char* lds,
+                                         Accum<T>& acc) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the declaration
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in SGPRs
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const __amdgpu_buffer_rsrc_t rsrcA =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, (int)((int64_t)M * lda * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, (int)((int64_t)N * ldb * 2), 0x00020000);
+
+  // per-lane source offsets (bytes) of the loads this wave issues each stage
+  unsigned voffA[T::A_INSTR], voffB[T::B_INSTR];
+#pragma unroll
+  for (int c = 0; c < T::A_INSTR; ++c) {
+    const int row = (wave * T::A_INSTR + c) * T::RPI + lane / T::CPR;
+    const int ch = (lane % T::CPR) ^ ((row / T::RW) % T::CPR);
+    voffA[c] = (m0 + row < M) ? (unsigned)(((int64_t)(m0 + row) * lda + ch * 8) * 2) : OOB_OFFSET;
+  }
+#pragma unroll
+  for (int c = 0; c < T::B_INSTR; ++c) {
+    const int row = (wave * T::B_INSTR + c) * T::RPI + lane / T::CPR;
+    const int ch = (lane % T::CPR) ^ ((row / T::RW) % T::CPR);
+    voffB[c] = (n0 + row < N) ? (unsigned)(((int64_t)(n0 + row) * ldb + ch * 8) * 2) : OOB_OFFSET;
+  }
+
+  // per-lane LDS offsets of the MFMA fragments: row (lane % 32) of a 32-row block, logical chunk
+  // 2 kk + lane / 32.  Block bases are multiples of 16 rows, so the swizzle term depends on the lane only.
+  unsigned frag_off[T::KK];
+  {
+    const int r = lane & 31;
+    const int sw = (r / T::RW) % T::CPR;
+#pragma unroll
+    for (int kk = 0; kk < T::KK; ++kk) frag_off[kk] = r * T::ROWB + (((kk * 2 + (lane >> 5)) ^ sw) << 4);
+  }
+
+  auto issue_loads = [&](int stage, int slot, int nstages) {
+    const unsigned kbytes = stage < nstages ? (unsigned)stage * (T::BK * 2) : PAST_END_OFFSET;
+    unsigned char* base = lds + slot * T::STAGE;
+#pragma unroll
+    for (int c = 0; c < T::A_INSTR; ++c)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base + (wave * T::A_INSTR + c) * 1024), 16,
+                                               voffA[c] + kbytes, 0, 0, 0);
+#pragma unroll
+    for (int c = 0; c < T::B_INSTR; ++c)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rsrcB, (lds_ptr_t)(base + T::A_BYTES + (wave * T::B_INSTR + c) * 1024), 16, voffB[c] + kbytes, 0, 0, 0);
+  };
+
+  bf16x8_t fa[2][T::TM], fb[2][T::TN];
+  auto read_frags = [&](int slot, int kk, int set) {
+    const unsigned char* as = lds + slot * T::STAGE + wm * T::WTM * T::ROWB + frag_off[kk];
+    const unsigned char* bs = lds + slot * T::STAGE + T::A_BYTES + wn * T::WTN * T::ROWB + frag_off[kk];
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a) fa[set][a] = *reinterpret_cast<const bf16x8_t*>(as + a * 32 * T::ROWB);
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) fb[set][b] = *reinterpret_cast<const bf16x8_t*>(bs + b * 32 * T::ROWB);
+  };
+  auto mfma_block = [&](int set) {
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+      for (int b = 0; b < T::TN; ++b)
+        acc.v[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc.v[a][b], 0, 0, 0);
+  };
+
+  const int nk = K / T::BK;
+  constexpr int LOADS = T::A_INSTR + T::B_INSTR;
+#pragma unroll
+  for (int s = 0; s < T::D; ++s) issue_loads(s, s, nk);
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+  __builtin_amdgcn_s_barrier();
+  read_frags(0, 0, 0);
+
+  // Steady state, one basic block per stage.  Loads for stage s + D are issued first (stages past
+  // the end get an out-of-range offset: no memory traffic, and the vmcnt arithmetic stays uniform).
+  int slot = 0;
+  for (int s = 0; s < nk; ++s) {
+    int pslot = slot + T::D;
+    if (pslot >= T::NS) pslot -= T::NS;
+    int nslot = slot + 1;
+    if (nslot == T::NS) nslot = 0;
+#pragma unroll
+    for (int kk = 0; kk < T::KK; ++kk) {
+      if (kk + 1 < T::KK) {
+        // LDS reads first in program order: the DMA loads below write LDS and are kept behind them
+        read_frags(slot, kk + 1, (kk + 1) & 1);
+        if (kk == 0) issue_loads(s + T::D, pslot, nk);
+        mfma_block(kk & 1);
+        if (kk == 0) {
+          // interleave: matrix op, LDS read, ..., then matrix ops with the global loads
+#pragma unroll
+          for (int q = 0; q < T::TM + T::TN; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+#pragma unroll
+          for (int q = 0; q < LOADS; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          }
+        } else {
+#pragma unroll
+          for (int q = 0; q < T::TM + T::TN; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+        }
+      } else {
+        // stage s + 1 must have landed for every wave, and every wave must be done reading stage s - 1's
+        // slot mate before it is refilled: all of this wave's LDS reads so far have returned.
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm((T::D - 1) * LOADS));
+        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+        __builtin_amdgcn_s_barrier();
+        read_frags(nslot, 0, 0);  // after the last stage this reads stale LDS; the values are never used
+        mfma_block(kk & 1);
+#pragma unroll
+        for (int q = 0; q < T::TM + T::TN; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      }
+    }
+    slot = nslot;
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+  __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+  __builtin_amdgcn_s_barrier();
+#endif
+}
+
+// Row m and first column n of the 4 consecutive outputs held in registers 4 eg .. 4 eg + 3 of
+// accumulator tile (a, b), relative to the macro tile origin.
+template <class T>
+__device__ __forceinline__ void acc_coords(int a, int b, int eg, int& m, int& n) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  m = (wave >> 1) * T::WTM + a * 32 + (lane & 31);
+  n = (wave & 1) * T::WTN + b * 32 + 8 * eg + 4 * (lane >> 5);
+}
+
+}  // namespace gemm
+}  // namespace l4q
