@@ -65,13 +65,18 @@ struct FwdWs {
   size_t bytes;
 };
 struct BwdWs {
-  void* wq;        // [o,i] storage type
-  bf16_t* wqT;     // [i,o]          (bf16 only)
-  bf16_t* xT;      // [i,Tpad]       (bf16 only)
-  bf16_t* dyT;     // [o,Tpad]       (bf16 only)
-  float* dwq;      // [o,i]
-  float* dA_part;  // [ceil(o/kDaRowBlock), r, i]
-  int64_t Tpad;
+  bool fused;        // bf16: weight-gradient GEMM with the fused quantizer epilogue
+  float* wq32;       // [o,i]                      (binary32 mode)
+  bf16_t* wqT;       // [i,opad]                   (bf16)
+  bf16_t* xT;        // [i,Tpad]                   (bf16)
+  bf16_t* dyT;       // [o,Tpad]                   (bf16)
+  uint16_t* fgrad;   // [o,i] binary16             (bf16 fused)
+  bf16_t* bT;        // [r,opad]                   (bf16 fused)
+  float* dB_part;    // [2 tiles_n, o, r]          (bf16 fused)
+  float* dwq;        // [o,i]                      (binary32 mode, bf16 unfused)
+  float* dA_part;    // [tiles_m or ceil(o/kDaRowBlock), r, i]
+  int64_t Tpad, opad;
+  int tiles_m, tiles_n;
   size_t bytes;
 };
 
@@ -87,20 +92,33 @@ FwdWs carve_fwd(const l4q_desc* d, void* ws) {
 BwdWs carve_bwd(const l4q_desc* d, void* ws) {
   Carver c(ws);
   BwdWs w = {};
-  const size_t o = (size_t)d->out_features, i = (size_t)d->in_features;
+  const size_t o = (size_t)d->out_features, i = (size_t)d->in_features, r = (size_t)d->rank;
   const size_t n = o * i;
-  w.Tpad = (int64_t)align_up((size_t)d->tokens, 8);
+  // token and out-feature axes are zero-padded to the k-step of the matrix-core kernels
+  w.Tpad = (int64_t)align_up((size_t)d->tokens, 32);
+  w.opad = (int64_t)align_up(o, 32);
+  const LayerDims L = dims_of(d);
+  const size_t nrb = (o + l4q::kDaRowBlock - 1) / l4q::kDaRowBlock;
   if (d->dtype == L4Q_DTYPE_BF16) {
-    w.wq = c.take<bf16_t>(n);
-    w.wqT = c.take<bf16_t>(n);
+    w.fused = !(d->flags & L4Q_FLAG_UNFUSED_BACKWARD) && l4q::dw_fused_supported(L, w.Tpad);
+    w.wqT = c.take<bf16_t>(i * (size_t)w.opad);
     w.xT = c.take<bf16_t>(i * (size_t)w.Tpad);
     w.dyT = c.take<bf16_t>(o * (size_t)w.Tpad);
+    if (w.fused) {
+      l4q::dw_fused_tiles(L, &w.tiles_m, &w.tiles_n);
+      w.fgrad = c.take<uint16_t>(n);
+      w.bT = c.take<bf16_t>(r * (size_t)w.opad);
+      w.dB_part = c.take<float>(2 * (size_t)w.tiles_n * o * r);
+      w.dA_part = c.take<float>((size_t)w.tiles_m * r * i);
+    } else {
+      w.dwq = c.take<float>(n);
+      w.dA_part = c.take<float>(nrb * r * i);
+    }
   } else {
-    w.wq = c.take<float>(n);
+    w.wq32 = c.take<float>(n);
+    w.dwq = c.take<float>(n);
+    w.dA_part = c.take<float>(nrb * r * i);
   }
-  w.dwq = c.take<float>(n);
-  const size_t nrb = (o + l4q::kDaRowBlock - 1) / l4q::kDaRowBlock;
-  w.dA_part = c.take<float>(nrb * (size_t)d->rank * i);
   w.bytes = c.used;
   return w;
 }
@@ -134,6 +152,27 @@ void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t
     std::lock_guard<std::mutex> lk(g_prof.mu);
     g_prof.events.emplace_back(e0, e1);
     g_prof.flops += 2.0 * (double)M * (double)N * (double)K_algorithmic;
+  }
+}
+
+// The fused weight-gradient kernel is a GEMM launch too: time it the same way.
+void dw_fused(const LayerDims& d, const BwdWs& w, const bf16_t* A, float* dscale, float* dzero, hipStream_t stream) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool timed = false;
+  {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (g_prof.on && hipEventCreate(&e0) == hipSuccess) {
+      if (hipEventCreate(&e1) == hipSuccess) timed = true;
+      else (void)hipEventDestroy(e0);
+    }
+  }
+  if (timed) (void)hipEventRecord(e0, stream);
+  l4q::launch_dw_fused(d, w.dyT, w.xT, w.Tpad, w.fgrad, A, w.bT, w.opad, dscale, dzero, w.dA_part, w.dB_part, stream);
+  if (timed) {
+    (void)hipEventRecord(e1, stream);
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.events.emplace_back(e0, e1);
+    g_prof.flops += 2.0 * (double)d.o * (double)d.i * (double)d.T;
   }
 }
 
@@ -183,13 +222,17 @@ int l4q_forward(const l4q_desc* desc, const void* X, const void* W0, const void*
   (void)hipGetLastError();
   if (desc->dtype == L4Q_DTYPE_BF16) {
     bf16_t* wq = static_cast<bf16_t*>(w.wq);
-    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, wq,
-                                    nullptr, nullptr, nullptr, stream);
+    l4q::MergeQuantOut<bf16_t> mq;
+    mq.wq = wq;
+    mq.ld_wq = d.i;
+    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
     gemm_nt((const bf16_t*)X, d.i, wq, d.i, d.T, d.o, d.i, d.i, (bf16_t*)Y, nullptr, d.o, stream);
   } else {
     float* wq = static_cast<float*>(w.wq);
-    l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, wq, nullptr,
-                                   nullptr, nullptr, stream);
+    l4q::MergeQuantOut<float> mq;
+    mq.wq = wq;
+    mq.ld_wq = d.i;
+    l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, mq, stream);
     // Y[t,p] = sum_j X[t,j] Wq[p,j]
     l4q::launch_sgemm((const float*)X, d.i, 1, wq, 1, d.i, (float*)Y, d.o, d.T, d.o, d.i, 1.f, stream);
   }
@@ -215,23 +258,36 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     const bf16_t* W0b = (const bf16_t*)W0;
     const bf16_t* Ab = (const bf16_t*)A;
     const bf16_t* Bb = (const bf16_t*)B;
-    bf16_t* wq = static_cast<bf16_t*>(w.wq);
-    // recompute Wq (nothing was kept from the forward pass), then dX = dY . Wq
-    l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, wq, nullptr, nullptr, nullptr, stream);
-    l4q::launch_transpose_u16(wq, d.o, d.i, w.wqT, d.o, stream);
-    gemm_nt((const bf16_t*)dY, d.o, w.wqT, d.o, d.T, d.i, d.o, d.o, (bf16_t*)dX, nullptr, d.i, stream);
-    // dWq = dY^T . X with the token axis made contiguous (and zero-padded to a multiple of 8)
+    // recompute the quantizer (nothing was kept from the forward pass): Wq^T for dX = dY . Wq and,
+    // for the fused epilogue, the per-element d(Wq)/d(scale) factor
+    l4q::MergeQuantOut<bf16_t> mq;
+    mq.wqT = w.wqT;
+    mq.ld_wqT = w.opad;
+    mq.fgrad = w.fgrad;  // null when unfused
+    l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, mq, stream);
+    gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, nullptr, d.i, stream);
+    // dWq = dY^T . X with the token axis made contiguous and zero-padded
     l4q::launch_transpose_u16((const bf16_t*)X, d.T, d.i, w.xT, w.Tpad, stream);
     l4q::launch_transpose_u16((const bf16_t*)dY, d.T, d.o, w.dyT, w.Tpad, stream);
-    gemm_nt(w.dyT, w.Tpad, w.xT, w.Tpad, d.o, d.i, w.Tpad, d.T, nullptr, w.dwq, d.i, stream);
-    l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);
-    l4q::launch_dA<bf16_t>(d, Bb, w.dwq, w.dA_part, dA, stream);
+    if (w.fused) {
+      l4q::launch_transpose_lora_b(Bb, d.o, d.r, w.bT, w.opad, stream);
+      dw_fused(d, w, Ab, dscale, dzero, stream);
+      l4q::launch_reduce_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, d.gamma, dA, stream);
+      l4q::launch_reduce_partials(w.dB_part, 2 * w.tiles_n, d.o * d.r, d.gamma, dB, stream);
+    } else {
+      gemm_nt(w.dyT, w.Tpad, w.xT, w.Tpad, d.o, d.i, w.Tpad, d.T, nullptr, w.dwq, d.i, stream);
+      l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);
+      l4q::launch_dA<bf16_t>(d, Bb, w.dwq, w.dA_part, dA, stream);
+    }
   } else {
     const float* W0f = (const float*)W0;
     const float* Af = (const float*)A;
     const float* Bf = (const float*)B;
-    float* wq = static_cast<float*>(w.wq);
-    l4q::launch_merge_quant<float>(d, W0f, Af, Bf, scale, zero, wq, nullptr, nullptr, nullptr, stream);
+    float* wq = w.wq32;
+    l4q::MergeQuantOut<float> mq;
+    mq.wq = wq;
+    mq.ld_wq = d.i;
+    l4q::launch_merge_quant<float>(d, W0f, Af, Bf, scale, zero, mq, stream);
     // dX[t,j] = sum_p dY[t,p] Wq[p,j]
     l4q::launch_sgemm((const float*)dY, d.o, 1, wq, d.i, 1, (float*)dX, d.i, d.T, d.i, d.o, 1.f, stream);
     // dWq[p,j] = sum_t dY[t,p] X[t,j]
@@ -253,12 +309,19 @@ int l4q_export_codes(const l4q_desc* desc, const void* W0, const void* A, const 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const LayerDims d = dims_of(desc);
   (void)hipGetLastError();
-  if (desc->dtype == L4Q_DTYPE_BF16)
-    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, nullptr,
-                                    codes, wcomb, mask, stream);
-  else
-    l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, nullptr,
-                                   codes, wcomb, mask, stream);
+  if (desc->dtype == L4Q_DTYPE_BF16) {
+    l4q::MergeQuantOut<bf16_t> mq;
+    mq.codes = codes;
+    mq.wcomb = wcomb;
+    mq.mask = mask;
+    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
+  } else {
+    l4q::MergeQuantOut<float> mq;
+    mq.codes = codes;
+    mq.wcomb = wcomb;
+    mq.mask = mask;
+    l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, mq, stream);
+  }
   return launch_status();
 }
 

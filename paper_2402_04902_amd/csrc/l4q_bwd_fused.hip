@@ -1,0 +1,294 @@
+// Weight-gradient GEMM with the quantizer backward fused into its epilogue (bf16 mode).
+//
+//   dWq[o,i] = dYT[o,T] . XT[i,T]^T            (App. A.1, Eq. appen_wq)   -- stays in registers
+//   dscale[p,q] = sum_{j in group q} dWq[p,j] * f[p,j]                    (Eq. quant_lsq_s + case list)
+//   dzero [p,q] = sum_{j in group q} dWq[p,j] * (1 - m[p,j])              (Eq. appen_lsq_b)
+//   dB[p,k]     = gamma * sum_j (m * dWq)[p,j] A[k,j]                     (Eq. appen_l4q_b)
+//   dA[k,j]     = gamma * sum_p B[p,k] (m * dWq)[p,j]                     (Eq. appen_l4q_a)
+//
+// f = d(Wq)/d(scale) is what the merge+quantize pass of this same backward call left in the
+// workspace as binary16: code - w (|f| <= 1/2) where the element is in range, Q_N or Q_P
+// (|f| >= 1) where it is clipped; the straight-through mask m is read off its magnitude.
+// dWq itself is never written to memory.
+//
+// Accumulator layout (see l4q_gemm_core.h): a lane owns weight row p = 32 a + lane % 32 of its
+// wave's 128 rows and, per 32-column tile b, the 16 columns 8 (e/4) + 4 (lane/32) + e%4.
+//  * group sums over j are in-lane adds plus one exchange with lane ^ 32;
+//  * dB is a second MFMA straight from the registers: the masked gradient is the row operand and
+//    the 8 k-slots of a lane are loaded from A with the same column pattern;
+//  * dA contracts over p, the lane axis, so the masked tile goes through LDS once, transposed
+//    ([j][p], 2-byte writes, 16-byte fragment reads), and is multiplied with B^T.
+// Partial results per tile row / tile column go to the workspace and are summed by a second,
+// tiny kernel in a fixed order, so the result does not depend on scheduling.
+#include "l4q_device.h"
+#include "l4q_gemm_core.h"
+#include "l4q_kernels.h"
+
+namespace l4q {
+
+namespace {
+
+typedef gemm::Tile<256, 256, 32, 4> T;
+static_assert(T::WTM == 128 && T::WTN == 128 && T::TM == 4 && T::TN == 4, "epilogue is written for 128 x 128 wave tiles");
+
+constexpr int EP_ROWB = 256 * 2 + 16;             // bytes per [j] row of the transposed tile: 256 p + pad
+constexpr int EP_TILE = 256 * EP_ROWB;            // 135168
+constexpr int EP_SCRATCH = 2 * 128 * 2 * 4;       // per wave-row pair: 128 rows x (dscale, dzero)
+constexpr int EP_LDS = EP_TILE + EP_SCRATCH;
+constexpr int FUSED_LDS = EP_LDS > T::LDS_BYTES ? EP_LDS : T::LDS_BYTES;
+
+typedef gemm::bf16x8_t bf16x8_t;
+typedef gemm::f32x16_t f32x16_t;
+
+struct FusedArgs {
+  const bf16_t* dYT; int64_t ld_dyt;  // [o, Tpad]
+  const bf16_t* XT;  int64_t ld_xt;   // [i, Tpad]
+  int K;                              // Tpad, multiple of 32
+  int o, i, r, g;
+  const uint16_t* fgrad;              // [o, i] binary16
+  const bf16_t* A;                    // [r, i]
+  const bf16_t* BT; int64_t ld_bt;    // [r, ld_bt], zero beyond o
+  float* dscale; float* dzero;        // [o, i/g]
+  float* dA_part;                     // [tiles_m, r, i]
+  float* dB_part;                     // [2 * tiles_n, o, r]
+  int tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 v = {a, b, c, d};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+__global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[FUSED_LDS];
+#if defined(__HIP_DEVICE_COMPILE__)
+  int tile_m, tile_n;
+  gemm::tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * T::BM, n0 = tile_n * T::BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  gemm::Accum<T> acc;
+#pragma unroll
+  for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
+  gemm::mainloop<T>(p.dYT, p.ld_dyt, p.XT, p.ld_xt, p.o, p.i, p.K, m0, n0, lds, acc);
+  // LDS is free from here on (mainloop ends with a barrier after the last fragment read)
+
+  // ---- fragments of the LoRA factor A for the dB product: lane = rank index, 8 k-slots = the same
+  //      column pattern the accumulator registers 8h .. 8h+7 of a lane group have
+  bf16x8_t afrag[T::TN][2];
+#pragma unroll
+  for (int b = 0; b < T::TN; ++b) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int j = n0 + wn * 128 + b * 32 + 16 * h + 4 * lh;
+      uint2 lo = make_uint2(0, 0), hi = make_uint2(0, 0);
+      if (l32 < p.r && j < p.i) {  // i is a multiple of 32 here (g >= 32), so a 32-column tile is inside or outside as a whole
+        lo = *reinterpret_cast<const uint2*>(p.A + (int64_t)l32 * p.i + j);
+        hi = *reinterpret_cast<const uint2*>(p.A + (int64_t)l32 * p.i + j + 8);
+      }
+      afrag[b][h] = as_bf16x8(lo.x, lo.y, hi.x, hi.y);
+    }
+  }
+
+  const int G = p.i / p.g;
+  float keep_ds[T::TM], keep_db[T::TM];  // g == 256: this wave's half of the group, per row block
+  f32x16_t accB[T::TM];
+
+#pragma unroll
+  for (int a = 0; a < T::TM; ++a) {
+    const int row = m0 + wm * 128 + a * 32 + l32;  // the weight row this lane owns in block a
+    const bool row_ok = row < p.o;
+    float ds_b[T::TN], db_b[T::TN];
+    uint32_t pk[T::TN][8];
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) {
+      ds_b[b] = 0.f;
+      db_b[b] = 0.f;
+#pragma unroll
+      for (int eg = 0; eg < 4; ++eg) {
+        const int j = n0 + wn * 128 + b * 32 + 8 * eg + 4 * lh;
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        h4 fh = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
+        if (row_ok && j < p.i) fh = *reinterpret_cast<const h4*>(p.fgrad + (int64_t)row * p.i + j);
+        float xm[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x = acc.v[a][b][4 * eg + e];
+          const float f = (float)fh[e];
+          const bool clipped = fabsf(f) > 0.75f;
+          ds_b[b] = fmaf(x, f, ds_b[b]);
+          db_b[b] += clipped ? x : 0.f;
+          xm[e] = clipped ? 0.f : x;
+        }
+        pk[b][2 * eg] = pack_bf16x2(xm[0], xm[1]);
+        pk[b][2 * eg + 1] = pack_bf16x2(xm[2], xm[3]);
+      }
+    }
+
+    // ---- group sums: the other half of every 8-column run lives in lane ^ 32
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) {
+      ds_b[b] += __shfl_xor(ds_b[b], 32, 64);
+      db_b[b] += __shfl_xor(db_b[b], 32, 64);
+    }
+    const int col0 = n0 + wn * 128;
+    if (p.g == 32) {
+#pragma unroll
+      for (int b = 0; b < T::TN; ++b) {
+        const int q = (col0 + b * 32) / 32;
+        if (lh == 0 && row_ok && q < G) {
+          p.dscale[(int64_t)row * G + q] = ds_b[b];
+          p.dzero[(int64_t)row * G + q] = db_b[b];
+        }
+      }
+    } else if (p.g == 64) {
+#pragma unroll
+      for (int b = 0; b < T::TN; b += 2) {
+        const int q = (col0 + b * 32) / 64;
+        if (lh == 0 && row_ok && q < G) {
+          p.dscale[(int64_t)row * G + q] = ds_b[b] + ds_b[b + 1];
+          p.dzero[(int64_t)row * G + q] = db_b[b] + db_b[b + 1];
+        }
+      }
+    } else {
+      const float ds = (ds_b[0] + ds_b[1]) + (ds_b[2] + ds_b[3]);
+      const float db = (db_b[0] + db_b[1]) + (db_b[2] + db_b[3]);
+      keep_ds[a] = ds;
+      keep_db[a] = db;
+      if (p.g == 128) {
+        const int q = col0 / 128;
+        if (lh == 0 && row_ok && q < G) {
+          p.dscale[(int64_t)row * G + q] = ds;
+          p.dzero[(int64_t)row * G + q] = db;
+        }
+      } else if (wn == 1 && lh == 0) {  // g == 256: hand the right half to the left wave
+        float* sc = reinterpret_cast<float*>(lds + EP_TILE) + (wm * 128 + a * 32 + l32) * 2;
+        sc[0] = ds;
+        sc[1] = db;
+      }
+    }
+
+    // ---- dB: (masked gradient) x A^T on the matrix core, 2 k-steps of 16 columns per 32-column tile
+    f32x16_t cb;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) cb[e] = 0.f;
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const bf16x8_t gfrag = as_bf16x8(pk[b][4 * h], pk[b][4 * h + 1], pk[b][4 * h + 2], pk[b][4 * h + 3]);
+        cb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gfrag, afrag[b][h], cb, 0, 0, 0);
+      }
+    }
+    accB[a] = cb;
+
+    // ---- masked gradient, transposed, to LDS: element (p, j) at [j][p]
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int jl = wn * 128 + b * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+        const int pl = wm * 128 + a * 32 + l32;
+        const uint32_t w = pk[b][e >> 1];
+        *reinterpret_cast<uint16_t*>(lds + jl * EP_ROWB + pl * 2) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
+      }
+    }
+  }
+
+  // ---- dB partials: register e of lane l is (row 8 (e/4) + 4 (l/32) + e%4 of the block, rank l % 32)
+  {
+    float* dst = p.dB_part + (int64_t)(tile_n * 2 + wn) * p.o * p.r;
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * 128 + a * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+        if (l32 < p.r && row < p.o) dst[(int64_t)row * p.r + l32] = accB[a][e];
+      }
+    }
+  }
+
+  __syncthreads();
+
+  if (p.g == 256 && wn == 0 && lh == 0) {
+    const int q = n0 / 256;
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a) {
+      const int row = m0 + wm * 128 + a * 32 + l32;
+      const float* sc = reinterpret_cast<const float*>(lds + EP_TILE) + (wm * 128 + a * 32 + l32) * 2;
+      if (row < p.o && q < G) {
+        p.dscale[(int64_t)row * G + q] = keep_ds[a] + sc[0];
+        p.dzero[(int64_t)row * G + q] = keep_db[a] + sc[1];
+      }
+    }
+  }
+
+  // ---- dA: B^T x (masked gradient); this wave takes the 64 columns 64 wave .. 64 wave + 63, all 256 rows
+  f32x16_t ca[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) ca[nb][e] = 0.f;
+#pragma unroll 4
+  for (int ks = 0; ks < 16; ++ks) {
+    const int64_t prow = (int64_t)m0 + ks * 16 + lh * 8;
+    uint4 bt = make_uint4(0, 0, 0, 0);
+    if (l32 < p.r && prow < p.ld_bt) bt = *reinterpret_cast<const uint4*>(p.BT + (int64_t)l32 * p.ld_bt + prow);
+    const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bt);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const int jl = wave * 64 + nb * 32 + l32;
+      const bf16x8_t gfrag = *reinterpret_cast<const bf16x8_t*>(lds + jl * EP_ROWB + ks * 32 + lh * 16);
+      ca[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, gfrag, ca[nb], 0, 0, 0);
+    }
+  }
+  {
+    float* dst = p.dA_part + (int64_t)tile_m * p.r * p.i;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const int j = n0 + wave * 64 + nb * 32 + l32;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int k = 8 * (e >> 2) + 4 * lh + (e & 3);
+        if (k < p.r && j < p.i) dst[(int64_t)k * p.i + j] = ca[nb][e];
+      }
+    }
+  }
+#endif
+}
+
+}  // namespace
+
+bool dw_fused_supported(const LayerDims& d, int64_t Tpad) {
+  const bool g_ok = d.g == 32 || d.g == 64 || d.g == 128 || d.g == 256;
+  return g_ok && d.r <= 32 && Tpad % T::BK == 0 && d.o * Tpad * 2 < (1ll << 30) && d.i * Tpad * 2 < (1ll << 30);
+}
+
+void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n) {
+  *tiles_m = (int)((d.o + T::BM - 1) / T::BM);
+  *tiles_n = (int)((d.i + T::BN - 1) / T::BN);
+}
+
+void launch_dw_fused(const LayerDims& d, const bf16_t* dYT, const bf16_t* XT, int64_t Tpad, const uint16_t* fgrad,
+                     const bf16_t* A, const bf16_t* BT, int64_t ld_bt, float* dscale, float* dzero, float* dA_part,
+                     float* dB_part, hipStream_t stream) {
+  FusedArgs p;
+  p.dYT = dYT; p.ld_dyt = Tpad;
+  p.XT = XT; p.ld_xt = Tpad;
+  p.K = (int)Tpad;
+  p.o = (int)d.o; p.i = (int)d.i; p.r = d.r; p.g = d.g;
+  p.fgrad = fgrad; p.A = A; p.BT = BT; p.ld_bt = ld_bt;
+  p.dscale = dscale; p.dzero = dzero; p.dA_part = dA_part; p.dB_part = dB_part;
+  dw_fused_tiles(d, &p.tiles_m, &p.tiles_n);
+  hipLaunchKernelGGL(dw_fused_kernel, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(T::NT), 0, stream, p);
+}
+
+}  // namespace l4q

@@ -19,11 +19,25 @@ struct LayerDims {
 };
 
 // ---- merge + quantize pass (Eqs. l4q_Wcombine, l4q_Wquant, l4q_Wdequant) ----
-// Any of the outputs may be null.  wq has the storage type T and leading dimension i.
+// Every output is optional (null = not written).
+template <class T>
+struct MergeQuantOut {
+  T* wq = nullptr;           // dequantized Wq [o, ld_wq], storage type
+  int64_t ld_wq = 0;
+  bf16_t* wqT = nullptr;     // Wq^T [i, ld_wqT] bf16; columns o..ld_wqT-1 are written as zeros (bf16 mode only)
+  int64_t ld_wqT = 0;        // multiple of 8
+  uint16_t* fgrad = nullptr; // [o,i] binary16: d(Wq)/d(scale) = code - w in range, code (= Q_N or Q_P) when clipped;
+                             // |value| <= 1/2 exactly when the element is in range
+  int8_t* codes = nullptr;   // [o,i]
+  float* wcomb = nullptr;    // [o,i] binary32 merged weight
+  uint8_t* mask = nullptr;   // [o,i] 1 where Q_N <= w <= Q_P
+};
 template <class T>
 void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B, const float* scale,
-                        const float* zero, T* wq, int8_t* codes, float* wcomb, uint8_t* mask,
-                        hipStream_t stream);
+                        const float* zero, const MergeQuantOut<T>& out, hipStream_t stream);
+
+// B^T [r, ld] from the LoRA factor B [o, r]; columns o..ld-1 zero
+void launch_transpose_lora_b(const bf16_t* B, int64_t o, int r, bf16_t* BT, int64_t ld, hipStream_t stream);
 
 // ---- per-group min/max initialisation (App. B, Eq. quant_inits) ----
 template <class T>
@@ -56,5 +70,19 @@ void launch_quant_grads(const LayerDims& d, const T* W0, const T* A, const T* B,
 constexpr int kDaRowBlock = 128;
 template <class T>
 void launch_dA(const LayerDims& d, const T* B, const float* dWp, float* partial, float* dA, hipStream_t stream);
+
+// out[e] = scale * sum_b partial[b * n + e], b ascending (fixed summation order)
+void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, float scale, float* out,
+                            hipStream_t stream);
+
+// ---- weight-gradient GEMM with fused quantizer backward (bf16 mode) ----
+// dYT [o, Tpad], XT [i, Tpad] zero-padded along T; fgrad [o, i] binary16 from launch_merge_quant;
+// BT [r, ld_bt] from launch_transpose_lora_b.  Writes dscale, dzero [o, G] and the partial sums
+// dA_part [tiles_m, r, i], dB_part [2 * tiles_n, o, r] (no gamma applied yet).
+bool dw_fused_supported(const LayerDims& d, int64_t Tpad);
+void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n);
+void launch_dw_fused(const LayerDims& d, const bf16_t* dYT, const bf16_t* XT, int64_t Tpad, const uint16_t* fgrad,
+                     const bf16_t* A, const bf16_t* BT, int64_t ld_bt, float* dscale, float* dzero, float* dA_part,
+                     float* dB_part, hipStream_t stream);
 
 }  // namespace l4q

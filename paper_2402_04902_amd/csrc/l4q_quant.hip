@@ -1,9 +1,9 @@
 // Merge + quantize pass, integer-code export, min/max initialisation, 16-bit transpose.
 //
-// merge_quant_kernel is the HBM-streaming prologue of both passes: it reads W0 once with
-// coalesced 8/16-byte loads, adds the rank-r update from registers/L2, applies the group-wise
-// quantizer and writes whichever outputs were asked for (dequantized Wq, int8 codes, the
-// binary32 merged weight, the straight-through mask).
+// merge_quant_tile_kernel is the HBM-streaming prologue of both passes: it reads W0 once with
+// coalesced 8/16-byte loads, adds the rank-r update from registers, applies the group-wise
+// quantizer and writes whichever outputs were asked for (dequantized Wq, its transpose, the
+// per-element d(Wq)/d(scale) factor, int8 codes, the binary32 merged weight, the mask).
 #include "l4q_device.h"
 #include "l4q_kernels.h"
 
@@ -12,43 +12,136 @@ namespace l4q {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kColsPerThread = 4;
-constexpr int kColsPerBlock = kThreads * kColsPerThread;  // 1024
-constexpr int kRowsPerBlock = 16;
+
+// ------------------------------------------------------------------ merge + quantize, tiled
+// Block tile: MQ_ROWS weight rows x 256 columns.  A thread owns 4 consecutive columns (one 8- or
+// 16-byte load of W0 per row, 512 B / 1 KiB contiguous per wave) and its wave walks 16 rows, so the
+// 16 x 4 slice of A it needs stays in registers and B[p, :] is wave-uniform.  The rank loop runs
+// in chunks of 16 with the running sums of all 16 rows kept in registers, which preserves the
+// k-ascending summation order for any rank.
+constexpr int MQ_ROWS = 64;
+constexpr int MQ_COLS = 256;
+constexpr int MQ_RPW = MQ_ROWS / 4;  // rows per wave
+constexpr int MQ_KC = 16;            // rank chunk
+constexpr int MQ_TROW = 144;         // bytes per row of the transposed LDS tile: 64 bf16 + 16 B pad
 
 template <class T>
-__global__ __launch_bounds__(kThreads) void merge_quant_kernel(LayerDims d, const T* __restrict__ W0,
-                                                                const T* __restrict__ A, const T* __restrict__ B,
-                                                                const float* __restrict__ scale,
-                                                                const float* __restrict__ zero, T* __restrict__ wq,
-                                                                int8_t* __restrict__ codes, float* __restrict__ wcomb,
-                                                                uint8_t* __restrict__ mask) {
-  const int64_t j0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * kColsPerThread;
-  if (j0 >= d.i) return;
-  const int64_t p0 = (int64_t)blockIdx.y * kRowsPerBlock;
-  const int64_t p1 = p0 + kRowsPerBlock < d.o ? p0 + kRowsPerBlock : d.o;
+__global__ __launch_bounds__(kThreads) void merge_quant_tile_kernel(LayerDims d, const T* __restrict__ W0,
+                                                                     const T* __restrict__ A,
+                                                                     const T* __restrict__ B,
+                                                                     const float* __restrict__ scale,
+                                                                     const float* __restrict__ zero,
+                                                                     MergeQuantOut<T> out) {
+  __shared__ __attribute__((aligned(16))) unsigned char tile[MQ_COLS * MQ_TROW];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t jblk = (int64_t)blockIdx.x * MQ_COLS;
+  const int64_t j0 = jblk + lane * 4;
+  const bool col_ok = j0 < d.i;
+  const int64_t pw = (int64_t)blockIdx.y * MQ_ROWS + wave * MQ_RPW;  // first row of this wave
   const int64_t G = d.i / d.g;
   const int64_t q = j0 / d.g;  // 4 consecutive columns lie in one group because g % 4 == 0
-  for (int64_t p = p0; p < p1; ++p) {
-    float wc[4];
-    merged_weight4<T>(W0 + p * d.i, A, B + p * d.r, d.i, d.r, j0, d.gamma, wc);
-    const float s = scale[p * G + q];
-    const float b = zero[p * G + q];
-    float wqv[4];
-    uint32_t cpack = 0, mpack = 0;
+
+  float acc[MQ_RPW][4];
+#pragma unroll
+  for (int rr = 0; rr < MQ_RPW; ++rr)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
+
+  if (col_ok) {
+    for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
+      float a[MQ_KC][4];
+#pragma unroll
+      for (int k = 0; k < MQ_KC; ++k) {
+        if (k0 + k < d.r) load4(A + (int64_t)(k0 + k) * d.i + j0, a[k]);
+        else a[k][0] = a[k][1] = a[k][2] = a[k][3] = 0.f;
+      }
+#pragma unroll
+      for (int rr = 0; rr < MQ_RPW; ++rr) {
+        const int64_t p = pw + rr;
+        if (p < d.o) {
+          const T* brow = B + p * d.r + k0;
+#pragma unroll
+          for (int k = 0; k < MQ_KC; ++k) {
+            if (k0 + k < d.r) {
+              const float bk = load1(brow + k);
+#pragma unroll
+              for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[k][c]);
+            }
+          }
+        }
+      }
+    }
+  }
+
+  uint32_t tpack[4][MQ_RPW / 2];  // Wq of (column c, row pair) as two bf16, for the transposed output
+#pragma unroll
+  for (int rr = 0; rr < MQ_RPW; ++rr) {
+    const int64_t p = pw + rr;
+    float wqv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (col_ok && p < d.o) {
+      float w0[4], wc[4], fg[4];
+      load4(W0 + p * d.i + j0, w0);
+      const float s = scale[p * G + q];
+      const float b = zero[p * G + q];
+      uint32_t cpack = 0, mpack = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        wc[c] = w0[c] + d.gamma * acc[rr][c];
+        const QuantOut qo = quantize_elem(wc[c], s, b, d.qn, d.qp);
+        wqv[c] = dequant_elem(qo.code, s, b);
+        fg[c] = qo.in_range ? qo.code - qo.w : qo.code;
+        cpack |= ((uint32_t)(uint8_t)(int8_t)(int)qo.code) << (8 * c);
+        mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
+      }
+      const int64_t off = p * d.i + j0;
+      if (out.wq) store4(out.wq + p * out.ld_wq + j0, wqv);
+      if (out.codes) *reinterpret_cast<uint32_t*>(out.codes + off) = cpack;
+      if (out.mask) *reinterpret_cast<uint32_t*>(out.mask + off) = mpack;
+      if (out.wcomb) store4(out.wcomb + off, wc);
+      if (out.fgrad) {
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        h4 h = {(_Float16)fg[0], (_Float16)fg[1], (_Float16)fg[2], (_Float16)fg[3]};
+        *reinterpret_cast<h4*>(out.fgrad + off) = h;
+      }
+    }
+    if (out.wqT) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t h = f32_to_bf16(wqv[c]);
+        if (rr & 1) tpack[c][rr >> 1] |= h << 16;
+        else tpack[c][rr >> 1] = h;
+      }
+    }
+  }
+
+  if (out.wqT) {  // uniform: transpose the 64 x 256 tile through LDS, rows past o are zeros
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const QuantOut qo = quantize_elem(wc[c], s, b, d.qn, d.qp);
-      wqv[c] = dequant_elem(qo.code, s, b);
-      cpack |= ((uint32_t)(uint8_t)(int8_t)(int)qo.code) << (8 * c);
-      mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
+      unsigned char* dst = tile + (lane * 4 + c) * MQ_TROW + wave * (MQ_RPW * 2);
+      *reinterpret_cast<uint4*>(dst) = make_uint4(tpack[c][0], tpack[c][1], tpack[c][2], tpack[c][3]);
+      *reinterpret_cast<uint4*>(dst + 16) = make_uint4(tpack[c][4], tpack[c][5], tpack[c][6], tpack[c][7]);
     }
-    const int64_t off = p * d.i + j0;
-    if (wq) store4(wq + off, wqv);
-    if (codes) *reinterpret_cast<uint32_t*>(codes + off) = cpack;
-    if (mask) *reinterpret_cast<uint32_t*>(mask + off) = mpack;
-    if (wcomb) store4(wcomb + off, wc);
+    __syncthreads();
+    const int64_t pblk = (int64_t)blockIdx.y * MQ_ROWS;
+#pragma unroll
+    for (int it = 0; it < MQ_COLS * 8 / kThreads; ++it) {
+      const int idx = threadIdx.x + it * kThreads;
+      const int jr = idx >> 3, ch = idx & 7;
+      const int64_t j = jblk + jr, p = pblk + ch * 8;
+      if (j < d.i && p < out.ld_wqT)
+        *reinterpret_cast<uint4*>(out.wqT + j * out.ld_wqT + p) =
+            *reinterpret_cast<const uint4*>(tile + jr * MQ_TROW + ch * 16);
+    }
   }
+}
+
+// B^T [r, ld] from B [o, r] (bf16), columns o..ld-1 zero
+__global__ __launch_bounds__(256) void transpose_lora_b_kernel(const bf16_t* __restrict__ B, int64_t o, int r,
+                                                                bf16_t* __restrict__ BT, int64_t ld) {
+  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (p >= ld) return;
+  for (int k = 0; k < r; ++k) BT[(int64_t)k * ld + p] = p < o ? B[p * r + k] : (bf16_t)0;
 }
 
 // One wave per weight row; each lane owns 4 consecutive columns per 256-column step.
@@ -147,11 +240,15 @@ __global__ __launch_bounds__(256) void transpose_u16_kernel(const uint16_t* __re
 
 template <class T>
 void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B, const float* scale,
-                        const float* zero, T* wq, int8_t* codes, float* wcomb, uint8_t* mask,
-                        hipStream_t stream) {
-  dim3 grid((unsigned)((d.i + kColsPerBlock - 1) / kColsPerBlock), (unsigned)((d.o + kRowsPerBlock - 1) / kRowsPerBlock));
-  hipLaunchKernelGGL(merge_quant_kernel<T>, grid, dim3(kThreads), 0, stream, d, W0, A, B, scale, zero, wq, codes,
-                     wcomb, mask);
+                        const float* zero, const MergeQuantOut<T>& out, hipStream_t stream) {
+  const int64_t rows = out.wqT && out.ld_wqT > d.o ? out.ld_wqT : d.o;
+  dim3 grid((unsigned)((d.i + MQ_COLS - 1) / MQ_COLS), (unsigned)((rows + MQ_ROWS - 1) / MQ_ROWS));
+  hipLaunchKernelGGL(merge_quant_tile_kernel<T>, grid, dim3(kThreads), 0, stream, d, W0, A, B, scale, zero, out);
+}
+
+void launch_transpose_lora_b(const bf16_t* B, int64_t o, int r, bf16_t* BT, int64_t ld, hipStream_t stream) {
+  hipLaunchKernelGGL(transpose_lora_b_kernel, dim3((unsigned)((ld + 255) / 256)), dim3(256), 0, stream, B, o, r, BT,
+                     ld);
 }
 
 template <class T>
@@ -169,10 +266,9 @@ void launch_transpose_u16(const uint16_t* in, int64_t rows, int64_t cols, uint16
 }
 
 template void launch_merge_quant<float>(const LayerDims&, const float*, const float*, const float*, const float*,
-                                        const float*, float*, int8_t*, float*, uint8_t*, hipStream_t);
+                                        const float*, const MergeQuantOut<float>&, hipStream_t);
 template void launch_merge_quant<bf16_t>(const LayerDims&, const bf16_t*, const bf16_t*, const bf16_t*,
-                                         const float*, const float*, bf16_t*, int8_t*, float*, uint8_t*,
-                                         hipStream_t);
+                                         const float*, const float*, const MergeQuantOut<bf16_t>&, hipStream_t);
 template void launch_init_qparams<float>(const LayerDims&, const float*, const float*, const float*, int, float*,
                                          float*, hipStream_t);
 template void launch_init_qparams<bf16_t>(const LayerDims&, const bf16_t*, const bf16_t*, const bf16_t*, int,

@@ -185,6 +185,12 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   out[e] = scale * acc;
 }
 
+void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, float scale, float* out,
+                            hipStream_t stream) {
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, partial,
+                     nblocks, n, scale, out);
+}
+
 void launch_sgemm(const float* A, int64_t a_rs, int64_t a_cs, const float* B, int64_t b_rs, int64_t b_cs,
                   float* C, int64_t ldc, int64_t M, int64_t N, int64_t K, float scale, hipStream_t stream) {
   dim3 grid((unsigned)((N + SG_BN - 1) / SG_BN), (unsigned)((M + SG_BM - 1) / SG_BM));

@@ -79,6 +79,20 @@ def test_bf16_small_shapes(T, i, o, r, bits, g, shrink):
         assert rep["clipped"] > 0
 
 
+@pytest.mark.parametrize("T,i,o,r,bits,g", [(300, 640, 264, 16, 4, 128), (513, 768, 1032, 8, 4, 64)])
+def test_bf16_unfused_backward_flag(T, i, o, r, bits, g):
+    """The unfused backward (dWq through the workspace) must agree with the oracle as well."""
+    from paper_2402_04902_amd import binding
+    spec = LayerSpec(f"bf16_unfused_{T}x{i}x{o}", T, i, o, r, 2.0 * r, bits, g, DTYPE_BF16)
+    run_case(spec, seed=T + 1, shrink=0.8, flags=binding.FLAG_UNFUSED_BACKWARD, discrete=False)
+
+
+def test_bf16_rank_above_fused_limit():
+    """Rank 40 is beyond the fused epilogue's 32: the library takes the unfused kernels by itself."""
+    spec = LayerSpec("bf16_rank40", 200, 512, 264, 40, 80.0, 4, 128, DTYPE_BF16)
+    run_case(spec, seed=40, shrink=0.8)
+
+
 def test_bf16_zero_B_is_plain_qat_and_kills_dA():
     """The paper initialises B = 0: the layer is then plain group-wise QAT of W0 and dA vanishes."""
     def zero_b(arrs):
