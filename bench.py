@@ -21,6 +21,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+# HBM-side bytes per GEMM launch (mean over the 4 plain + 2 fused launches of a step) from the
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/l4q_layer__llama7b_mlp_T4096.md
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = (4 * (565e6 + 62e6) + 2 * (717e6 + 38e6)) / 6
 
 
 def cpu_baseline(specs, host_inputs):
@@ -57,6 +60,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=4096, help=argparse.SUPPRESS)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -87,6 +92,12 @@ def main() -> int:
         for layer in reversed(layers):
             layer.backward()
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -120,7 +131,7 @@ def main() -> int:
                    "workspace_bytes_bwd": max(l.bwd_bytes for l in layers)},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel", "achieved": gemm_tflops,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": None, "launches": gemm_launches,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "launches": gemm_launches,
                      "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
                      "gemm_share_of_step": gemm_ms / args.steps / ms_per_step},
     }

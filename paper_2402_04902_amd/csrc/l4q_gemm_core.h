@@ -33,7 +33,7 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int NUM_XCD = 8;
-constexpr int GROUP_M = 8;
+constexpr int GROUP_M = 4;
 // Operands are below 1 GiB.  A row outside the matrix gets OOB_OFFSET; a stage past the end of K adds
 // PAST_END_OFFSET.  Either one, or both together, lands beyond num_records without wrapping 32 bits.
 constexpr unsigned OOB_OFFSET = 0x80000000u;

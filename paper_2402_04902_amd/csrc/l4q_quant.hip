@@ -48,27 +48,31 @@ __global__ __launch_bounds__(kThreads) void merge_quant_tile_kernel(LayerDims d,
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
 
-  if (col_ok) {
+  // no lane leaves this loop early: the rank loop reads B through other lanes' registers
+  {
     for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
       float a[MQ_KC][4];
 #pragma unroll
       for (int k = 0; k < MQ_KC; ++k) {
-        if (k0 + k < d.r) load4(A + (int64_t)(k0 + k) * d.i + j0, a[k]);
+        if (col_ok && k0 + k < d.r) load4(A + (int64_t)(k0 + k) * d.i + j0, a[k]);
         else a[k][0] = a[k][1] = a[k][2] = a[k][3] = 0.f;
       }
+      // B[p, k0 .. k0+15] of each of the wave's rows: lane k fetches element k once, the rank loop
+      // then reads it from that lane (a scalar operand), so the wave issues 16 loads, not 256
+      float brow[MQ_RPW];
 #pragma unroll
       for (int rr = 0; rr < MQ_RPW; ++rr) {
         const int64_t p = pw + rr;
-        if (p < d.o) {
-          const T* brow = B + p * d.r + k0;
+        brow[rr] = (p < d.o && lane < MQ_KC && k0 + lane < d.r) ? load1(B + p * d.r + k0 + lane) : 0.f;
+      }
 #pragma unroll
-          for (int k = 0; k < MQ_KC; ++k) {
-            if (k0 + k < d.r) {
-              const float bk = load1(brow + k);
+      for (int rr = 0; rr < MQ_RPW; ++rr) {
 #pragma unroll
-              for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[k][c]);
-            }
-          }
+        for (int k = 0; k < MQ_KC; ++k) {
+          // ranks past r contribute b = 0 and a = 0: the running sum is unchanged bit for bit
+          const float bk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(brow[rr]), k));
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[k][c]);
         }
       }
     }
