@@ -14,33 +14,58 @@ namespace {
 constexpr int kThreads = 256;
 
 // ------------------------------------------------------------------ merge + quantize, tiled
-// Block tile: MQ_ROWS weight rows x 256 columns.  A thread owns 4 consecutive columns (one 8- or
-// 16-byte load of W0 per row, 512 B / 1 KiB contiguous per wave) and its wave walks 16 rows, so the
-// 16 x 4 slice of A it needs stays in registers and B[p, :] is wave-uniform.  The rank loop runs
-// in chunks of 16 with the running sums of all 16 rows kept in registers, which preserves the
-// k-ascending summation order for any rank.
+// Block tile: MQ_ROWS weight rows x 256 columns, 8 waves.  A thread owns 4 consecutive columns (one
+// 8- or 16-byte load of W0 per row, 512 B / 1 KiB contiguous per wave) and its wave walks MQ_RPW
+// rows.  The rank loop runs k-outer in chunks of 16: A[k, 4 columns] is unpacked once and used for
+// all rows, B[p, k] is fetched once per row by lane k and read back as a scalar, and the running
+// sums of all rows stay in registers, which keeps the k-ascending summation order for any rank.
+// Every load is unconditional (clamped address, value discarded where out of range) so that the
+// W0 / scale / zero loads of all rows are in flight while the rank loop runs.
 constexpr int MQ_ROWS = 64;
 constexpr int MQ_COLS = 256;
-constexpr int MQ_RPW = MQ_ROWS / 4;  // rows per wave
-constexpr int MQ_KC = 16;            // rank chunk
-constexpr int MQ_TROW = 144;         // bytes per row of the transposed LDS tile: 64 bf16 + 16 B pad
+constexpr int MQ_THREADS = 512;
+constexpr int MQ_RPW = MQ_ROWS / (MQ_THREADS / 64);  // rows per wave = 8
+constexpr int MQ_KC = 16;                            // rank chunk
+constexpr int MQ_TROW = 144;                         // bytes per row of the transposed LDS tile: 64 bf16 + 16 B pad
+
+template <class T> struct Raw4;
+template <> struct Raw4<float> { typedef float4 type; };
+template <> struct Raw4<bf16_t> { typedef uint2 type; };
+__device__ __forceinline__ void unpack4(const float4& r, float (&v)[4]) { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
+__device__ __forceinline__ void unpack4(const uint2& r, float (&v)[4]) {
+  v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xFFFF0000u);
+}
 
 template <class T>
-__global__ __launch_bounds__(kThreads) void merge_quant_tile_kernel(LayerDims d, const T* __restrict__ W0,
-                                                                     const T* __restrict__ A,
-                                                                     const T* __restrict__ B,
-                                                                     const float* __restrict__ scale,
-                                                                     const float* __restrict__ zero,
-                                                                     MergeQuantOut<T> out) {
+__global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims d, const T* __restrict__ W0,
+                                                                       const T* __restrict__ A,
+                                                                       const T* __restrict__ B,
+                                                                       const float* __restrict__ scale,
+                                                                       const float* __restrict__ zero,
+                                                                       MergeQuantOut<T> out) {
+  typedef typename Raw4<T>::type raw4_t;
   __shared__ __attribute__((aligned(16))) unsigned char tile[MQ_COLS * MQ_TROW];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t jblk = (int64_t)blockIdx.x * MQ_COLS;
   const int64_t j0 = jblk + lane * 4;
   const bool col_ok = j0 < d.i;
-  const int64_t pw = (int64_t)blockIdx.y * MQ_ROWS + wave * MQ_RPW;  // first row of this wave
+  const int64_t jc = col_ok ? j0 : 0;                                  // clamped column for loads
+  const int64_t pw = (int64_t)blockIdx.y * MQ_ROWS + wave * MQ_RPW;    // first row of this wave
   const int64_t G = d.i / d.g;
-  const int64_t q = j0 / d.g;  // 4 consecutive columns lie in one group because g % 4 == 0
+  const int64_t q = jc / d.g;  // 4 consecutive columns lie in one group because g % 4 == 0
+
+  // row data, requested up front
+  raw4_t w0raw[MQ_RPW];
+  float sv[MQ_RPW], bv[MQ_RPW];
+#pragma unroll
+  for (int rr = 0; rr < MQ_RPW; ++rr) {
+    const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
+    w0raw[rr] = *reinterpret_cast<const raw4_t*>(W0 + pc * d.i + jc);
+    sv[rr] = scale[pc * G + q];
+    bv[rr] = zero[pc * G + q];
+  }
 
   float acc[MQ_RPW][4];
 #pragma unroll
@@ -48,32 +73,32 @@ __global__ __launch_bounds__(kThreads) void merge_quant_tile_kernel(LayerDims d,
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
 
-  // no lane leaves this loop early: the rank loop reads B through other lanes' registers
-  {
-    for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
-      float a[MQ_KC][4];
+  for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
+    raw4_t araw[MQ_KC];
 #pragma unroll
-      for (int k = 0; k < MQ_KC; ++k) {
-        if (col_ok && k0 + k < d.r) load4(A + (int64_t)(k0 + k) * d.i + j0, a[k]);
-        else a[k][0] = a[k][1] = a[k][2] = a[k][3] = 0.f;
-      }
-      // B[p, k0 .. k0+15] of each of the wave's rows: lane k fetches element k once, the rank loop
-      // then reads it from that lane (a scalar operand), so the wave issues 16 loads, not 256
-      float brow[MQ_RPW];
+    for (int k = 0; k < MQ_KC; ++k) {
+      const int kc = k0 + k < d.r ? k0 + k : d.r - 1;
+      araw[k] = *reinterpret_cast<const raw4_t*>(A + (int64_t)kc * d.i + jc);
+    }
+    // B[p, k0 + lane] for lanes 0..15 of each row; zero past the rank so those steps add nothing
+    float brow[MQ_RPW];
+#pragma unroll
+    for (int rr = 0; rr < MQ_RPW; ++rr) {
+      const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
+      const int kl = k0 + (lane & (MQ_KC - 1));
+      const float v = load1(B + pc * d.r + (kl < d.r ? kl : d.r - 1));
+      brow[rr] = kl < d.r ? v : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < MQ_KC; ++k) {
+      float a[4];
+      unpack4(araw[k], a);
 #pragma unroll
       for (int rr = 0; rr < MQ_RPW; ++rr) {
-        const int64_t p = pw + rr;
-        brow[rr] = (p < d.o && lane < MQ_KC && k0 + lane < d.r) ? load1(B + p * d.r + k0 + lane) : 0.f;
-      }
+        // b = 0 past the rank: acc + 0 * a and fma(0, a, acc) leave the running sum unchanged bit for bit
+        const float bk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(brow[rr]), k));
 #pragma unroll
-      for (int rr = 0; rr < MQ_RPW; ++rr) {
-#pragma unroll
-        for (int k = 0; k < MQ_KC; ++k) {
-          // ranks past r contribute b = 0 and a = 0: the running sum is unchanged bit for bit
-          const float bk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(brow[rr]), k));
-#pragma unroll
-          for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[k][c]);
-        }
+        for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[c]);
       }
     }
   }
@@ -82,22 +107,21 @@ __global__ __launch_bounds__(kThreads) void merge_quant_tile_kernel(LayerDims d,
 #pragma unroll
   for (int rr = 0; rr < MQ_RPW; ++rr) {
     const int64_t p = pw + rr;
-    float wqv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (col_ok && p < d.o) {
-      float w0[4], wc[4], fg[4];
-      load4(W0 + p * d.i + j0, w0);
-      const float s = scale[p * G + q];
-      const float b = zero[p * G + q];
-      uint32_t cpack = 0, mpack = 0;
+    const bool ok = col_ok && p < d.o;
+    float w0[4], wc[4], fg[4], wqv[4];
+    unpack4(w0raw[rr], w0);
+    const float s = sv[rr], b = bv[rr];
+    uint32_t cpack = 0, mpack = 0;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        wc[c] = w0[c] + d.gamma * acc[rr][c];
-        const QuantOut qo = quantize_elem(wc[c], s, b, d.qn, d.qp);
-        wqv[c] = dequant_elem(qo.code, s, b);
-        fg[c] = qo.in_range ? qo.code - qo.w : qo.code;
-        cpack |= ((uint32_t)(uint8_t)(int8_t)(int)qo.code) << (8 * c);
-        mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
-      }
+    for (int c = 0; c < 4; ++c) {
+      wc[c] = w0[c] + d.gamma * acc[rr][c];
+      const QuantOut qo = quantize_elem(wc[c], s, b, d.qn, d.qp);
+      wqv[c] = ok ? dequant_elem(qo.code, s, b) : 0.f;
+      fg[c] = qo.in_range ? qo.code - qo.w : qo.code;
+      cpack |= ((uint32_t)(uint8_t)(int8_t)(int)qo.code) << (8 * c);
+      mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
+    }
+    if (ok) {
       const int64_t off = p * d.i + j0;
       if (out.wq) store4(out.wq + p * out.ld_wq + j0, wqv);
       if (out.codes) *reinterpret_cast<uint32_t*>(out.codes + off) = cpack;
@@ -109,13 +133,11 @@ __global__ __launch_bounds__(kThreads) void merge_quant_tile_kernel(LayerDims d,
         *reinterpret_cast<h4*>(out.fgrad + off) = h;
       }
     }
-    if (out.wqT) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const uint32_t h = f32_to_bf16(wqv[c]);
-        if (rr & 1) tpack[c][rr >> 1] |= h << 16;
-        else tpack[c][rr >> 1] = h;
-      }
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t h = f32_to_bf16(wqv[c]);
+      if (rr & 1) tpack[c][rr >> 1] |= h << 16;
+      else tpack[c][rr >> 1] = h;
     }
   }
 
@@ -124,13 +146,12 @@ __global__ __launch_bounds__(kThreads) void merge_quant_tile_kernel(LayerDims d,
     for (int c = 0; c < 4; ++c) {
       unsigned char* dst = tile + (lane * 4 + c) * MQ_TROW + wave * (MQ_RPW * 2);
       *reinterpret_cast<uint4*>(dst) = make_uint4(tpack[c][0], tpack[c][1], tpack[c][2], tpack[c][3]);
-      *reinterpret_cast<uint4*>(dst + 16) = make_uint4(tpack[c][4], tpack[c][5], tpack[c][6], tpack[c][7]);
     }
     __syncthreads();
     const int64_t pblk = (int64_t)blockIdx.y * MQ_ROWS;
 #pragma unroll
-    for (int it = 0; it < MQ_COLS * 8 / kThreads; ++it) {
-      const int idx = threadIdx.x + it * kThreads;
+    for (int it = 0; it < MQ_COLS * 8 / MQ_THREADS; ++it) {
+      const int idx = threadIdx.x + it * MQ_THREADS;
       const int jr = idx >> 3, ch = idx & 7;
       const int64_t j = jblk + jr, p = pblk + ch * 8;
       if (j < d.i && p < out.ld_wqT)
@@ -247,7 +268,7 @@ void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B,
                         const float* zero, const MergeQuantOut<T>& out, hipStream_t stream) {
   const int64_t rows = out.wqT && out.ld_wqT > d.o ? out.ld_wqT : d.o;
   dim3 grid((unsigned)((d.i + MQ_COLS - 1) / MQ_COLS), (unsigned)((rows + MQ_ROWS - 1) / MQ_ROWS));
-  hipLaunchKernelGGL(merge_quant_tile_kernel<T>, grid, dim3(kThreads), 0, stream, d, W0, A, B, scale, zero, out);
+  hipLaunchKernelGGL(merge_quant_tile_kernel<T>, grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, scale, zero, out);
 }
 
 void launch_transpose_lora_b(const bf16_t* B, int64_t o, int r, bf16_t* BT, int64_t ld, hipStream_t stream) {
