@@ -85,6 +85,7 @@ struct Tile {
   static_assert(BM % (RPI * 4) == 0 && BN % (RPI * 4) == 0, "load split");
   static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-steps");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+  static_assert(NS >= 3, "the last part of a stage's loads is issued after the wait for the next stage");
 };
 
 template <class T>
@@ -135,17 +136,20 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     for (int kk = 0; kk < T::KK; ++kk) frag_off[kk] = r * T::ROWB + (((kk * 2 + (lane >> 5)) ^ sw) << 4);
   }
 
-  auto issue_loads = [&](int stage, int slot, int nstages) {
+  // part 0 / 1 of a stage's loads: the first / second half of the A and of the B instructions
+  auto issue_loads = [&](int stage, int slot, int nstages, int part, int nparts) {
     const unsigned kbytes = stage < nstages ? (unsigned)stage * (T::BK * 2) : PAST_END_OFFSET;
     unsigned char* base = lds + slot * T::STAGE;
 #pragma unroll
     for (int c = 0; c < T::A_INSTR; ++c)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base + (wave * T::A_INSTR + c) * 1024), 16,
-                                               voffA[c] + kbytes, 0, 0, 0);
+      if (c * nparts / T::A_INSTR == part)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base + (wave * T::A_INSTR + c) * 1024), 16,
+                                                 voffA[c] + kbytes, 0, 0, 0);
 #pragma unroll
     for (int c = 0; c < T::B_INSTR; ++c)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(
-          rsrcB, (lds_ptr_t)(base + T::A_BYTES + (wave * T::B_INSTR + c) * 1024), 16, voffB[c] + kbytes, 0, 0, 0);
+      if (c * nparts / T::B_INSTR == part)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrcB, (lds_ptr_t)(base + T::A_BYTES + (wave * T::B_INSTR + c) * 1024), 16, voffB[c] + kbytes, 0, 0, 0);
   };
 
   bf16x8_t fa[2][T::TM], fb[2][T::TN];
@@ -167,14 +171,19 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 
   const int nk = K / T::BK;
   constexpr int LOADS = T::A_INSTR + T::B_INSTR;
+  static_assert(T::A_INSTR % T::KK == 0 && T::B_INSTR % T::KK == 0, "loads are spread evenly over the k-steps");
+  constexpr int LPK = LOADS / T::KK;  // loads issued per k-step
 #pragma unroll
-  for (int s = 0; s < T::D; ++s) issue_loads(s, s, nk);
+  for (int s = 0; s < T::D; ++s) issue_loads(s, s, nk, 0, 1);
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
   __builtin_amdgcn_s_barrier();
   read_frags(0, 0, 0);
 
-  // Steady state, one basic block per stage.  Loads for stage s + D are issued first (stages past
-  // the end get an out-of-range offset: no memory traffic, and the vmcnt arithmetic stays uniform).
+  // Steady state.  Per k-step: the LDS reads of the next k-step, 1/KK of the global loads for stage
+  // s + D (stages past the end get an out-of-range offset: no memory traffic, and the vmcnt arithmetic
+  // stays uniform), and TM x TN matrix ops, interleaved so that the other two kinds issue in the
+  // shadow of the matrix pipeline and the global loads of the four waves do not arrive in one burst.
+  // In program order the LDS reads come first: the DMA loads write LDS and are kept behind them.
   int slot = 0;
   for (int s = 0; s < nk; ++s) {
     int pslot = slot + T::D;
@@ -184,42 +193,28 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 #pragma unroll
     for (int kk = 0; kk < T::KK; ++kk) {
       if (kk + 1 < T::KK) {
-        // LDS reads first in program order: the DMA loads below write LDS and are kept behind them
         read_frags(slot, kk + 1, (kk + 1) & 1);
-        if (kk == 0) issue_loads(s + T::D, pslot, nk);
-        mfma_block(kk & 1);
-        if (kk == 0) {
-          // interleave: matrix op, LDS read, ..., then matrix ops with the global loads
-#pragma unroll
-          for (int q = 0; q < T::TM + T::TN; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          }
-#pragma unroll
-          for (int q = 0; q < LOADS; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-          }
-        } else {
-#pragma unroll
-          for (int q = 0; q < T::TM + T::TN; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          }
-        }
       } else {
-        // stage s + 1 must have landed for every wave, and every wave must be done reading stage s - 1's
-        // slot mate before it is refilled: all of this wave's LDS reads so far have returned.
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm((T::D - 1) * LOADS));
+        // Stage s + 1 must have landed for every wave: all but the loads of stages s + 2 .. s + D issued
+        // so far, i.e. (D - 2) whole stages plus this stage's first KK - 1 parts, may still be in flight.
+        // All of this wave's LDS reads have returned, so the slot refilled next is free once every wave is here.
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm((T::D - 2) * LOADS + (T::KK - 1) * LPK));
         __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
         __builtin_amdgcn_s_barrier();
         read_frags(nslot, 0, 0);  // after the last stage this reads stale LDS; the values are never used
-        mfma_block(kk & 1);
+      }
+      issue_loads(s + T::D, pslot, nk, kk, T::KK);
+      mfma_block(kk & 1);
 #pragma unroll
-        for (int q = 0; q < T::TM + T::TN; ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
+      for (int q = 0; q < T::TM + T::TN; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      constexpr int REST = T::TM * T::TN - (T::TM + T::TN);
+#pragma unroll
+      for (int q = 0; q < LPK; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, REST / LPK, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       }
     }
     slot = nslot;
