@@ -30,6 +30,11 @@ int check_desc(const l4q_desc* d, bool need_tokens) {
   if (d->group_size < 4 || !is_pow2(d->group_size) || d->in_features % d->group_size != 0) return L4Q_ERR_SHAPE;
   if (d->dtype == L4Q_DTYPE_BF16) {
     if (d->group_size % 8 != 0 || d->out_features % 8 != 0) return L4Q_ERR_SHAPE;
+    // the matrix-core kernels address each operand with 32-bit byte offsets below 1 GiB
+    const int64_t lim = (1ll << 29) - (1ll << 20);  // elements
+    const int64_t t = need_tokens ? d->tokens : 1;
+    if (t * d->in_features >= lim || t * d->out_features >= lim || d->out_features * d->in_features >= lim)
+      return L4Q_ERR_SHAPE;
   }
   if (!(d->alpha == d->alpha)) return L4Q_ERR_SHAPE;
   return L4Q_OK;
@@ -61,21 +66,20 @@ struct Carver {
 };
 
 struct FwdWs {
-  void* wq;  // [o,i] storage type
+  void* wq;      // [o,ipad] storage type; ipad = i rounded up to the GEMM k-step in bf16 mode
+  int64_t ipad;
   size_t bytes;
 };
 struct BwdWs {
   bool fused;        // bf16: weight-gradient GEMM with the fused quantizer epilogue
   float* wq32;       // [o,i]                      (binary32 mode)
   bf16_t* wqT;       // [i,opad]                   (bf16)
-  bf16_t* xT;        // [i,Tpad]                   (bf16)
-  bf16_t* dyT;       // [o,Tpad]                   (bf16)
   uint16_t* fgrad;   // [o,i] binary16             (bf16 fused)
   bf16_t* bT;        // [r,opad]                   (bf16 fused)
   float* dB_part;    // [2 tiles_n, o, r]          (bf16 fused)
   float* dwq;        // [o,i]                      (binary32 mode, bf16 unfused)
   float* dA_part;    // [tiles_m or ceil(o/kDaRowBlock), r, i]
-  int64_t Tpad, opad;
+  int64_t opad;
   int tiles_m, tiles_n;
   size_t bytes;
 };
@@ -83,7 +87,8 @@ struct BwdWs {
 FwdWs carve_fwd(const l4q_desc* d, void* ws) {
   Carver c(ws);
   FwdWs w;
-  const size_t n = (size_t)d->out_features * (size_t)d->in_features;
+  w.ipad = d->dtype == L4Q_DTYPE_BF16 ? (int64_t)align_up((size_t)d->in_features, 32) : d->in_features;
+  const size_t n = (size_t)d->out_features * (size_t)w.ipad;
   w.wq = d->dtype == L4Q_DTYPE_BF16 ? (void*)c.take<bf16_t>(n) : (void*)c.take<float>(n);
   w.bytes = c.used;
   return w;
@@ -94,16 +99,13 @@ BwdWs carve_bwd(const l4q_desc* d, void* ws) {
   BwdWs w = {};
   const size_t o = (size_t)d->out_features, i = (size_t)d->in_features, r = (size_t)d->rank;
   const size_t n = o * i;
-  // token and out-feature axes are zero-padded to the k-step of the matrix-core kernels
-  w.Tpad = (int64_t)align_up((size_t)d->tokens, 32);
+  // Wq^T is zero-padded along its out-feature axis to the k-step of the matrix-core kernels
   w.opad = (int64_t)align_up(o, 32);
   const LayerDims L = dims_of(d);
   const size_t nrb = (o + l4q::kDaRowBlock - 1) / l4q::kDaRowBlock;
   if (d->dtype == L4Q_DTYPE_BF16) {
-    w.fused = !(d->flags & L4Q_FLAG_UNFUSED_BACKWARD) && l4q::dw_fused_supported(L, w.Tpad);
+    w.fused = !(d->flags & L4Q_FLAG_UNFUSED_BACKWARD) && l4q::dw_fused_supported(L);
     w.wqT = c.take<bf16_t>(i * (size_t)w.opad);
-    w.xT = c.take<bf16_t>(i * (size_t)w.Tpad);
-    w.dyT = c.take<bf16_t>(o * (size_t)w.Tpad);
     if (w.fused) {
       l4q::dw_fused_tiles(L, &w.tiles_m, &w.tiles_n);
       w.fgrad = c.take<uint16_t>(n);
@@ -135,7 +137,7 @@ struct GemmProfile {
 
 // Enqueue one bf16 GEMM; when profiling is on, bracket it with events on the same stream.
 void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
-             int64_t K_algorithmic, bf16_t* C_bf16, float* C_f32, int64_t ldc, hipStream_t stream) {
+             int64_t K_algorithmic, bf16_t* C, int64_t ldc, hipStream_t stream) {
   hipEvent_t e0 = nullptr, e1 = nullptr;
   bool timed = false;
   {
@@ -146,7 +148,7 @@ void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t
     }
   }
   if (timed) (void)hipEventRecord(e0, stream);
-  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, C_bf16, C_f32, ldc, stream);
+  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, C, ldc, stream);
   if (timed) {
     (void)hipEventRecord(e1, stream);
     std::lock_guard<std::mutex> lk(g_prof.mu);
@@ -156,7 +158,8 @@ void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t
 }
 
 // The fused weight-gradient kernel is a GEMM launch too: time it the same way.
-void dw_fused(const LayerDims& d, const BwdWs& w, const bf16_t* A, float* dscale, float* dzero, hipStream_t stream) {
+void dw_fused(const LayerDims& d, const BwdWs& w, const bf16_t* dY, const bf16_t* X, const bf16_t* A, float* dscale,
+              float* dzero, hipStream_t stream) {
   hipEvent_t e0 = nullptr, e1 = nullptr;
   bool timed = false;
   {
@@ -167,7 +170,7 @@ void dw_fused(const LayerDims& d, const BwdWs& w, const bf16_t* A, float* dscale
     }
   }
   if (timed) (void)hipEventRecord(e0, stream);
-  l4q::launch_dw_fused(d, w.dyT, w.xT, w.Tpad, w.fgrad, A, w.bT, w.opad, dscale, dzero, w.dA_part, w.dB_part, stream);
+  l4q::launch_dw_fused(d, dY, X, w.fgrad, A, w.bT, w.opad, dscale, dzero, w.dA_part, w.dB_part, stream);
   if (timed) {
     (void)hipEventRecord(e1, stream);
     std::lock_guard<std::mutex> lk(g_prof.mu);
@@ -224,9 +227,9 @@ int l4q_forward(const l4q_desc* desc, const void* X, const void* W0, const void*
     bf16_t* wq = static_cast<bf16_t*>(w.wq);
     l4q::MergeQuantOut<bf16_t> mq;
     mq.wq = wq;
-    mq.ld_wq = d.i;
+    mq.ld_wq = w.ipad;
     l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
-    gemm_nt((const bf16_t*)X, d.i, wq, d.i, d.T, d.o, d.i, d.i, (bf16_t*)Y, nullptr, d.o, stream);
+    gemm_nt((const bf16_t*)X, d.i, wq, w.ipad, d.T, d.o, w.ipad, d.i, (bf16_t*)Y, d.o, stream);
   } else {
     float* wq = static_cast<float*>(w.wq);
     l4q::MergeQuantOut<float> mq;
@@ -265,17 +268,15 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     mq.ld_wqT = w.opad;
     mq.fgrad = w.fgrad;  // null when unfused
     l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, mq, stream);
-    gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, nullptr, d.i, stream);
-    // dWq = dY^T . X with the token axis made contiguous and zero-padded
-    l4q::launch_transpose_u16((const bf16_t*)X, d.T, d.i, w.xT, w.Tpad, stream);
-    l4q::launch_transpose_u16((const bf16_t*)dY, d.T, d.o, w.dyT, w.Tpad, stream);
+    gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream);
+    // dWq = dY^T . X, both operands read as they lie in memory
     if (w.fused) {
       l4q::launch_transpose_lora_b(Bb, d.o, d.r, w.bT, w.opad, stream);
-      dw_fused(d, w, Ab, dscale, dzero, stream);
+      dw_fused(d, w, (const bf16_t*)dY, (const bf16_t*)X, Ab, dscale, dzero, stream);
       l4q::launch_reduce_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, d.gamma, dA, stream);
       l4q::launch_reduce_partials(w.dB_part, 2 * w.tiles_n, d.o * d.r, d.gamma, dB, stream);
     } else {
-      gemm_nt(w.dyT, w.Tpad, w.xT, w.Tpad, d.o, d.i, w.Tpad, d.T, nullptr, w.dwq, d.i, stream);
+      l4q::launch_gemm_bf16_kmajor_f32((const bf16_t*)dY, d.o, (const bf16_t*)X, d.i, d.o, d.i, d.T, w.dwq, d.i, stream);
       l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);
       l4q::launch_dA<bf16_t>(d, Bb, w.dwq, w.dA_part, dA, stream);
     }

@@ -1,6 +1,7 @@
 // Weight-gradient GEMM with the quantizer backward fused into its epilogue (bf16 mode).
 //
-//   dWq[o,i] = dYT[o,T] . XT[i,T]^T            (App. A.1, Eq. appen_wq)   -- stays in registers
+//   dWq[o,i] = dY[T,o]^T . X[T,i]              (App. A.1, Eq. appen_wq)   -- stays in registers;
+//                                              dY and X are read as they lie in memory (K-major operands)
 //   dscale[p,q] = sum_{j in group q} dWq[p,j] * f[p,j]                    (Eq. quant_lsq_s + case list)
 //   dzero [p,q] = sum_{j in group q} dWq[p,j] * (1 - m[p,j])              (Eq. appen_lsq_b)
 //   dB[p,k]     = gamma * sum_j (m * dWq)[p,j] A[k,j]                     (Eq. appen_l4q_b)
@@ -41,9 +42,9 @@ typedef gemm::bf16x8_t bf16x8_t;
 typedef gemm::f32x16_t f32x16_t;
 
 struct FusedArgs {
-  const bf16_t* dYT; int64_t ld_dyt;  // [o, Tpad]
-  const bf16_t* XT;  int64_t ld_xt;   // [i, Tpad]
-  int K;                              // Tpad, multiple of 32
+  const bf16_t* dY;                   // [T, o]
+  const bf16_t* X;                    // [T, i]
+  int K;                              // T
   int o, i, r, g;
   const uint16_t* fgrad;              // [o, i] binary16
   const bf16_t* A;                    // [r, i]
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     for (int b = 0; b < T::TN; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
-  gemm::mainloop<T>(p.dYT, p.ld_dyt, p.XT, p.ld_xt, p.o, p.i, p.K, m0, n0, lds, acc);
+  gemm::mainloop<T, true, true>(p.dY, p.o, p.X, p.i, p.o, p.i, p.K, m0, n0, lds, acc);
   // LDS is free from here on (mainloop ends with a barrier after the last fragment read)
 
   // ---- fragments of the LoRA factor A for the dB product: lane = rank index, 8 k-slots = the same
@@ -267,9 +268,9 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
 
 }  // namespace
 
-bool dw_fused_supported(const LayerDims& d, int64_t Tpad) {
+bool dw_fused_supported(const LayerDims& d) {
   const bool g_ok = d.g == 32 || d.g == 64 || d.g == 128 || d.g == 256;
-  return g_ok && d.r <= 32 && Tpad % T::BK == 0 && d.o * Tpad * 2 < (1ll << 30) && d.i * Tpad * 2 < (1ll << 30);
+  return g_ok && d.r <= 32;
 }
 
 void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n) {
@@ -277,13 +278,13 @@ void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n) {
   *tiles_n = (int)((d.i + T::BN - 1) / T::BN);
 }
 
-void launch_dw_fused(const LayerDims& d, const bf16_t* dYT, const bf16_t* XT, int64_t Tpad, const uint16_t* fgrad,
-                     const bf16_t* A, const bf16_t* BT, int64_t ld_bt, float* dscale, float* dzero, float* dA_part,
-                     float* dB_part, hipStream_t stream) {
+void launch_dw_fused(const LayerDims& d, const bf16_t* dY, const bf16_t* X, const uint16_t* fgrad, const bf16_t* A,
+                     const bf16_t* BT, int64_t ld_bt, float* dscale, float* dzero, float* dA_part, float* dB_part,
+                     hipStream_t stream) {
   FusedArgs p;
-  p.dYT = dYT; p.ld_dyt = Tpad;
-  p.XT = XT; p.ld_xt = Tpad;
-  p.K = (int)Tpad;
+  p.dY = dY;
+  p.X = X;
+  p.K = (int)d.T;
   p.o = (int)d.o; p.i = (int)d.i; p.r = d.r; p.g = d.g;
   p.fgrad = fgrad; p.A = A; p.BT = BT; p.ld_bt = ld_bt;
   p.dscale = dscale; p.dzero = dzero; p.dA_part = dA_part; p.dB_part = dB_part;

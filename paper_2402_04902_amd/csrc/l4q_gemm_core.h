@@ -23,6 +23,8 @@
 // gradient, makes a lane the owner of one weight row.
 #pragma once
 
+#include <type_traits>
+
 #include "l4q_device.h"
 
 namespace l4q {
@@ -93,41 +95,69 @@ struct Accum {
   f32x16_t v[T::TM][T::TN];
 };
 
-// Runs the whole K loop for the tile (m0, n0).  K must be a multiple of T::BK; lda, ldb in
-// elements (multiples of 8).  Rows m >= M of A and n >= N of B read as zeros.
+// Runs the whole K loop for the tile (m0, n0) and leaves C^T tiles in `acc`.
+//
+// Operand forms.  The MFMA wants, per lane, 8 consecutive k of one row.
+//  * K-contiguous operand (A_KM / B_KM = false): P[rows, ld] with k along the contiguous axis.  A stage
+//    is `rows` LDS rows of BK bf16, XOR-swizzled as described at the top; one ds_read_b128 per fragment.
+//  * K-major operand (true): P[k, ld] with the tile's 256 rows along the contiguous axis (dY and X
+//    in dWq = dY^T X, Wq in dX = dY Wq).  A stage is BK LDS rows of 512 B exactly as they lie in
+//    memory (each wave-wide load brings two full 512 B rows), and the transposition happens on
+//    the way to the registers with ds_read_b64_tr_b16: within 16 lanes, lane j supplies the address of
+//    4 consecutive elements of row k0 + j / 4 at column 4 (j % 4), and receives column j of rows
+//    k0 .. k0 + 3.  Two such reads fill the 8 k-slots of a lane.  The 16-byte chunk c of LDS row k sits
+//    at chunk position c ^ 4 (k % 4), which puts the 4 x 32 B a 16-lane group reads, and the two
+//    groups of a half-wave, on all 64 banks once.
+// Ranges.  rows_a / rows_b: valid tile-axis extent of the operand (M, N).  K: number of k values.
+// Anything outside reads as zero through the buffer range check for K-major operands (their row
+// axis is k, so num_records ends the matrix in k; out-of-range columns get an out-of-bounds offset).
+// A K-contiguous operand reads zeros for rows past its extent but, when K is not a multiple of BK,
+// whatever follows in memory for k >= K: the caller pairs it with an operand that is exactly zero there
+// (K-major, or zero-padded storage).
 // On return every wave has passed a barrier after its last LDS read, so LDS may be reused.
-template <class T>
+template <class T, bool A_KM = false, bool B_KM = false>
 __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
                                          int64_t ldb, int M, int N, int K, int m0, int n0, unsigned char* lds,
                                          Accum<T>& acc) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the declaration
+  static_assert((!A_KM || T::BM == 256) && (!B_KM || T::BN == 256), "K-major staging is written for 256-wide tiles");
+  typedef short s16x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr_t;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in SGPRs
   const int wm = wave >> 1, wn = wave & 1;
 
-  const __amdgpu_buffer_rsrc_t rsrcA =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, (int)((int64_t)M * lda * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrcB =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, (int)((int64_t)N * ldb * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(A), 0, (int)((int64_t)(A_KM ? K : M) * lda * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(B), 0, (int)((int64_t)(B_KM ? K : N) * ldb * 2), 0x00020000);
 
   // per-lane source offsets (bytes) of the loads this wave issues each stage
   unsigned voffA[T::A_INSTR], voffB[T::B_INSTR];
+  auto setup_voff = [&](auto km, unsigned* voff, int ninstr, int64_t ld, int origin, int extent) {
 #pragma unroll
-  for (int c = 0; c < T::A_INSTR; ++c) {
-    const int row = (wave * T::A_INSTR + c) * T::RPI + lane / T::CPR;
-    const int ch = (lane % T::CPR) ^ ((row / T::RW) % T::CPR);
-    voffA[c] = (m0 + row < M) ? (unsigned)(((int64_t)(m0 + row) * lda + ch * 8) * 2) : OOB_OFFSET;
-  }
-#pragma unroll
-  for (int c = 0; c < T::B_INSTR; ++c) {
-    const int row = (wave * T::B_INSTR + c) * T::RPI + lane / T::CPR;
-    const int ch = (lane % T::CPR) ^ ((row / T::RW) % T::CPR);
-    voffB[c] = (n0 + row < N) ? (unsigned)(((int64_t)(n0 + row) * ldb + ch * 8) * 2) : OOB_OFFSET;
-  }
+    for (int c = 0; c < ninstr; ++c) {
+      const int q = wave * ninstr + c;
+      if constexpr (decltype(km)::value) {
+        const int kr = q * 2 + (lane >> 5);                    // LDS row = k within the stage
+        const int col = origin + (((lane & 31) ^ (4 * (kr & 3))) << 3);
+        voff[c] = col < extent ? (unsigned)(((int64_t)kr * ld + col) * 2) : OOB_OFFSET;
+      } else {
+        const int row = q * T::RPI + lane / T::CPR;
+        const int ch = (lane % T::CPR) ^ ((row / T::RW) % T::CPR);
+        voff[c] = origin + row < extent ? (unsigned)(((int64_t)(origin + row) * ld + ch * 8) * 2) : OOB_OFFSET;
+      }
+    }
+  };
+  setup_voff(std::integral_constant<bool, A_KM>(), voffA, T::A_INSTR, lda, m0, M);
+  setup_voff(std::integral_constant<bool, B_KM>(), voffB, T::B_INSTR, ldb, n0, N);
+  const unsigned stage_bytes_a = A_KM ? (unsigned)(T::BK * lda * 2) : (unsigned)(T::BK * 2);
+  const unsigned stage_bytes_b = B_KM ? (unsigned)(T::BK * ldb * 2) : (unsigned)(T::BK * 2);
 
-  // per-lane LDS offsets of the MFMA fragments: row (lane % 32) of a 32-row block, logical chunk
-  // 2 kk + lane / 32.  Block bases are multiples of 16 rows, so the swizzle term depends on the lane only.
+  // per-lane LDS offsets of the MFMA fragments.
+  // K-contiguous: row (lane % 32) of a 32-row block, logical chunk 2 kk + lane / 32; block bases are
+  // multiples of 16 rows, so the swizzle term depends on the lane only (one offset per k-step).
   unsigned frag_off[T::KK];
   {
     const int r = lane & 31;
@@ -135,31 +165,62 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 #pragma unroll
     for (int kk = 0; kk < T::KK; ++kk) frag_off[kk] = r * T::ROWB + (((kk * 2 + (lane >> 5)) ^ sw) << 4);
   }
+  // K-major: one offset per 32-column block; k-steps and the second half add constants.
+  unsigned km_off_a[T::TM], km_off_b[T::TN];
+  auto setup_km = [&](unsigned* off, int nblk, int wave_col0) {
+    const int j = lane & 15, g16 = lane >> 4;
+    const int kr = 8 * (lane >> 5) + (j >> 2);
+#pragma unroll
+    for (int blk = 0; blk < nblk; ++blk) {
+      const int chunk = (wave_col0 + blk * 32) / 8 + 2 * (g16 & 1) + ((j & 3) >> 1);
+      off[blk] = kr * 512 + ((chunk ^ (4 * (j >> 2))) << 4) + ((j & 1) << 3);
+    }
+  };
+  if constexpr (A_KM) setup_km(km_off_a, T::TM, wm * T::WTM);
+  if constexpr (B_KM) setup_km(km_off_b, T::TN, wn * T::WTN);
 
-  // part 0 / 1 of a stage's loads: the first / second half of the A and of the B instructions
+  // part `part` of `nparts` of a stage's loads
   auto issue_loads = [&](int stage, int slot, int nstages, int part, int nparts) {
-    const unsigned kbytes = stage < nstages ? (unsigned)stage * (T::BK * 2) : PAST_END_OFFSET;
+    const bool live = stage < nstages;
+    const unsigned ka = live ? (unsigned)stage * stage_bytes_a : PAST_END_OFFSET;
+    const unsigned kb = live ? (unsigned)stage * stage_bytes_b : PAST_END_OFFSET;
     unsigned char* base = lds + slot * T::STAGE;
 #pragma unroll
     for (int c = 0; c < T::A_INSTR; ++c)
       if (c * nparts / T::A_INSTR == part)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base + (wave * T::A_INSTR + c) * 1024), 16,
-                                                 voffA[c] + kbytes, 0, 0, 0);
+                                                 voffA[c] + ka, 0, 0, 0);
 #pragma unroll
     for (int c = 0; c < T::B_INSTR; ++c)
       if (c * nparts / T::B_INSTR == part)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrcB, (lds_ptr_t)(base + T::A_BYTES + (wave * T::B_INSTR + c) * 1024), 16, voffB[c] + kbytes, 0, 0, 0);
+            rsrcB, (lds_ptr_t)(base + T::A_BYTES + (wave * T::B_INSTR + c) * 1024), 16, voffB[c] + kb, 0, 0, 0);
   };
 
   bf16x8_t fa[2][T::TM], fb[2][T::TN];
-  auto read_frags = [&](int slot, int kk, int set) {
-    const unsigned char* as = lds + slot * T::STAGE + wm * T::WTM * T::ROWB + frag_off[kk];
-    const unsigned char* bs = lds + slot * T::STAGE + T::A_BYTES + wn * T::WTN * T::ROWB + frag_off[kk];
+  auto read_km = [&](const unsigned char* region, unsigned off, int kk) -> bf16x8_t {
+    const unsigned char* p0 = region + off + kk * (16 * 512);
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)p0);
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(p0 + 4 * 512));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    const s16x8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8_t, v);
+  };
+  auto read_frags_a = [&](int slot, int kk, int set) {
+    const unsigned char* region = lds + slot * T::STAGE;
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a) fa[set][a] = *reinterpret_cast<const bf16x8_t*>(as + a * 32 * T::ROWB);
+    for (int a = 0; a < T::TM; ++a) {
+      if constexpr (A_KM) fa[set][a] = read_km(region, km_off_a[a], kk);
+      else fa[set][a] = *reinterpret_cast<const bf16x8_t*>(region + wm * T::WTM * T::ROWB + frag_off[kk] + a * 32 * T::ROWB);
+    }
+  };
+  auto read_frags_b = [&](int slot, int kk, int set) {
+    const unsigned char* region = lds + slot * T::STAGE + T::A_BYTES;
 #pragma unroll
-    for (int b = 0; b < T::TN; ++b) fb[set][b] = *reinterpret_cast<const bf16x8_t*>(bs + b * 32 * T::ROWB);
+    for (int b = 0; b < T::TN; ++b) {
+      if constexpr (B_KM) fb[set][b] = read_km(region, km_off_b[b], kk);
+      else fb[set][b] = *reinterpret_cast<const bf16x8_t*>(region + wn * T::WTN * T::ROWB + frag_off[kk] + b * 32 * T::ROWB);
+    }
   };
   auto mfma_block = [&](int set) {
 #pragma unroll
@@ -169,21 +230,28 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         acc.v[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][b], fa[set][a], acc.v[a][b], 0, 0, 0);
   };
 
-  const int nk = K / T::BK;
+  const int nk = (K + T::BK - 1) / T::BK;
   constexpr int LOADS = T::A_INSTR + T::B_INSTR;
   static_assert(T::A_INSTR % T::KK == 0 && T::B_INSTR % T::KK == 0, "loads are spread evenly over the k-steps");
-  constexpr int LPK = LOADS / T::KK;  // loads issued per k-step
+  constexpr int LPK = LOADS / T::KK;                 // loads issued per k-step
+  constexpr int NDA = T::TM * (A_KM ? 2 : 1);        // LDS read instructions per k-step
+  constexpr int NDB = T::TN * (B_KM ? 2 : 1);
+  constexpr int NMF = T::TM * T::TN;
+  constexpr int EXTRA = NDA + NDB + LPK > NMF ? NDA + NDB + LPK - NMF : 0;  // reads that share a matrix op
+  static_assert(2 * EXTRA <= NDA, "too many LDS reads per matrix op");
 #pragma unroll
   for (int s = 0; s < T::D; ++s) issue_loads(s, s, nk, 0, 1);
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
   __builtin_amdgcn_s_barrier();
-  read_frags(0, 0, 0);
+  read_frags_a(0, 0, 0);
+  read_frags_b(0, 0, 0);
 
   // Steady state.  Per k-step: the LDS reads of the next k-step, 1/KK of the global loads for stage
   // s + D (stages past the end get an out-of-range offset: no memory traffic, and the vmcnt arithmetic
   // stays uniform), and TM x TN matrix ops, interleaved so that the other two kinds issue in the
   // shadow of the matrix pipeline and the global loads of the four waves do not arrive in one burst.
-  // In program order the LDS reads come first: the DMA loads write LDS and are kept behind them.
+  // Program order is A reads, DMA loads, B reads: the DMA loads write LDS, so the compiler keeps
+  // them behind the reads before them and ahead of the reads after them.
   int slot = 0;
   for (int s = 0; s < nk; ++s) {
     int pslot = slot + T::D;
@@ -192,29 +260,39 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     if (nslot == T::NS) nslot = 0;
 #pragma unroll
     for (int kk = 0; kk < T::KK; ++kk) {
-      if (kk + 1 < T::KK) {
-        read_frags(slot, kk + 1, (kk + 1) & 1);
-      } else {
+      const bool last = kk + 1 == T::KK;
+      if (last) {
         // Stage s + 1 must have landed for every wave: all but the loads of stages s + 2 .. s + D issued
         // so far, i.e. (D - 2) whole stages plus this stage's first KK - 1 parts, may still be in flight.
         // All of this wave's LDS reads have returned, so the slot refilled next is free once every wave is here.
         __builtin_amdgcn_s_waitcnt(waitcnt_vm((T::D - 2) * LOADS + (T::KK - 1) * LPK));
         __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
         __builtin_amdgcn_s_barrier();
-        read_frags(nslot, 0, 0);  // after the last stage this reads stale LDS; the values are never used
       }
+      // after the last stage the reads below fetch stale LDS; the values are never used
+      read_frags_a(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
       issue_loads(s + T::D, pslot, nk, kk, T::KK);
+      read_frags_b(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
       mfma_block(kk & 1);
 #pragma unroll
-      for (int q = 0; q < T::TM + T::TN; ++q) {
+      for (int q = 0; q < EXTRA; ++q) {  // where reads outnumber matrix ops, two reads per matrix op
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+#pragma unroll
+      for (int q = 0; q < NDA - 2 * EXTRA; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-      constexpr int REST = T::TM * T::TN - (T::TM + T::TN);
 #pragma unroll
       for (int q = 0; q < LPK; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, REST / LPK, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+#pragma unroll
+      for (int q = 0; q < NDB; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
     }
     slot = nslot;

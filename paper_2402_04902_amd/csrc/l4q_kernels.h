@@ -44,15 +44,16 @@ template <class T>
 void launch_init_qparams(const LayerDims& d, const T* W0, const T* A, const T* B, int method, float* scale,
                          float* zero, hipStream_t stream);
 
-// ---- out[c, r] = in[r, c] for 16-bit elements; out has leading dimension ld_out >= rows and
-// the columns rows..ld_out-1 of every output row are zero-filled ----
-void launch_transpose_u16(const uint16_t* in, int64_t rows, int64_t cols, uint16_t* out, int64_t ld_out,
-                          hipStream_t stream);
-
-// ---- bf16 MFMA GEMM  C[M,N] = A[M,K] . B[N,K]^T, fp32 accumulate ----
-// A, B row-major with leading dimensions lda, ldb (elements, multiples of 8); K multiple of 8.
+// ---- bf16 MFMA GEMM  C[M,N] = A[M,K] . B[N,K]^T, fp32 accumulate, bf16 output ----
+// A, B row-major and K-contiguous with leading dimensions lda, ldb (elements, multiples of 8).  B must hold
+// zeros for k in [K_true, K) where K is rounded up to 32; A may be read past its row end there.
+// Every operand below 1 GiB, N % 4 == 0, ldc % 4 == 0.
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
-                         int64_t K, bf16_t* C_bf16, float* C_f32, int64_t ldc, hipStream_t stream);
+                         int64_t K, bf16_t* C, int64_t ldc, hipStream_t stream);
+
+// ---- C[M,N] (float) = A[K,M]^T . B[K,N]: both operands K-major (rows = k), any K ----
+void launch_gemm_bf16_kmajor_f32(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
+                                 int64_t K, float* C, int64_t ldc, hipStream_t stream);
 
 // ---- binary32 GEMM with arbitrary strides: C[m,n] = scale * sum_k A[m*a_rs + k*a_cs] B[k*b_rs + n*b_cs] ----
 void launch_sgemm(const float* A, int64_t a_rs, int64_t a_cs, const float* B, int64_t b_rs, int64_t b_cs,
@@ -76,13 +77,13 @@ void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, fl
                             hipStream_t stream);
 
 // ---- weight-gradient GEMM with fused quantizer backward (bf16 mode) ----
-// dYT [o, Tpad], XT [i, Tpad] zero-padded along T; fgrad [o, i] binary16 from launch_merge_quant;
+// dY [T, o], X [T, i] as the caller holds them; fgrad [o, i] binary16 from launch_merge_quant;
 // BT [r, ld_bt] from launch_transpose_lora_b.  Writes dscale, dzero [o, G] and the partial sums
 // dA_part [tiles_m, r, i], dB_part [2 * tiles_n, o, r] (no gamma applied yet).
-bool dw_fused_supported(const LayerDims& d, int64_t Tpad);
+bool dw_fused_supported(const LayerDims& d);
 void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n);
-void launch_dw_fused(const LayerDims& d, const bf16_t* dYT, const bf16_t* XT, int64_t Tpad, const uint16_t* fgrad,
-                     const bf16_t* A, const bf16_t* BT, int64_t ld_bt, float* dscale, float* dzero, float* dA_part,
-                     float* dB_part, hipStream_t stream);
+void launch_dw_fused(const LayerDims& d, const bf16_t* dY, const bf16_t* X, const uint16_t* fgrad, const bf16_t* A,
+                     const bf16_t* BT, int64_t ld_bt, float* dscale, float* dzero, float* dA_part, float* dB_part,
+                     hipStream_t stream);
 
 }  // namespace l4q

@@ -1,4 +1,4 @@
-// Merge + quantize pass, integer-code export, min/max initialisation, 16-bit transpose.
+// Merge + quantize pass, integer-code export, min/max initialisation.
 //
 // merge_quant_tile_kernel is the HBM-streaming prologue of both passes: it reads W0 once with
 // coalesced 8/16-byte loads, adds the rank-r update from registers, applies the group-wise
@@ -121,9 +121,10 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
       cpack |= ((uint32_t)(uint8_t)(int8_t)(int)qo.code) << (8 * c);
       mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
     }
+    // the dequantized weight is zero-padded up to its leading dimension (k-step of the GEMM)
+    if (out.wq && p < d.o && j0 < out.ld_wq) store4(out.wq + p * out.ld_wq + j0, wqv);
     if (ok) {
       const int64_t off = p * d.i + j0;
-      if (out.wq) store4(out.wq + p * out.ld_wq + j0, wqv);
       if (out.codes) *reinterpret_cast<uint32_t*>(out.codes + off) = cpack;
       if (out.mask) *reinterpret_cast<uint32_t*>(out.mask + off) = mpack;
       if (out.wcomb) store4(out.wcomb + off, wc);
@@ -221,46 +222,6 @@ __global__ __launch_bounds__(kThreads) void init_qparams_kernel(LayerDims d, con
   }
 }
 
-// 64 x 64 tile through LDS; 16-byte global accesses on both sides.
-__global__ __launch_bounds__(256) void transpose_u16_kernel(const uint16_t* __restrict__ in, int64_t rows,
-                                                             int64_t cols, uint16_t* __restrict__ out,
-                                                             int64_t ld_out) {
-  __shared__ uint32_t tile[64][33];  // 64 rows of 64 halves; 33-dword stride keeps column reads conflict-free
-  const int64_t r0 = (int64_t)blockIdx.y * 64;
-  const int64_t c0 = (int64_t)blockIdx.x * 64;
-  const int tid = threadIdx.x;
-#pragma unroll
-  for (int it = 0; it < 2; ++it) {
-    const int idx = tid + it * 256;
-    const int rr = idx >> 3, ch = idx & 7;
-    const int64_t r = r0 + rr, c = c0 + ch * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < rows && c < cols) v = *reinterpret_cast<const uint4*>(in + r * cols + c);
-    tile[rr][ch * 4 + 0] = v.x;
-    tile[rr][ch * 4 + 1] = v.y;
-    tile[rr][ch * 4 + 2] = v.z;
-    tile[rr][ch * 4 + 3] = v.w;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < 2; ++it) {
-    const int idx = tid + it * 256;
-    const int cc = idx >> 3, ch = idx & 7;  // output row cc, 8 consecutive input rows ch*8..
-    const int64_t c = c0 + cc, r = r0 + ch * 8;
-    if (c < cols && r < ld_out) {
-      uint32_t h[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) h[e] = (tile[ch * 8 + e][cc >> 1] >> (16 * (cc & 1))) & 0xFFFFu;
-      uint4 v;
-      v.x = h[0] | (h[1] << 16);
-      v.y = h[2] | (h[3] << 16);
-      v.z = h[4] | (h[5] << 16);
-      v.w = h[6] | (h[7] << 16);
-      *reinterpret_cast<uint4*>(out + c * ld_out + r) = v;
-    }
-  }
-}
-
 }  // namespace
 
 template <class T>
@@ -282,12 +243,6 @@ void launch_init_qparams(const LayerDims& d, const T* W0, const T* A, const T* B
   const int rows_per_block = kThreads / 64;
   dim3 grid((unsigned)((d.o + rows_per_block - 1) / rows_per_block));
   hipLaunchKernelGGL(init_qparams_kernel<T>, grid, dim3(kThreads), 0, stream, d, W0, A, B, method, scale, zero);
-}
-
-void launch_transpose_u16(const uint16_t* in, int64_t rows, int64_t cols, uint16_t* out, int64_t ld_out,
-                          hipStream_t stream) {
-  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((ld_out + 63) / 64));
-  hipLaunchKernelGGL(transpose_u16_kernel, grid, dim3(256), 0, stream, in, rows, cols, out, ld_out);
 }
 
 template void launch_merge_quant<float>(const LayerDims&, const float*, const float*, const float*, const float*,

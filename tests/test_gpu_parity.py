@@ -70,6 +70,8 @@ def test_fp32_ragged_shapes():
     (513, 768, 1032, 20, 4, 256),    # rank above one register chunk
     (64, 512, 8, 1, 2, 32),          # one row block, rank 1, 2 bits
     (777, 2048, 776, 8, 8, 2048),    # one group per row
+    (70, 40, 24, 2, 4, 8),           # in-features not a multiple of the 32-wide k-step, tiny group
+    (45, 200, 136, 4, 4, 8),
 ])
 @pytest.mark.parametrize("shrink", [1.0, 0.8])
 def test_bf16_small_shapes(T, i, o, r, bits, g, shrink):
