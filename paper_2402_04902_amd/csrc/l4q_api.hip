@@ -273,8 +273,8 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     if (w.fused) {
       l4q::launch_transpose_lora_b(Bb, d.o, d.r, w.bT, w.opad, stream);
       dw_fused(d, w, (const bf16_t*)dY, (const bf16_t*)X, Ab, dscale, dzero, stream);
-      l4q::launch_reduce_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, d.gamma, dA, stream);
-      l4q::launch_reduce_partials(w.dB_part, 2 * w.tiles_n, d.o * d.r, d.gamma, dB, stream);
+      l4q::launch_reduce_two_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, dA, w.dB_part, 2 * w.tiles_n,
+                                      d.o * d.r, dB, d.gamma, stream);
     } else {
       l4q::launch_gemm_bf16_kmajor_f32((const bf16_t*)dY, d.o, (const bf16_t*)X, d.i, d.o, d.i, d.T, w.dwq, d.i, stream);
       l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);

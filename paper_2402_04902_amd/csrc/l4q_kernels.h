@@ -76,6 +76,10 @@ void launch_dA(const LayerDims& d, const T* B, const float* dWp, float* partial,
 void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, float scale, float* out,
                             hipStream_t stream);
 
+// outa = scale * sum of nba partials of na elements, outb likewise, in one launch (na, nb multiples of 4)
+void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* outa, const float* pb, int nbb,
+                                int64_t nb, float* outb, float scale, hipStream_t stream);
+
 // ---- weight-gradient GEMM with fused quantizer backward (bf16 mode) ----
 // dY [T, o], X [T, i] as the caller holds them; fgrad [o, i] binary16 from launch_merge_quant;
 // BT [r, ld_bt] from launch_transpose_lora_b.  Writes dscale, dzero [o, G] and the partial sums

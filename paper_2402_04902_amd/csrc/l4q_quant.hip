@@ -51,10 +51,11 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
   const int64_t jblk = (int64_t)blockIdx.x * MQ_COLS;
   const int64_t j0 = jblk + lane * 4;
   const bool col_ok = j0 < d.i;
-  const int64_t jc = col_ok ? j0 : 0;                                  // clamped column for loads
+  const unsigned jc = col_ok ? (unsigned)j0 : 0u;                      // clamped column for loads (32-bit lane offset)
+  const unsigned j32 = (unsigned)j0;
   const int64_t pw = (int64_t)blockIdx.y * MQ_ROWS + wave * MQ_RPW;    // first row of this wave
   const int64_t G = d.i / d.g;
-  const int64_t q = jc / d.g;  // 4 consecutive columns lie in one group because g % 4 == 0
+  const unsigned q = jc / (unsigned)d.g;  // 4 consecutive columns lie in one group because g % 4 == 0
 
   // row data, requested up front
   raw4_t w0raw[MQ_RPW];
@@ -62,9 +63,10 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
 #pragma unroll
   for (int rr = 0; rr < MQ_RPW; ++rr) {
     const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
-    w0raw[rr] = *reinterpret_cast<const raw4_t*>(W0 + pc * d.i + jc);
-    sv[rr] = scale[pc * G + q];
-    bv[rr] = zero[pc * G + q];
+    // wave-uniform row base first, lane offset second: the loads take a scalar base register
+    w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
+    sv[rr] = (scale + pc * G)[q];
+    bv[rr] = (zero + pc * G)[q];
   }
 
   float acc[MQ_RPW][4];
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
 #pragma unroll
     for (int k = 0; k < MQ_KC; ++k) {
       const int kc = k0 + k < d.r ? k0 + k : d.r - 1;
-      araw[k] = *reinterpret_cast<const raw4_t*>(A + (int64_t)kc * d.i + jc);
+      araw[k] = *reinterpret_cast<const raw4_t*>((A + (int64_t)kc * d.i) + jc);
     }
     // B[p, k0 + lane] for lanes 0..15 of each row; zero past the rank so those steps add nothing
     float brow[MQ_RPW];
@@ -86,7 +88,7 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
     for (int rr = 0; rr < MQ_RPW; ++rr) {
       const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
       const int kl = k0 + (lane & (MQ_KC - 1));
-      const float v = load1(B + pc * d.r + (kl < d.r ? kl : d.r - 1));
+      const float v = load1((B + pc * d.r) + (kl < d.r ? kl : d.r - 1));
       brow[rr] = kl < d.r ? v : 0.f;
     }
 #pragma unroll
@@ -122,16 +124,16 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
       mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
     }
     // the dequantized weight is zero-padded up to its leading dimension (k-step of the GEMM)
-    if (out.wq && p < d.o && j0 < out.ld_wq) store4(out.wq + p * out.ld_wq + j0, wqv);
+    if (out.wq && p < d.o && j0 < out.ld_wq) store4((out.wq + p * out.ld_wq) + j32, wqv);
     if (ok) {
-      const int64_t off = p * d.i + j0;
-      if (out.codes) *reinterpret_cast<uint32_t*>(out.codes + off) = cpack;
-      if (out.mask) *reinterpret_cast<uint32_t*>(out.mask + off) = mpack;
-      if (out.wcomb) store4(out.wcomb + off, wc);
+      const int64_t rowoff = p * d.i;  // wave-uniform
+      if (out.codes) *reinterpret_cast<uint32_t*>((out.codes + rowoff) + j32) = cpack;
+      if (out.mask) *reinterpret_cast<uint32_t*>((out.mask + rowoff) + j32) = mpack;
+      if (out.wcomb) store4((out.wcomb + rowoff) + j32, wc);
       if (out.fgrad) {
         typedef _Float16 h4 __attribute__((ext_vector_type(4)));
         h4 h = {(_Float16)fg[0], (_Float16)fg[1], (_Float16)fg[2], (_Float16)fg[3]};
-        *reinterpret_cast<h4*>(out.fgrad + off) = h;
+        *reinterpret_cast<h4*>((out.fgrad + rowoff) + j32) = h;
       }
     }
 #pragma unroll

@@ -191,6 +191,34 @@ void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, fl
                      nblocks, n, scale, out);
 }
 
+// Both reductions of the fused backward in one launch; 4 consecutive elements per thread (n % 4 == 0).
+__global__ __launch_bounds__(256) void reduce_two_partials_kernel(const float* __restrict__ pa, int nba, int64_t na,
+                                                                   float* __restrict__ outa,
+                                                                   const float* __restrict__ pb, int nbb, int64_t nb,
+                                                                   float* __restrict__ outb, float scale,
+                                                                   int blocks_a) {
+  const bool second = (int)blockIdx.x >= blocks_a;
+  const float* __restrict__ part = second ? pb : pa;
+  float* __restrict__ out = second ? outb : outa;
+  const int nblocks = second ? nbb : nba;
+  const int64_t n = second ? nb : na;
+  const int64_t e = ((int64_t)(second ? blockIdx.x - blocks_a : blockIdx.x) * 256 + threadIdx.x) * 4;
+  if (e >= n) return;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int b = 0; b < nblocks; ++b) {  // ascending: the summation order is fixed
+    const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)b * n + e);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  *reinterpret_cast<float4*>(out + e) = make_float4(scale * acc.x, scale * acc.y, scale * acc.z, scale * acc.w);
+}
+
+void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* outa, const float* pb, int nbb,
+                                int64_t nb, float* outb, float scale, hipStream_t stream) {
+  const int blocks_a = (int)((na / 4 + 255) / 256), blocks_b = (int)((nb / 4 + 255) / 256);
+  hipLaunchKernelGGL(reduce_two_partials_kernel, dim3((unsigned)(blocks_a + blocks_b)), dim3(256), 0, stream, pa, nba,
+                     na, outa, pb, nbb, nb, outb, scale, blocks_a);
+}
+
 void launch_sgemm(const float* A, int64_t a_rs, int64_t a_cs, const float* B, int64_t b_rs, int64_t b_cs,
                   float* C, int64_t ldc, int64_t M, int64_t N, int64_t K, float scale, hipStream_t stream) {
   dim3 grid((unsigned)((N + SG_BN - 1) / SG_BN), (unsigned)((M + SG_BM - 1) / SG_BM));
