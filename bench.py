@@ -110,6 +110,17 @@ def main() -> int:
     gemm_ms, gemm_launches, gemm_flops = binding.l4q_profile_gemm_read()
     binding.l4q_profile_gemm(False)
 
+    # matrix-core-only ceiling on this chip for the benchmark's own operand values (random bf16 from X)
+    sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda:0")
+    binding.l4q_mfma_probe(layers[0].X, 2000, 2048, sink)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    probe_flops = binding.l4q_mfma_probe(layers[0].X, 8000, 2048, sink)
+    ev1.record()
+    torch.cuda.synchronize()
+    mfma_only_tflops = probe_flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
+
     flops_per_step = sum(s.gemm_flops() for s in specs)
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = flops_per_step / (ms_per_step * 1e-3) / 1e12
@@ -133,7 +144,8 @@ def main() -> int:
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "launches": gemm_launches,
                      "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
-                     "gemm_share_of_step": gemm_ms / args.steps / ms_per_step},
+                     "gemm_share_of_step": gemm_ms / args.steps / ms_per_step,
+                     "measured_mfma_only_tflops": mfma_only_tflops},
     }
     if not args.no_cpu_baseline:
         del layers

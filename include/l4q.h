@@ -136,10 +136,22 @@ int l4q_export_codes(const l4q_desc* desc, const void* W0, const void* A, const 
  *   L4Q_INIT_ASYMM : s = (max - min) / (Q_P - Q_N),  b = min - s Q_N
  *   L4Q_INIT_SYMM  : s = max|W| / 2^(n-1),           b = 0
  *   L4Q_INIT_L4Q   : s = max(|min / Q_N|, |max / Q_P|), b = 0
- * evaluated in binary32, one rounding per written operation.  `tokens` is ignored. */
-enum { L4Q_INIT_ASYMM = 0, L4Q_INIT_SYMM = 1, L4Q_INIT_L4Q = 2 };
+ *   L4Q_INIT_LSQPLUS : s = max(|mu - 3 sigma|, |mu + 3 sigma|) / 2^(n-1), b = 0, mu / sigma the mean and
+ *                      (population) standard deviation of the group; group_size <= 256 only
+ * The first three are evaluated in binary32, one rounding per written operation (bit-reproducible);
+ * LSQ+ sums in binary32 in an unspecified order.  `tokens` is ignored. */
+enum { L4Q_INIT_ASYMM = 0, L4Q_INIT_SYMM = 1, L4Q_INIT_L4Q = 2, L4Q_INIT_LSQPLUS = 3 };
 int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const void* B,
                      int method, float* scale, float* zero, void* hip_stream);
+
+/* Quantization and clipping error of the current parameters (App. B, the E_quant / E_clip columns of the
+ * initialisation table; the paper names them without formulas, read here as)
+ *   errors[0] = sum over the weight of |Wc - Wq|,   errors[1] = sum of |Wc - (clamp(w, Q_N, Q_P) scale + zero)|.
+ * errors: 2 floats on the device.  workspace: out_features * ceil(in_features / 256) * 8 bytes, 256-byte
+ * aligned.  `tokens` is ignored. */
+int l4q_quant_errors(const l4q_desc* desc, const void* W0, const void* A, const void* B,
+                     const float* scale, const float* zero, float* errors,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Opt-in timing of the bf16 GEMM launches, for benchmarks (not for use under graph capture:
  * it creates HIP events).  While enabled, every GEMM the library enqueues is bracketed by two
@@ -150,6 +162,13 @@ int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const 
  * their algorithmic FLOPs (2 M N K each, with the unpadded K); any pointer may be NULL. */
 int l4q_profile_gemm(int enable);
 int l4q_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops);
+
+/* Matrix-core-only microbenchmark (for benchmarks): `workgroups` workgroups of 4 waves each run
+ * `iterations` x 16 v_mfma_f32_32x32x16_bf16 on operand fragments taken from the first 64 KiB of
+ * `data` (device, bf16), with the register shape of the library's GEMM and no memory traffic in
+ * the loop.  sink: device, workgroups * 256 floats (written once at the end).  *flops receives the
+ * FLOPs of the launch.  What it sustains depends on the operand values (power). */
+int l4q_mfma_probe(const void* data, int iterations, int workgroups, float* sink, double* flops, void* hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* l4q_status_string(int status);

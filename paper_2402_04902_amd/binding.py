@@ -15,10 +15,10 @@ from .inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libl4q.so")
 
 FLAG_UNFUSED_BACKWARD = 1
-INIT_ASYMM, INIT_SYMM, INIT_L4Q = 0, 1, 2
+INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
-            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read"]
+            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors"]
 
 
 class L4QDesc(ctypes.Structure):
@@ -64,6 +64,10 @@ def load_library() -> ctypes.CDLL:
     lib.l4q_profile_gemm_read.restype = ctypes.c_int
     lib.l4q_profile_gemm_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
                                           ctypes.POINTER(ctypes.c_double)]
+    lib.l4q_quant_errors.restype = ctypes.c_int
+    lib.l4q_quant_errors.argtypes = [dp, vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+    lib.l4q_mfma_probe.restype = ctypes.c_int
+    lib.l4q_mfma_probe.argtypes = [vp, ctypes.c_int, ctypes.c_int, fp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
     return lib
 
@@ -123,6 +127,13 @@ def l4q_init_qparams(desc: L4QDesc, W0, A, B, method: int, scale, zero) -> None:
                                            _ptr(zero), _stream()), "l4q_init_qparams")
 
 
+def l4q_quant_errors(desc: L4QDesc, W0, A, B, scale, zero, errors, workspace) -> None:
+    _check(load_library().l4q_quant_errors(ctypes.byref(desc), _ptr(W0), _ptr(A), _ptr(B), _ptr(scale), _ptr(zero),
+                                           _ptr(errors), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()),
+           "l4q_quant_errors")
+
+
 def l4q_profile_gemm(enable: bool) -> None:
     _check(load_library().l4q_profile_gemm(1 if enable else 0), "l4q_profile_gemm")
 
@@ -133,6 +144,14 @@ def l4q_profile_gemm_read() -> Tuple[float, int, float]:
     _check(load_library().l4q_profile_gemm_read(ctypes.byref(ms), ctypes.byref(n), ctypes.byref(fl)),
            "l4q_profile_gemm_read")
     return ms.value, n.value, fl.value
+
+
+def l4q_mfma_probe(data, iterations: int, workgroups: int, sink) -> float:
+    """Enqueue the matrix-core-only probe; returns the FLOPs of the launch."""
+    fl = ctypes.c_double(0)
+    _check(load_library().l4q_mfma_probe(_ptr(data), int(iterations), int(workgroups), _ptr(sink), ctypes.byref(fl),
+                                         _stream()), "l4q_mfma_probe")
+    return fl.value
 
 
 # ---------------------------------------------------------------------------

@@ -330,7 +330,9 @@ int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const 
                      float* zero, void* hip_stream) {
   const int st = check_desc(desc, false);
   if (st != L4Q_OK) return st;
-  if (method != L4Q_INIT_ASYMM && method != L4Q_INIT_SYMM && method != L4Q_INIT_L4Q) return L4Q_ERR_METHOD;
+  if (method != L4Q_INIT_ASYMM && method != L4Q_INIT_SYMM && method != L4Q_INIT_L4Q && method != L4Q_INIT_LSQPLUS)
+    return L4Q_ERR_METHOD;
+  if (method == L4Q_INIT_LSQPLUS && desc->group_size > 256) return L4Q_ERR_METHOD;
   if (!W0 || !A || !B || !scale || !zero) return L4Q_ERR_NULL;
   const void* ptrs[] = {W0, A, B, scale, zero};
   for (const void* p : ptrs)
@@ -344,6 +346,40 @@ int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const 
   else
     l4q::launch_init_qparams<float>(d, (const float*)W0, (const float*)A, (const float*)B, method, scale, zero,
                                     stream);
+  return launch_status();
+}
+
+int l4q_quant_errors(const l4q_desc* desc, const void* W0, const void* A, const void* B, const float* scale,
+                     const float* zero, float* errors, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int st = check_desc(desc, false);
+  if (st != L4Q_OK) return st;
+  if (!W0 || !A || !B || !scale || !zero || !errors) return L4Q_ERR_NULL;
+  const void* ptrs[] = {W0, A, B, scale, zero, errors};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  const size_t need = (size_t)desc->out_features * (size_t)((desc->in_features + 255) / 256) * 2 * sizeof(float);
+  if (!workspace || workspace_bytes < need) return L4Q_ERR_WORKSPACE;
+  if (!aligned(workspace, kWsAlign)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16)
+    l4q::launch_quant_errors<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero,
+                                     (float*)workspace, errors, stream);
+  else
+    l4q::launch_quant_errors<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero,
+                                    (float*)workspace, errors, stream);
+  return launch_status();
+}
+
+int l4q_mfma_probe(const void* data, int iterations, int workgroups, float* sink, double* flops, void* hip_stream) {
+  if (!data || !sink) return L4Q_ERR_NULL;
+  if (iterations < 1 || workgroups < 1 || workgroups > (1 << 20)) return L4Q_ERR_SHAPE;
+  if (!aligned(data, 16) || !aligned(sink, 16)) return L4Q_ERR_ALIGN;
+  (void)hipGetLastError();
+  const double f = l4q::launch_mfma_probe((const bf16_t*)data, iterations, workgroups, sink,
+                                          static_cast<hipStream_t>(hip_stream));
+  if (flops) *flops = f;
   return launch_status();
 }
 

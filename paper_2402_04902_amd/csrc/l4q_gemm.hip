@@ -55,7 +55,50 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* 
   }
 }
 
+// Matrix-core-only loop with the GEMM's register shape (4 x 4 accumulator tiles, 8 fragments per wave) and
+// no memory traffic inside the loop: what the matrix pipeline sustains on this chip for the given data.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const bf16_t* __restrict__ data, int iterations,
+                                                         float* __restrict__ sink) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef gemm::bf16x8_t bf16x8_t;
+  typedef gemm::f32x16_t f32x16_t;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  bf16x8_t fa[4], fb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {  // 8 fragments of 16 bytes per lane out of the first 64 KiB of data
+    fa[q] = *reinterpret_cast<const bf16x8_t*>(data + ((wave * 8 + q) * 64 + lane) * 8);
+    fb[q] = *reinterpret_cast<const bf16x8_t*>(data + ((wave * 8 + 4 + q) * 64 + lane) * 8);
+  }
+  f32x16_t acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+  for (int it = 0; it < iterations; ++it) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[b], fa[a], acc[a][b], 0, 0, 0);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) t += acc[a][b][e];
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = t;
+#endif
+}
+
 }  // namespace
+
+double launch_mfma_probe(const bf16_t* data, int iterations, int workgroups, float* sink, hipStream_t stream) {
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, data, iterations, sink);
+  return (double)workgroups * 4.0 * (double)iterations * 16.0 * (2.0 * 32 * 32 * 16);
+}
 
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
                          int64_t K, bf16_t* C, int64_t ldc, hipStream_t stream) {

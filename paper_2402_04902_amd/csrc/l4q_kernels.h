@@ -44,12 +44,22 @@ template <class T>
 void launch_init_qparams(const LayerDims& d, const T* W0, const T* A, const T* B, int method, float* scale,
                          float* zero, hipStream_t stream);
 
+// ---- quantization / clipping error sums (App. B, Table 5): out2[0] = sum |Wc - Wq|, out2[1] = sum |Wc - (clamp(w) s + b)| ----
+// partial: [o * ceil(i / 256) * 2] floats of scratch
+template <class T>
+void launch_quant_errors(const LayerDims& d, const T* W0, const T* A, const T* B, const float* scale,
+                         const float* zero, float* partial, float* out2, hipStream_t stream);
+
 // ---- bf16 MFMA GEMM  C[M,N] = A[M,K] . B[N,K]^T, fp32 accumulate, bf16 output ----
 // A, B row-major and K-contiguous with leading dimensions lda, ldb (elements, multiples of 8).  B must hold
 // zeros for k in [K_true, K) where K is rounded up to 32; A may be read past its row end there.
 // Every operand below 1 GiB, N % 4 == 0, ldc % 4 == 0.
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
                          int64_t K, bf16_t* C, int64_t ldc, hipStream_t stream);
+
+// ---- matrix-core-only probe: `workgroups` x 4 waves x `iterations` x 16 MFMA 32x32x16 on fragments taken from the
+// first 64 KiB of `data`; sink [workgroups * 256] floats.  Returns the FLOPs the launch performs. ----
+double launch_mfma_probe(const bf16_t* data, int iterations, int workgroups, float* sink, hipStream_t stream);
 
 // ---- C[M,N] (float) = A[K,M]^T . B[K,N]: both operands K-major (rows = k), any K ----
 void launch_gemm_bf16_kmajor_f32(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,

@@ -37,6 +37,48 @@ __device__ __forceinline__ void unpack4(const uint2& r, float (&v)[4]) {
   v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xFFFF0000u);
 }
 
+// acc[rr][c] = sum_k B[pw + rr, k] * A[k, jc + c], k ascending, for the MQ_RPW rows of a wave and the 4 columns
+// of a lane.  Rows past o are clamped (their sums are never used); no lane may skip this call because
+// B is read through other lanes' registers.
+template <class T>
+__device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restrict__ A, const T* __restrict__ B,
+                                          unsigned jc, int64_t pw, int lane, float (&acc)[MQ_RPW][4]) {
+  typedef typename Raw4<T>::type raw4_t;
+#pragma unroll
+  for (int rr = 0; rr < MQ_RPW; ++rr)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
+  for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
+    raw4_t araw[MQ_KC];
+#pragma unroll
+    for (int k = 0; k < MQ_KC; ++k) {
+      const int kc = k0 + k < d.r ? k0 + k : d.r - 1;
+      araw[k] = *reinterpret_cast<const raw4_t*>((A + (int64_t)kc * d.i) + jc);
+    }
+    // B[p, k0 + lane] for lanes 0..15 of each row; zero past the rank so those steps add nothing
+    float brow[MQ_RPW];
+#pragma unroll
+    for (int rr = 0; rr < MQ_RPW; ++rr) {
+      const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
+      const int kl = k0 + (lane & (MQ_KC - 1));
+      const float v = load1((B + pc * d.r) + (kl < d.r ? kl : d.r - 1));
+      brow[rr] = kl < d.r ? v : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < MQ_KC; ++k) {
+      float a[4];
+      unpack4(araw[k], a);
+#pragma unroll
+      for (int rr = 0; rr < MQ_RPW; ++rr) {
+        // b = 0 past the rank: acc + 0 * a and fma(0, a, acc) leave the running sum unchanged bit for bit
+        const float bk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(brow[rr]), k));
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[c]);
+      }
+    }
+  }
+}
+
 template <class T>
 __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims d, const T* __restrict__ W0,
                                                                        const T* __restrict__ A,
@@ -70,40 +112,7 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
   }
 
   float acc[MQ_RPW][4];
-#pragma unroll
-  for (int rr = 0; rr < MQ_RPW; ++rr)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
-
-  for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
-    raw4_t araw[MQ_KC];
-#pragma unroll
-    for (int k = 0; k < MQ_KC; ++k) {
-      const int kc = k0 + k < d.r ? k0 + k : d.r - 1;
-      araw[k] = *reinterpret_cast<const raw4_t*>((A + (int64_t)kc * d.i) + jc);
-    }
-    // B[p, k0 + lane] for lanes 0..15 of each row; zero past the rank so those steps add nothing
-    float brow[MQ_RPW];
-#pragma unroll
-    for (int rr = 0; rr < MQ_RPW; ++rr) {
-      const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
-      const int kl = k0 + (lane & (MQ_KC - 1));
-      const float v = load1((B + pc * d.r) + (kl < d.r ? kl : d.r - 1));
-      brow[rr] = kl < d.r ? v : 0.f;
-    }
-#pragma unroll
-    for (int k = 0; k < MQ_KC; ++k) {
-      float a[4];
-      unpack4(araw[k], a);
-#pragma unroll
-      for (int rr = 0; rr < MQ_RPW; ++rr) {
-        // b = 0 past the rank: acc + 0 * a and fma(0, a, acc) leave the running sum unchanged bit for bit
-        const float bk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(brow[rr]), k));
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[c]);
-      }
-    }
-  }
+  lora_rows<T>(d, A, B, jc, pw, lane, acc);
 
   uint32_t tpack[4][MQ_RPW / 2];  // Wq of (column c, row pair) as two bf16, for the transposed output
 #pragma unroll
@@ -161,6 +170,130 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
         *reinterpret_cast<uint4*>(out.wqT + j * out.ld_wqT + p) =
             *reinterpret_cast<const uint4*>(tile + jr * MQ_TROW + ch * 16);
     }
+  }
+}
+
+// ------------------------------------------------------------------ per-group statistics of the merged weight
+// Same tile mapping as the merge pass.  mode 0..3: initialisation schemes of App. B (asymmetric, symmetric,
+// L4Q_init, LSQ+_init) for group sizes up to 256 (a group then lies inside one wave's 256 columns);
+// mode 4: per-row, per-column-block sums of |Wc - Wq| and |Wc - (clamp(w) s + b)| (E_quant, E_clip).
+constexpr int STAT_ERRORS = 4;
+
+template <class T>
+__global__ __launch_bounds__(MQ_THREADS) void weight_stats_tile_kernel(LayerDims d, const T* __restrict__ W0,
+                                                                        const T* __restrict__ A,
+                                                                        const T* __restrict__ B, int mode,
+                                                                        float* __restrict__ scale,
+                                                                        float* __restrict__ zero,
+                                                                        float* __restrict__ err_part) {
+  typedef typename Raw4<T>::type raw4_t;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t j0 = (int64_t)blockIdx.x * MQ_COLS + lane * 4;
+  const bool col_ok = j0 < d.i;
+  const unsigned jc = col_ok ? (unsigned)j0 : 0u;
+  const int64_t pw = (int64_t)blockIdx.y * MQ_ROWS + wave * MQ_RPW;
+  const int64_t G = d.i / d.g;
+  const unsigned q = jc / (unsigned)d.g;
+  const int width = d.g / 4 < 64 ? d.g / 4 : 64;  // lanes per group (power of two)
+  const float inf = __builtin_huge_valf();
+
+  raw4_t w0raw[MQ_RPW];
+  float sv[MQ_RPW], bv[MQ_RPW];
+#pragma unroll
+  for (int rr = 0; rr < MQ_RPW; ++rr) {
+    const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
+    w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
+    sv[rr] = mode == STAT_ERRORS ? (scale + pc * G)[q] : 1.f;
+    bv[rr] = mode == STAT_ERRORS ? (zero + pc * G)[q] : 0.f;
+  }
+  float acc[MQ_RPW][4];
+  lora_rows<T>(d, A, B, jc, pw, lane, acc);
+
+#pragma unroll
+  for (int rr = 0; rr < MQ_RPW; ++rr) {
+    const int64_t p = pw + rr;
+    const bool ok = col_ok && p < d.o;
+    float w0[4], wc[4];
+    unpack4(w0raw[rr], w0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) wc[c] = w0[c] + d.gamma * acc[rr][c];
+    if (mode == STAT_ERRORS) {
+      float eq = 0.f, ec = 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const QuantOut qo = quantize_elem(wc[c], sv[rr], bv[rr], d.qn, d.qp);
+        const float clamped = fminf(fmaxf(qo.w, d.qn), d.qp);
+        eq += ok ? fabsf(wc[c] - dequant_elem(qo.code, sv[rr], bv[rr])) : 0.f;
+        ec += ok ? fabsf(wc[c] - dequant_elem(clamped, sv[rr], bv[rr])) : 0.f;
+      }
+      eq = wave_sum_width(eq, 64);
+      ec = wave_sum_width(ec, 64);
+      if (lane == 0 && p < d.o) {
+        float* dst = err_part + (p * gridDim.x + blockIdx.x) * 2;
+        dst[0] = eq;
+        dst[1] = ec;
+      }
+    } else {
+      float lo = inf, hi = -inf, sum = 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        lo = ok ? fminf(lo, wc[c]) : lo;
+        hi = ok ? fmaxf(hi, wc[c]) : hi;
+        sum += ok ? wc[c] : 0.f;
+      }
+      for (int off = width >> 1; off > 0; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off, 64));
+        hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+        sum += __shfl_xor(sum, off, 64);
+      }
+      float s = 0.f, b = 0.f;
+      if (mode == 0) {  // asymmetric min/max
+        s = __fdiv_rn(hi - lo, d.qp - d.qn);
+        b = lo - s * d.qn;
+      } else if (mode == 1) {  // symmetric
+        s = __fdiv_rn(fmaxf(fabsf(lo), fabsf(hi)), -d.qn);
+      } else if (mode == 2) {  // L4Q_init (Eq. l4q_quant_init)
+        s = fmaxf(fabsf(__fdiv_rn(lo, d.qn)), fabsf(__fdiv_rn(hi, d.qp)));
+      } else {  // LSQ+_init: mean and (population) standard deviation of the group, two passes in registers
+        const float mu = sum / (float)d.g;
+        float ss = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ss += ok ? (wc[c] - mu) * (wc[c] - mu) : 0.f;
+        for (int off = width >> 1; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        const float sd = sqrtf(ss / (float)d.g);
+        s = fmaxf(fabsf(mu - 3.f * sd), fabsf(mu + 3.f * sd)) / -d.qn;
+      }
+      if (ok && (lane & (width - 1)) == 0) {
+        scale[p * G + q] = s;
+        zero[p * G + q] = b;
+      }
+    }
+  }
+}
+
+// sums err_part [rows * 2] pairs into out[0] (E_quant) and out[1] (E_clip); one block, fixed order
+__global__ __launch_bounds__(256) void sum_error_pairs_kernel(const float* __restrict__ part, int64_t npairs,
+                                                               float* __restrict__ out) {
+  __shared__ double sh[2][256];
+  double a = 0.0, b = 0.0;
+  for (int64_t e = threadIdx.x; e < npairs; e += 256) {
+    a += part[2 * e];
+    b += part[2 * e + 1];
+  }
+  sh[0][threadIdx.x] = a;
+  sh[1][threadIdx.x] = b;
+  __syncthreads();
+  for (int st = 128; st > 0; st >>= 1) {
+    if ((int)threadIdx.x < st) {
+      sh[0][threadIdx.x] += sh[0][threadIdx.x + st];
+      sh[1][threadIdx.x] += sh[1][threadIdx.x + st];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    out[0] = (float)sh[0][0];
+    out[1] = (float)sh[1][0];
   }
 }
 
@@ -242,15 +375,35 @@ void launch_transpose_lora_b(const bf16_t* B, int64_t o, int r, bf16_t* BT, int6
 template <class T>
 void launch_init_qparams(const LayerDims& d, const T* W0, const T* A, const T* B, int method, float* scale,
                          float* zero, hipStream_t stream) {
+  if (d.g <= 256) {
+    dim3 grid((unsigned)((d.i + MQ_COLS - 1) / MQ_COLS), (unsigned)((d.o + MQ_ROWS - 1) / MQ_ROWS));
+    hipLaunchKernelGGL(weight_stats_tile_kernel<T>, grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, method, scale,
+                       zero, (float*)nullptr);
+    return;
+  }
   const int rows_per_block = kThreads / 64;
   dim3 grid((unsigned)((d.o + rows_per_block - 1) / rows_per_block));
   hipLaunchKernelGGL(init_qparams_kernel<T>, grid, dim3(kThreads), 0, stream, d, W0, A, B, method, scale, zero);
 }
 
+template <class T>
+void launch_quant_errors(const LayerDims& d, const T* W0, const T* A, const T* B, const float* scale,
+                         const float* zero, float* partial, float* out2, hipStream_t stream) {
+  dim3 grid((unsigned)((d.i + MQ_COLS - 1) / MQ_COLS), (unsigned)((d.o + MQ_ROWS - 1) / MQ_ROWS));
+  hipLaunchKernelGGL(weight_stats_tile_kernel<T>, grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, STAT_ERRORS,
+                     const_cast<float*>(scale), const_cast<float*>(zero), partial);
+  hipLaunchKernelGGL(sum_error_pairs_kernel, dim3(1), dim3(256), 0, stream, partial, d.o * (int64_t)grid.x, out2);
+}
+
+
 template void launch_merge_quant<float>(const LayerDims&, const float*, const float*, const float*, const float*,
                                         const float*, const MergeQuantOut<float>&, hipStream_t);
 template void launch_merge_quant<bf16_t>(const LayerDims&, const bf16_t*, const bf16_t*, const bf16_t*,
                                          const float*, const float*, const MergeQuantOut<bf16_t>&, hipStream_t);
+template void launch_quant_errors<float>(const LayerDims&, const float*, const float*, const float*, const float*,
+                                         const float*, float*, float*, hipStream_t);
+template void launch_quant_errors<bf16_t>(const LayerDims&, const bf16_t*, const bf16_t*, const bf16_t*,
+                                          const float*, const float*, float*, float*, hipStream_t);
 template void launch_init_qparams<float>(const LayerDims&, const float*, const float*, const float*, int, float*,
                                          float*, hipStream_t);
 template void launch_init_qparams<bf16_t>(const LayerDims&, const bf16_t*, const bf16_t*, const bf16_t*, int,

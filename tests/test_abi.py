@@ -91,6 +91,10 @@ def test_null_alignment_and_workspace_errors(lib):
     assert lib.l4q_export_codes(r, 16, 16, 16, 16, 16, 8, None, None, None) == -5
     assert lib.l4q_init_qparams(r, 16, 16, 16, 7, 16, 16, None) == -8
     assert lib.l4q_init_qparams(r, 16, 16, 16, 0, None, 16, None) == -1
+    assert lib.l4q_quant_errors(r, 16, 16, 16, 16, 16, 16, 256, 8, None) == -6
+    assert lib.l4q_quant_errors(r, 16, 16, 16, 16, 16, None, 256, 1 << 30, None) == -1
+    assert lib.l4q_mfma_probe(None, 1, 1, 16, None, None) == -1
+    assert lib.l4q_mfma_probe(16, 0, 1, 16, None, None) == -2
 
 
 def test_descriptor_layout_matches_header():

@@ -165,6 +165,38 @@ def test_init_qparams_bit_exact(dtype, method, mid):
         assert np.allclose(s, s64, rtol=1e-5, atol=0) and np.allclose(b, b64, rtol=1e-4, atol=1e-7)
 
 
+@pytest.mark.parametrize("dtype", [DTYPE_F32, DTYPE_BF16])
+def test_init_lsqplus_and_error_sums(dtype):
+    """LSQ+ initialisation (App. B) within binary32 rounding of the oracle; E_quant / E_clip sums of the
+    resulting (clipping) state against the oracle's float64 sums."""
+    import torch
+    from oracle import l4q_oracle as O
+    from paper_2402_04902_amd import binding
+    for g in (32, 128, 256):
+        spec = LayerSpec(f"lsqplus_g{g}", 8, 1280, 200, 8, 16.0, 4, g, dtype)
+        print("case", spec.name, "dtype", dtype, flush=True)
+        arrs = inputs.make_layer_inputs(spec, seed=g + 1)
+        layer = binding.upload(spec, arrs)
+        binding.l4q_init_qparams(layer.desc, layer.W0, layer.A, layer.B, binding.INIT_LSQPLUS, layer.scale, layer.zero)
+        torch.cuda.synchronize()
+        Wc = O.merge(arrs["W0"], arrs["A"], arrs["B"], spec.alpha)
+        s64, b64 = O.init_qparams(Wc, spec.bits, g, "lsq+")
+        s_gpu = layer.scale.cpu().numpy()
+        assert np.allclose(s_gpu, s64, rtol=2e-5, atol=0)
+        assert not layer.zero.cpu().numpy().any() and not b64.any()
+        # error sums with the GPU's own (float32) scales: LSQ+ clips the outliers
+        errors = torch.zeros(4, dtype=torch.float32, device=layer.W0.device)
+        ws = torch.empty(spec.out_features * ((spec.in_features + 255) // 256) * 8, dtype=torch.uint8,
+                         device=layer.W0.device)
+        binding.l4q_quant_errors(layer.desc, layer.W0, layer.A, layer.B, layer.scale, layer.zero, errors, ws)
+        torch.cuda.synchronize()
+        e = errors.cpu().numpy()
+        eq = O.quantization_error(Wc, s_gpu, b64, spec.bits, g)
+        ec = O.clipping_error(Wc, s_gpu, b64, spec.bits, g)
+        assert ec > 0
+        assert abs(e[0] - eq) <= 1e-4 * eq and abs(e[1] - ec) <= 1e-4 * ec, (e, eq, ec)
+
+
 # ------------------------------------------------------------------ run-to-run reproducibility
 
 def test_backward_is_bit_reproducible():
