@@ -263,3 +263,54 @@ def quantization_error(Wc, s, b, bits: int, g: int) -> float:
     """E_quant = sum |W_comb - W_q|  (App. B, Table 5; formula is this file's reading)."""
     w = prequant(Wc, s, b, g)
     return float(np.abs(np.asarray(Wc, F64) - dequant(codes_from_w(w, bits), s, b, g)).sum())
+
+
+# --------------------------------------------------------------------------
+# fully quantized layer: packed integer codes and the single forward path
+# (Sec. 3.2: inference uses only Wq = w~ s + b; Eq. l4q_forward)
+# --------------------------------------------------------------------------
+
+def pack_codes(codes, bits: int) -> np.ndarray:
+    """Pack integer codes [o, i] into 32-bit words [o, bits*i/32].
+
+    The unsigned field u = w~ - Q_N (0 .. 2^n - 1) of column j occupies bits [n j, n j + n) of the
+    row's little-endian bit string; i must be a multiple of 32 so that rows end on a word.
+    The paper fixes no storage format; this is the layout of this repository.
+    """
+    qn, _ = q_bounds(bits)
+    c = np.asarray(codes).astype(np.int64)
+    o, i = c.shape
+    assert i % 32 == 0
+    u = (c - qn).astype(np.uint64)
+    words = np.zeros((o, bits * i // 32), dtype=np.uint64)
+    for j in range(i):
+        bit = bits * j
+        w, sh = bit >> 5, bit & 31
+        words[:, w] |= (u[:, j] << np.uint64(sh)) & np.uint64(0xFFFFFFFF)
+        if sh + bits > 32:
+            words[:, w + 1] |= u[:, j] >> np.uint64(32 - sh)
+    return words.astype(np.uint32)
+
+
+def unpack_codes(packed, bits: int, i: int) -> np.ndarray:
+    """Inverse of pack_codes: integer codes [o, i] (int64)."""
+    qn, _ = q_bounds(bits)
+    p = np.asarray(packed).astype(np.uint64)
+    o = p.shape[0]
+    out = np.empty((o, i), dtype=np.int64)
+    mask = np.uint64((1 << bits) - 1)
+    for j in range(i):
+        bit = bits * j
+        w, sh = bit >> 5, bit & 31
+        v = p[:, w] >> np.uint64(sh)
+        if sh + bits > 32:
+            v = v | (p[:, w + 1] << np.uint64(32 - sh))
+        out[:, j] = (v & mask).astype(np.int64) + qn
+    return out
+
+
+def quantized_forward(X, packed, s, b, bits: int, g: int) -> np.ndarray:
+    """Y = X Wq^T with Wq = w~ s + b rebuilt from the packed codes alone (no W0, A, B)."""
+    i = np.asarray(X).shape[1]
+    Wq = dequant(unpack_codes(packed, bits, i), s, b, g)
+    return np.asarray(X, F64) @ Wq.T

@@ -389,3 +389,37 @@ def test_f32_merge_order_is_sequential_unfused():
             for k in range(5):
                 acc = f(acc + f(B[p, k] * A[k, j]))
             assert got[p, j] == f(W0[p, j] + f(gamma * acc))
+
+
+# ---------------------------------------------------------------- packed codes, single forward path (Sec. 3.2)
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+def test_pack_unpack_roundtrip_and_bit_positions(bits):
+    rng = np.random.default_rng(37 + bits)
+    qn, qp = O.q_bounds(bits)
+    codes = rng.integers(qn, qp + 1, size=(5, 64))
+    packed = O.pack_codes(codes, bits)
+    assert packed.dtype == np.uint32 and packed.shape == (5, bits * 64 // 32)
+    assert np.array_equal(O.unpack_codes(packed, bits, 64), codes)
+    # field j sits at bit n*j of the row's little-endian bit string: rebuild row 0 as one big integer
+    big = 0
+    for w, word in enumerate(packed[0]):
+        big |= int(word) << (32 * w)
+    for j in range(64):
+        assert ((big >> (bits * j)) & ((1 << bits) - 1)) + qn == codes[0, j]
+    # extreme codes map to all-zero / all-one fields
+    assert O.pack_codes(np.full((1, 32), qn), bits).max() == 0
+    assert O.pack_codes(np.full((1, 32), qp), bits).min() == 0xFFFFFFFF
+
+
+def test_packed_forward_is_the_layer_forward():
+    """The fully quantized path (codes, scale, zero only) gives exactly the layer's training-time output."""
+    p = small_problem(seed=41, T=6, o=7, i=64, r=3, g=32, bits=4, shrink=0.8)
+    dec = O.decide_f64(p["W0"], p["A"], p["B"], p["s"], p["b"], 4, 32, p["alpha"])
+    packed = O.pack_codes(dec.codes, 4)
+    Yq = O.quantized_forward(p["X"], packed, p["s"], p["b"], 4, 32)
+    assert np.array_equal(Yq, call_fwd(p))
+    # and independently: dequantize by hand from the unpacked fields
+    c = O.unpack_codes(packed, 4, 64)
+    Wq = np.array([[c[q, j] * p["s"][q, j // 32] + p["b"][q, j // 32] for j in range(64)] for q in range(7)])
+    assert np.allclose(Yq, p["X"] @ Wq.T, rtol=1e-13)
