@@ -131,6 +131,21 @@ int l4q_export_codes(const l4q_desc* desc, const void* W0, const void* A, const 
                      const float* scale, const float* zero,
                      int8_t* codes, float* wcomb, uint8_t* mask, void* hip_stream);
 
+/* Packed export of the fully quantized layer (Sec. 3.2).  packed: out_features * bits * in_features / 32
+ * 32-bit words; the unsigned field u = w~ - Q_N of column j occupies bits [bits*j, bits*j + bits) of the row's
+ * little-endian bit string.  in_features % 32 == 0.  workspace: out_features * in_features bytes,
+ * 256-byte aligned.  `tokens` is ignored. */
+int l4q_export_packed(const l4q_desc* desc, const void* W0, const void* A, const void* B,
+                      const float* scale, const float* zero, uint32_t* packed,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Forward pass of the fully quantized layer from the packed codes alone (no W0, A, B):
+ *   Y[T,o] = X[T,i] . (w~ scale + zero)^T        (Eq. l4q_forward with Eq. l4q_Wdequant)
+ * BF16 only (X, Y bfloat16); bits in {2,3,4,8}; in_features % 64 == 0.  Meant for decode-sized T:
+ * the weight stream is re-read for every 64 tokens.  Needs no workspace. */
+int l4q_quantized_forward(const l4q_desc* desc, const void* X, const uint32_t* packed,
+                          const float* scale, const float* zero, void* Y, void* hip_stream);
+
 /* Quantization-parameter initialisation from the merged weight (Sec. 3.3, Eq. l4q_quant_init;
  * App. B, Eq. quant_inits).  Writes scale, zero [o,G].
  *   L4Q_INIT_ASYMM : s = (max - min) / (Q_P - Q_N),  b = min - s Q_N

@@ -18,7 +18,7 @@ FLAG_UNFUSED_BACKWARD = 1
 INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
-            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors"]
+            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward"]
 
 
 class L4QDesc(ctypes.Structure):
@@ -66,6 +66,10 @@ def load_library() -> ctypes.CDLL:
                                           ctypes.POINTER(ctypes.c_double)]
     lib.l4q_quant_errors.restype = ctypes.c_int
     lib.l4q_quant_errors.argtypes = [dp, vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+    lib.l4q_export_packed.restype = ctypes.c_int
+    lib.l4q_export_packed.argtypes = [dp, vp, vp, vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
+    lib.l4q_quantized_forward.restype = ctypes.c_int
+    lib.l4q_quantized_forward.argtypes = [dp, vp, vp, fp, fp, vp, vp]
     lib.l4q_mfma_probe.restype = ctypes.c_int
     lib.l4q_mfma_probe.argtypes = [vp, ctypes.c_int, ctypes.c_int, fp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -132,6 +136,18 @@ def l4q_quant_errors(desc: L4QDesc, W0, A, B, scale, zero, errors, workspace) ->
                                            _ptr(errors), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream()),
            "l4q_quant_errors")
+
+
+def l4q_export_packed(desc: L4QDesc, W0, A, B, scale, zero, packed, workspace) -> None:
+    _check(load_library().l4q_export_packed(ctypes.byref(desc), _ptr(W0), _ptr(A), _ptr(B), _ptr(scale), _ptr(zero),
+                                            _ptr(packed), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream()),
+           "l4q_export_packed")
+
+
+def l4q_quantized_forward(desc: L4QDesc, X, packed, scale, zero, Y) -> None:
+    _check(load_library().l4q_quantized_forward(ctypes.byref(desc), _ptr(X), _ptr(packed), _ptr(scale), _ptr(zero),
+                                                _ptr(Y), _stream()), "l4q_quantized_forward")
 
 
 def l4q_profile_gemm(enable: bool) -> None:

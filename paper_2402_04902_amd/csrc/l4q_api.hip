@@ -349,6 +349,52 @@ int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const 
   return launch_status();
 }
 
+int l4q_export_packed(const l4q_desc* desc, const void* W0, const void* A, const void* B, const float* scale,
+                      const float* zero, uint32_t* packed, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  const int st = check_desc(desc, false);
+  if (st != L4Q_OK) return st;
+  if (desc->in_features % 32 != 0) return L4Q_ERR_SHAPE;
+  if (!W0 || !A || !B || !scale || !zero || !packed) return L4Q_ERR_NULL;
+  const void* ptrs[] = {W0, A, B, scale, zero, packed};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  const size_t need = (size_t)desc->out_features * (size_t)desc->in_features;
+  if (!workspace || workspace_bytes < need) return L4Q_ERR_WORKSPACE;
+  if (!aligned(workspace, kWsAlign)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  int8_t* codes = static_cast<int8_t*>(workspace);
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16) {
+    l4q::MergeQuantOut<bf16_t> mq;
+    mq.codes = codes;
+    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
+  } else {
+    l4q::MergeQuantOut<float> mq;
+    mq.codes = codes;
+    l4q::launch_merge_quant<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, mq, stream);
+  }
+  l4q::launch_pack_codes(codes, d.o, d.i, d.bits, packed, stream);
+  return launch_status();
+}
+
+int l4q_quantized_forward(const l4q_desc* desc, const void* X, const uint32_t* packed, const float* scale,
+                          const float* zero, void* Y, void* hip_stream) {
+  const int st = check_desc(desc, true);
+  if (st != L4Q_OK) return st;
+  if (desc->dtype != L4Q_DTYPE_BF16) return L4Q_ERR_DTYPE;
+  const LayerDims d = dims_of(desc);
+  if (!l4q::qgemm_supported(d)) return (d.bits == 2 || d.bits == 3 || d.bits == 4 || d.bits == 8) ? L4Q_ERR_SHAPE : L4Q_ERR_BITS;
+  if (!X || !packed || !scale || !zero || !Y) return L4Q_ERR_NULL;
+  const void* ptrs[] = {X, packed, scale, zero, Y};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  (void)hipGetLastError();
+  l4q::launch_qgemm(d, (const bf16_t*)X, packed, scale, zero, (bf16_t*)Y, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
 int l4q_quant_errors(const l4q_desc* desc, const void* W0, const void* A, const void* B, const float* scale,
                      const float* zero, float* errors, void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int st = check_desc(desc, false);

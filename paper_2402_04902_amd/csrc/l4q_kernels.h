@@ -86,6 +86,12 @@ void launch_dA(const LayerDims& d, const T* B, const float* dWp, float* partial,
 void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, float scale, float* out,
                             hipStream_t stream);
 
+// ---- fully quantized layer: bit-packing of int8 codes [o,i] (i % 32 == 0) and Y = X . dequant(packed)^T ----
+void launch_pack_codes(const int8_t* codes, int64_t o, int64_t i, int bits, uint32_t* packed, hipStream_t stream);
+bool qgemm_supported(const LayerDims& d);
+void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, const float* scale, const float* zero,
+                  bf16_t* Y, hipStream_t stream);
+
 // outa = scale * sum of nba partials of na elements, outb likewise, in one launch (na, nb multiples of 4)
 void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* outa, const float* pb, int nbb,
                                 int64_t nb, float* outb, float scale, hipStream_t stream);
