@@ -121,6 +121,37 @@ def main() -> int:
     torch.cuda.synchronize()
     mfma_only_tflops = probe_flops / (ev0.elapsed_time(ev1) * 1e-3) / 1e12
 
+    # fully quantized inference path at decode batch sizes: packed codes + scale/zero only (HBM-bound)
+    decode = {}
+    packs = []
+    for layer in layers:
+        sp = layer.spec
+        pk = torch.empty((sp.out_features, sp.bits * sp.in_features // 32), dtype=torch.int32, device="cuda:0")
+        binding.l4q_export_packed(layer.desc, layer.W0, layer.A, layer.B, layer.scale, layer.zero, pk,
+                                  layer.ws[: sp.out_features * sp.in_features])
+        packs.append(pk)
+    for tok in (1, 16, 64):
+        descs = [binding.make_desc(l.spec.with_(tokens=tok)) for l in layers]
+        xs = [l.X[:tok] for l in layers]
+        ys = [l.Y[:tok] for l in layers]
+
+        def qstep():
+            for d_, x_, p_, l_, y_ in zip(descs, xs, packs, layers, ys):
+                binding.l4q_quantized_forward(d_, x_, p_, l_.scale, l_.zero, y_)
+        for _ in range(5):
+            qstep()
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(50):
+            qstep()
+        ev1.record()
+        torch.cuda.synchronize()
+        us = ev0.elapsed_time(ev1) * 1e3 / 50
+        nbytes = sum(p_.numel() * 4 + 2 * l_.scale.numel() * 4 + tok * (l_.spec.in_features + l_.spec.out_features) * 2
+                     for p_, l_ in zip(packs, layers))
+        decode["T%d" % tok] = {"us_both_layers": us, "GB_per_s": nbytes / (us * 1e-6) / 1e9,
+                               "frac_hbm_8TBs": nbytes / (us * 1e-6) / 8e12}
+
     flops_per_step = sum(s.gemm_flops() for s in specs)
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = flops_per_step / (ms_per_step * 1e-3) / 1e12
@@ -147,6 +178,7 @@ def main() -> int:
                      "gemm_share_of_step": gemm_ms / args.steps / ms_per_step,
                      "measured_mfma_only_tflops": mfma_only_tflops},
     }
+    out["quantized_forward"] = decode
     if not args.no_cpu_baseline:
         del layers
         torch.cuda.empty_cache()

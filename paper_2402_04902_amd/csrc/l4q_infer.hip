@@ -38,14 +38,25 @@ __global__ __launch_bounds__(256) void pack_codes_kernel(const int8_t* __restric
   packed[idx] = word;
 }
 
-constexpr int QG_TOK = 64;  // tokens per pass
+constexpr int QG_WAVES = 8;   // k-split inside a workgroup
 
-template <int BITS>
-__global__ __launch_bounds__(256) void qgemm_kernel(const bf16_t* __restrict__ X, const uint32_t* __restrict__ packed,
-                                                     const float* __restrict__ scale,
-                                                     const float* __restrict__ zero, bf16_t* __restrict__ Y, int T,
-                                                     int o, int i, int g, float qn) {
-  __shared__ float red[4][2][16][64];
+// Integer code fields -> bf16 matrix operand without a per-element convert:
+//  * n <= 7: the bf16 bit pattern 0x4300 | u is the exact value 128 + u, so the matrix core multiplies
+//    X with (w~ + K0), K0 = 128 - Q_N, and the shift is undone together with the zero term below;
+//  * n == 8: v_cvt_f32_ubyte + (-128) gives w~ itself (|w~| <= 128 is exact in bf16), K0 = 0.
+// The affine part of Eq. l4q_Wdequant is applied to the accumulator, once per 64-wide k chunk (one group
+// or a whole number of groups when g < 64 -- then per 8-wide fragment):
+//   sum_k X (w~ s + b) = s * sum_k X (w~ + K0) + (b - K0 s) * sum_k X.
+// The matrix op is issued as D = Xfrag . Wfrag^T, so a lane of D is a weight row (scale / zero are per
+// lane) and its 16 registers are tokens; sum_k X comes from a second matrix op against a fragment of ones.
+template <int BITS, int NTB, bool PER_FRAG>
+__global__ __launch_bounds__(QG_WAVES * 64) void qgemm_kernel(const bf16_t* __restrict__ X,
+                                                               const uint32_t* __restrict__ packed,
+                                                               const float* __restrict__ scale,
+                                                               const float* __restrict__ zero,
+                                                               bf16_t* __restrict__ Y, int T, int o, int i, int g,
+                                                               float qn) {
+  __shared__ float red[QG_WAVES][2][16][64];
 #if defined(__HIP_DEVICE_COMPILE__)
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -56,10 +67,18 @@ __global__ __launch_bounds__(256) void qgemm_kernel(const bf16_t* __restrict__ X
   const int words_per_row = BITS * (i / 32);
   const int G = i / g;
   const uint32_t* wrow = packed + (int64_t)pc * words_per_row;
+  const float* srow = scale + (int64_t)pc * G;
+  const float* brow = zero + (int64_t)pc * G;
   const int nchunks = i / 64;
   constexpr uint32_t MASK = (1u << BITS) - 1u;
+  constexpr float K0 = BITS == 8 ? 0.f : 128.f + (float)(1 << (BITS - 1));
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
+  constexpr bool per_frag = PER_FRAG;  // g < 64: a chunk holds several groups
 
-  for (int t0 = 0; t0 < T; t0 += QG_TOK) {
+  for (int t0 = 0; t0 < T; t0 += 32 * NTB) {
+    constexpr bool two_blocks = NTB == 2;  // a pass covers 32 * NTB tokens
     f32x16_t acc[2];
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb)
@@ -69,58 +88,185 @@ __global__ __launch_bounds__(256) void qgemm_kernel(const bf16_t* __restrict__ X
     const bf16_t* xa = X + (int64_t)(t_a < T ? t_a : T - 1) * i;
     const bf16_t* xb = X + (int64_t)(t_b < T ? t_b : T - 1) * i;
 
-    for (int c = wave; c < nchunks; c += 4) {
-      const int krun = c * 64 + lh * 32;  // first k of this lane group's 32-code run
+    // Operands of one 64-wide k chunk.  Lane group h = lane / 32 owns k = 64 c + 32 h .. + 31 in both operands.
+    struct Chunk {
       uint32_t w[BITS + 1];
+      float s[4], b[4];
+      uint4 xa[4], xb[4];
+    };
+    auto fetch = [&](int c, Chunk& ck) {
+      const int cc = c < nchunks ? c : nchunks - 1;  // clamped: a fetch past the end is never consumed
+      const int krun = cc * 64 + lh * 32;
 #pragma unroll
-      for (int q = 0; q < BITS; ++q) w[q] = wrow[(krun / 32) * BITS + q];
-      w[BITS] = 0;
-      float s = scale[(int64_t)pc * G + krun / g], b = zero[(int64_t)pc * G + krun / g];
+      for (int q = 0; q < BITS; ++q) ck.w[q] = wrow[(krun / 32) * BITS + q];
+      ck.w[BITS] = 0;
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
-        if (g < 32 && m > 0) {  // a group can end inside the run: refresh per fragment
-          s = scale[(int64_t)pc * G + (krun + 8 * m) / g];
-          b = zero[(int64_t)pc * G + (krun + 8 * m) / g];
+        if (g < 32 || m == 0) {
+          const int kq = g >= 32 ? krun : krun + 8 * m;
+          ck.s[m] = srow[kq / g];
+          ck.b[m] = brow[kq / g];
+        } else {
+          ck.s[m] = ck.s[0];
+          ck.b[m] = ck.b[0];
         }
-        float f[8];
+        ck.xa[m] = *reinterpret_cast<const uint4*>(xa + krun + 8 * m);
+        if (two_blocks) ck.xb[m] = *reinterpret_cast<const uint4*>(xb + krun + 8 * m);
+      }
+    };
+    auto wfrag_of = [&](const Chunk& ck, int m) -> bf16x8_t {
+      uint32_t d[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int bit = (8 * m + e) * BITS;
+      for (int e2 = 0; e2 < 4; ++e2) {
+        uint32_t u[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int bit = (8 * m + 2 * e2 + h) * BITS;
           const int idx = bit >> 5, sh = bit & 31;
-          uint32_t v = w[idx] >> sh;
-          if (sh + BITS > 32) v |= w[idx + 1] << (32 - sh);
-          f[e] = p_ok ? fmaf((float)(v & MASK) + qn, s, b) : 0.f;
+          uint32_t v = ck.w[idx] >> sh;
+          if (sh + BITS > 32) v |= ck.w[idx + 1] << (32 - sh);
+          u[h] = v & MASK;
         }
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-        const u32x4 wp = {pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
-                          pack_bf16x2(f[6], f[7])};
-        const bf16x8_t wfrag = __builtin_bit_cast(bf16x8_t, wp);
-        uint4 ra = *reinterpret_cast<const uint4*>(xa + krun + 8 * m);
-        uint4 rb = *reinterpret_cast<const uint4*>(xb + krun + 8 * m);
-        if (t_a >= T) ra = make_uint4(0, 0, 0, 0);
-        if (t_b >= T) rb = make_uint4(0, 0, 0, 0);
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag, __builtin_bit_cast(bf16x8_t, ra), acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag, __builtin_bit_cast(bf16x8_t, rb), acc[1], 0, 0, 0);
+        if (BITS == 8) d[e2] = pack_bf16x2((float)u[0] - 128.f, (float)u[1] - 128.f);
+        else d[e2] = (u[0] | (u[1] << 16)) | 0x43004300u;
+      }
+      const u32x4 wp = {d[0], d[1], d[2], d[3]};
+      return __builtin_bit_cast(bf16x8_t, wp);
+    };
+    // The two lane groups of a wave hold different k ranges of the chunk and, for g < 64, different groups:
+    // the matrix op sums both groups' k-slots into one accumulator, so the affine part can only be applied
+    // per chunk when scale and zero are the same for both halves, i.e. g >= 64.  Smaller groups take the
+    // slower route of scaling the operand itself.
+    auto consume = [&](const Chunk& ck) {
+      if constexpr (!per_frag) {
+        f32x16_t tw[2], tx[2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { tw[tb][e] = 0.f; tx[tb][e] = 0.f; }
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const bf16x8_t wf = wfrag_of(ck, m);
+          const bf16x8_t xfa = __builtin_bit_cast(bf16x8_t, ck.xa[m]);  // tokens past T: clamped row, never stored
+          tw[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xfa, wf, tw[0], 0, 0, 0);
+          tx[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xfa, ones, tx[0], 0, 0, 0);
+          if (two_blocks) {
+            const bf16x8_t xfb = __builtin_bit_cast(bf16x8_t, ck.xb[m]);
+            tw[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xfb, wf, tw[1], 0, 0, 0);
+            tx[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xfb, ones, tx[1], 0, 0, 0);
+          }
+        }
+        // g >= 64: both lane groups share the chunk's scale / zero; take them from the row's own lane
+        const float sc = ck.s[0], bz = ck.b[0] - K0 * ck.s[0];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+          if (tb == 1 && !two_blocks) break;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[tb][e] = fmaf(bz, tx[tb][e], fmaf(sc, tw[tb][e], acc[tb][e]));
+        }
+      } else {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          // dequantize the operand itself: w~ s + b rounded to bf16, as the training forward does
+          float f[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int bit = (8 * m + e) * BITS;
+            const int idx = bit >> 5, sh = bit & 31;
+            uint32_t v = ck.w[idx] >> sh;
+            if (sh + BITS > 32) v |= ck.w[idx + 1] << (32 - sh);
+            f[e] = fmaf((float)(v & MASK) + qn, ck.s[m], ck.b[m]);
+          }
+          const u32x4 wp = {pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]),
+                            pack_bf16x2(f[6], f[7])};
+          const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, wp);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ck.xa[m]), wf, acc[0], 0, 0, 0);
+          if (two_blocks) {
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ck.xb[m]), wf, acc[1], 0, 0, 0);
+          }
+        }
+      }
+    };
+    if constexpr (per_frag) {
+      Chunk c0, c1;
+      fetch(wave, c0);
+      for (int c = wave; c < nchunks; c += 2 * QG_WAVES) {
+        fetch(c + QG_WAVES, c1);
+        consume(c0);
+        fetch(c + 2 * QG_WAVES, c0);
+        if (c + QG_WAVES < nchunks) consume(c1);
+      }
+    } else {
+      // g >= 64.  The weight stream is what has to come from HBM, and a wave sees only a few dozen chunks:
+      // to keep enough bytes in flight it requests the packed words (and scale / zero) of QG_NB chunks at a
+      // time, one batch ahead of the batch being consumed; X (cache resident) is fetched one chunk ahead.
+      constexpr int QG_NB = 4;
+      struct Batch {
+        uint32_t w[QG_NB][BITS + 1];
+        float s[QG_NB], b[QG_NB];
+      };
+      auto chunk_of = [&](int bt, int q) { return wave + QG_WAVES * (bt * QG_NB + q); };
+      auto fetch_batch = [&](int bt, Batch& B) {
+#pragma unroll
+        for (int q = 0; q < QG_NB; ++q) {
+          const int c = chunk_of(bt, q);
+          const int krun = (c < nchunks ? c : nchunks - 1) * 64 + lh * 32;
+#pragma unroll
+          for (int v = 0; v < BITS; ++v) B.w[q][v] = wrow[(krun / 32) * BITS + v];
+          B.w[q][BITS] = 0;
+          B.s[q] = srow[krun / g];
+          B.b[q] = brow[krun / g];
+        }
+      };
+      auto fetch_x = [&](int c, Chunk& ck) {
+        const int krun = (c < nchunks ? c : nchunks - 1) * 64 + lh * 32;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          ck.xa[m] = *reinterpret_cast<const uint4*>(xa + krun + 8 * m);
+          if (two_blocks) ck.xb[m] = *reinterpret_cast<const uint4*>(xb + krun + 8 * m);
+        }
+      };
+      auto consume_batch = [&](int bt, const Batch& B) {
+        Chunk cx[2];
+        fetch_x(chunk_of(bt, 0), cx[0]);
+#pragma unroll
+        for (int q = 0; q < QG_NB; ++q) {
+          if (q + 1 < QG_NB) fetch_x(chunk_of(bt, q + 1), cx[(q + 1) & 1]);
+          if (chunk_of(bt, q) < nchunks) {  // wave-uniform
+            Chunk& ck = cx[q & 1];
+#pragma unroll
+            for (int v = 0; v <= BITS; ++v) ck.w[v] = B.w[q][v];
+            ck.s[0] = B.s[q];
+            ck.b[0] = B.b[q];
+            consume(ck);
+          }
+        }
+      };
+      const int nbatches = (nchunks + QG_WAVES * QG_NB - 1) / (QG_WAVES * QG_NB);
+      Batch b0, b1;
+      fetch_batch(0, b0);
+      for (int bt = 0; bt < nbatches; bt += 2) {
+        fetch_batch(bt + 1, b1);
+        consume_batch(bt, b0);
+        fetch_batch(bt + 2, b0);
+        if (bt + 1 < nbatches) consume_batch(bt + 1, b1);
       }
     }
 
-    // accumulator: lane = token (second operand's index), register e = weight row 8 (e/4) + 4 (lane/32) + e%4
+    // accumulator: lane = weight row (second operand's index), register e = token 8 (e/4) + 4 (lane/32) + e%4
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) red[wave][tb][e][lane] = acc[tb][e];
     __syncthreads();
-    if (wave < 2) {  // wave 0 finishes token block 0, wave 1 token block 1
-      const int t = t0 + wave * 32 + l32;
+    if (wave < 2 && (wave == 0 || two_blocks)) {  // wave 0 finishes token block 0, wave 1 token block 1
 #pragma unroll
-      for (int eg = 0; eg < 4; ++eg) {
-        float v[4];
+      for (int e = 0; e < 16; ++e) {
+        float v = 0.f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          v[e] = (red[0][wave][4 * eg + e][lane] + red[1][wave][4 * eg + e][lane]) +
-                 (red[2][wave][4 * eg + e][lane] + red[3][wave][4 * eg + e][lane]);
-        const int prow = blockIdx.x * 32 + 8 * eg + 4 * lh;
-        if (t < T && prow < o) store4(Y + (int64_t)t * o + prow, v);
+        for (int q = 0; q < QG_WAVES; ++q) v += red[q][wave][e][lane];
+        const int t = t0 + wave * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+        if (t < T && p_ok) Y[(int64_t)t * o + p] = f32_to_bf16(v);
       }
     }
     __syncthreads();
@@ -141,13 +287,20 @@ bool qgemm_supported(const LayerDims& d) { return (d.bits == 2 || d.bits == 3 ||
 void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, const float* scale, const float* zero,
                   bf16_t* Y, hipStream_t stream) {
   dim3 grid((unsigned)((d.o + 31) / 32));
-#define L4Q_QGEMM(B)                                                                                              \
-  hipLaunchKernelGGL(qgemm_kernel<B>, grid, dim3(256), 0, stream, X, packed, scale, zero, Y, (int)d.T, (int)d.o, \
-                     (int)d.i, d.g, d.qn)
-  if (d.bits == 2) L4Q_QGEMM(2);
-  else if (d.bits == 3) L4Q_QGEMM(3);
-  else if (d.bits == 4) L4Q_QGEMM(4);
-  else L4Q_QGEMM(8);
+#define L4Q_QGEMM(B, N, F)                                                                                  \
+  hipLaunchKernelGGL((qgemm_kernel<B, N, F>), grid, dim3(QG_WAVES * 64), 0, stream, X, packed, scale, zero, Y, \
+                     (int)d.T, (int)d.o, (int)d.i, d.g, d.qn)
+#define L4Q_QGEMM_B(B)                                  \
+  do {                                                  \
+    if (d.g < 64) L4Q_QGEMM(B, 1, true);                \
+    else if (d.T <= 32) L4Q_QGEMM(B, 1, false);         \
+    else L4Q_QGEMM(B, 2, false);                        \
+  } while (0)
+  if (d.bits == 2) L4Q_QGEMM_B(2);
+  else if (d.bits == 3) L4Q_QGEMM_B(3);
+  else if (d.bits == 4) L4Q_QGEMM_B(4);
+  else L4Q_QGEMM_B(8);
+#undef L4Q_QGEMM_B
 #undef L4Q_QGEMM
 }
 
