@@ -168,6 +168,28 @@ int l4q_quant_errors(const l4q_desc* desc, const void* W0, const void* A, const 
                      const float* scale, const float* zero, float* errors,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* One AdamW step (decoupled weight decay; App. C: weight decay 0.01) on the layer's four trainable tensors.
+ *   m <- beta1 m + (1 - beta1) g;   v <- beta2 v + (1 - beta2) g^2
+ *   p <- p - lr wd p - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * A32 [r,i], B32 [o,r], scale, zero [o,G]: binary32 master parameters, updated in place; dA .. dzero: their
+ * gradients (what l4q_backward writes); m, v: moments, r*i + o*r + 2*o*G floats each, laid out
+ * [A | B | scale | zero].  A_copy / B_copy (BF16 descriptors only, may be NULL): bfloat16 copies of the new A and
+ * B for the next forward.  The paper fixes neither betas nor eps; common values are 0.9, 0.999, 1e-8.
+ * `step` counts from 1.  `tokens` is ignored.  Arithmetic is binary32. */
+typedef struct l4q_adamw {
+  float lr, beta1, beta2, eps, weight_decay;
+  int32_t step;
+} l4q_adamw;
+int l4q_adamw_step(const l4q_desc* desc, const l4q_adamw* hp,
+                   float* A32, float* B32, float* scale, float* zero,
+                   const float* dA, const float* dB, const float* dscale, const float* dzero,
+                   float* m, float* v, void* A_copy, void* B_copy, void* hip_stream);
+
+/* Learning rate of 0-based `step` (host function): linear warm-up lr_max (step + 1) / W over the first
+ * W = ceil(warmup_fraction * total_steps) steps, then half a cosine from lr_max to 0 at total_steps
+ * (App. C: cosine decay with linear warm-up through 10 % of the steps; the end value is this file's reading). */
+float l4q_cosine_lr(int64_t step, int64_t total_steps, double lr_max, double warmup_fraction);
+
 /* Opt-in timing of the bf16 GEMM launches, for benchmarks (not for use under graph capture:
  * it creates HIP events).  While enabled, every GEMM the library enqueues is bracketed by two
  * events recorded on the caller's stream.  This switch and its event list are the library's only

@@ -18,13 +18,18 @@ FLAG_UNFUSED_BACKWARD = 1
 INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
-            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward"]
+            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward", "l4q_adamw_step", "l4q_cosine_lr"]
 
 
 class L4QDesc(ctypes.Structure):
     _fields_ = [("tokens", ctypes.c_int64), ("in_features", ctypes.c_int64), ("out_features", ctypes.c_int64),
                 ("rank", ctypes.c_int32), ("bits", ctypes.c_int32), ("group_size", ctypes.c_int32),
                 ("alpha", ctypes.c_float), ("dtype", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+class L4QAdamW(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("step", ctypes.c_int32)]
 
 
 class L4QError(RuntimeError):
@@ -70,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.l4q_export_packed.argtypes = [dp, vp, vp, vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
     lib.l4q_quantized_forward.restype = ctypes.c_int
     lib.l4q_quantized_forward.argtypes = [dp, vp, vp, fp, fp, vp, vp]
+    lib.l4q_adamw_step.restype = ctypes.c_int
+    lib.l4q_adamw_step.argtypes = [dp, ctypes.POINTER(L4QAdamW)] + [fp] * 10 + [vp, vp, vp]
+    lib.l4q_cosine_lr.restype = ctypes.c_float
+    lib.l4q_cosine_lr.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_double, ctypes.c_double]
     lib.l4q_mfma_probe.restype = ctypes.c_int
     lib.l4q_mfma_probe.argtypes = [vp, ctypes.c_int, ctypes.c_int, fp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -148,6 +157,17 @@ def l4q_export_packed(desc: L4QDesc, W0, A, B, scale, zero, packed, workspace) -
 def l4q_quantized_forward(desc: L4QDesc, X, packed, scale, zero, Y) -> None:
     _check(load_library().l4q_quantized_forward(ctypes.byref(desc), _ptr(X), _ptr(packed), _ptr(scale), _ptr(zero),
                                                 _ptr(Y), _stream()), "l4q_quantized_forward")
+
+
+def l4q_adamw_step(desc: L4QDesc, hp: L4QAdamW, A32, B32, scale, zero, dA, dB, dscale, dzero, m, v,
+                   A_copy=None, B_copy=None) -> None:
+    _check(load_library().l4q_adamw_step(ctypes.byref(desc), ctypes.byref(hp), _ptr(A32), _ptr(B32), _ptr(scale),
+                                         _ptr(zero), _ptr(dA), _ptr(dB), _ptr(dscale), _ptr(dzero), _ptr(m), _ptr(v),
+                                         _ptr(A_copy), _ptr(B_copy), _stream()), "l4q_adamw_step")
+
+
+def l4q_cosine_lr(step: int, total_steps: int, lr_max: float, warmup_fraction: float = 0.1) -> float:
+    return float(load_library().l4q_cosine_lr(step, total_steps, lr_max, warmup_fraction))
 
 
 def l4q_profile_gemm(enable: bool) -> None:

@@ -4,6 +4,7 @@
 
 #include "l4q_kernels.h"
 
+#include <cmath>
 #include <mutex>
 #include <utility>
 #include <vector>
@@ -416,6 +417,41 @@ int l4q_quant_errors(const l4q_desc* desc, const void* W0, const void* A, const 
     l4q::launch_quant_errors<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero,
                                     (float*)workspace, errors, stream);
   return launch_status();
+}
+
+int l4q_adamw_step(const l4q_desc* desc, const l4q_adamw* hp, float* A32, float* B32, float* scale, float* zero,
+                   const float* dA, const float* dB, const float* dscale, const float* dzero, float* m, float* v,
+                   void* A_copy, void* B_copy, void* hip_stream) {
+  const int st = check_desc(desc, false);
+  if (st != L4Q_OK) return st;
+  if (!hp || !A32 || !B32 || !scale || !zero || !dA || !dB || !dscale || !dzero || !m || !v) return L4Q_ERR_NULL;
+  if (hp->step < 1 || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f)) return L4Q_ERR_SHAPE;
+  if ((A_copy || B_copy) && desc->dtype != L4Q_DTYPE_BF16) return L4Q_ERR_DTYPE;
+  const void* ptrs[] = {A32, B32, scale, zero, dA, dB, dscale, dzero, m, v, A_copy, B_copy};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  const LayerDims d = dims_of(desc);
+  l4q::AdamwArgs a;
+  a.param[0] = A32; a.param[1] = B32; a.param[2] = scale; a.param[3] = zero;
+  a.grad[0] = dA; a.grad[1] = dB; a.grad[2] = dscale; a.grad[3] = dzero;
+  a.n[0] = (int64_t)d.r * d.i; a.n[1] = d.o * d.r; a.n[2] = d.o * d.G(); a.n[3] = d.o * d.G();
+  a.m = m; a.v = v;
+  a.copy_bf16[0] = static_cast<bf16_t*>(A_copy); a.copy_bf16[1] = static_cast<bf16_t*>(B_copy);
+  a.lr = hp->lr; a.beta1 = hp->beta1; a.beta2 = hp->beta2; a.eps = hp->eps; a.weight_decay = hp->weight_decay;
+  a.bias1 = (float)(1.0 - std::pow((double)hp->beta1, (double)hp->step));
+  a.bias2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
+  (void)hipGetLastError();
+  l4q::launch_adamw(a, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
+float l4q_cosine_lr(int64_t step, int64_t total_steps, double lr_max, double warmup_fraction) {
+  if (total_steps <= 0 || step < 0) return 0.f;
+  const int64_t w = (int64_t)std::ceil(warmup_fraction * (double)total_steps);
+  if (step < w) return (float)(lr_max * (double)(step + 1) / (double)w);
+  if (step >= total_steps) return 0.f;
+  const double pi = 3.14159265358979323846;
+  return (float)(lr_max * 0.5 * (1.0 + std::cos(pi * (double)(step - w) / (double)(total_steps - w))));
 }
 
 int l4q_mfma_probe(const void* data, int iterations, int workgroups, float* sink, double* flops, void* hip_stream) {

@@ -86,6 +86,19 @@ void launch_dA(const LayerDims& d, const T* B, const float* dWp, float* partial,
 void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, float scale, float* out,
                             hipStream_t stream);
 
+// ---- AdamW step (App. C) on the four trainable tensors, in the order A, B, scale, zero ----
+struct AdamwArgs {
+  float* param[4];        // binary32 master parameters, updated in place
+  const float* grad[4];
+  int64_t n[4];
+  float* m;               // first / second moments, concatenated in the same order
+  float* v;
+  bf16_t* copy_bf16[2];   // optional bfloat16 copies of the new A and B (null: none)
+  float lr, beta1, beta2, eps, weight_decay;
+  float bias1, bias2;     // 1 - beta1^t, 1 - beta2^t
+};
+void launch_adamw(const AdamwArgs& a, hipStream_t stream);
+
 // ---- fully quantized layer: bit-packing of int8 codes [o,i] (i % 32 == 0) and Y = X . dequant(packed)^T ----
 void launch_pack_codes(const int8_t* codes, int64_t o, int64_t i, int bits, uint32_t* packed, hipStream_t stream);
 bool qgemm_supported(const LayerDims& d);

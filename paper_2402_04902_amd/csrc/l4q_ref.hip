@@ -219,6 +219,34 @@ void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* out
                      na, outa, pb, nbb, nb, outb, scale, blocks_a);
 }
 
+// ------------------------------------------------------------------ AdamW step on {A, B, scale, zero}
+// One launch over the concatenation [A | B | scale | zero]; the moments m, v are stored in that order.
+__global__ __launch_bounds__(256) void adamw_kernel(AdamwArgs a) {
+  const int64_t n = a.n[0] + a.n[1] + a.n[2] + a.n[3];
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n; e += (int64_t)gridDim.x * 256) {
+    int t = 0;
+    int64_t k = e;
+    while (k >= a.n[t]) { k -= a.n[t]; ++t; }
+    const float g = a.grad[t][k];
+    float p = a.param[t][k];
+    const float m = a.beta1 * a.m[e] + (1.f - a.beta1) * g;
+    const float v = a.beta2 * a.v[e] + (1.f - a.beta2) * g * g;
+    a.m[e] = m;
+    a.v[e] = v;
+    const float mhat = m / a.bias1, vhat = v / a.bias2;
+    p = p - a.lr * a.weight_decay * p - a.lr * mhat / (sqrtf(vhat) + a.eps);
+    a.param[t][k] = p;
+    if (t < 2 && a.copy_bf16[t]) a.copy_bf16[t][k] = f32_to_bf16(p);
+  }
+}
+
+void launch_adamw(const AdamwArgs& a, hipStream_t stream) {
+  const int64_t n = a.n[0] + a.n[1] + a.n[2] + a.n[3];
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+}
+
 void launch_sgemm(const float* A, int64_t a_rs, int64_t a_cs, const float* B, int64_t b_rs, int64_t b_cs,
                   float* C, int64_t ldc, int64_t M, int64_t N, int64_t K, float scale, hipStream_t stream) {
   dim3 grid((unsigned)((N + SG_BN - 1) / SG_BN), (unsigned)((M + SG_BM - 1) / SG_BM));
