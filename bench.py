@@ -23,7 +23,7 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # HBM-side bytes per GEMM launch (mean over the 4 plain + 2 fused launches of a step) from the
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/l4q_layer__llama7b_mlp_T4096.md
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = (4 * (565e6 + 62e6) + 2 * (717e6 + 38e6)) / 6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = (2 * (588e6 + 91e6) + 2 * (543e6 + 34e6) + 2 * (718e6 + 39e6)) / 6
 
 
 def cpu_baseline(specs, host_inputs):
@@ -171,7 +171,7 @@ def main() -> int:
                    "activation_bytes_kept_fwd_to_bwd": kept, "plain_lora_would_keep": lora_kept,
                    "workspace_bytes_fwd": max(l.fwd_bytes for l in layers),
                    "workspace_bytes_bwd": max(l.bwd_bytes for l in layers)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_kernel", "achieved": gemm_tflops,
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_nt_fast_kernel (+ dw_fused_kernel main loop)", "achieved": gemm_tflops,
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "launches": gemm_launches,
                      "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
