@@ -34,6 +34,37 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* 
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
   gemm::mainloop<T, A_KM, B_KM>(A, lda, B, ldb, M, N, K, m0, n0, lds, acc);
+  // bf16 output through LDS (free after the main loop): a lane holds 4 consecutive columns of 64 different
+  // rows, which as direct stores are 16-byte pieces of 32 cache lines per instruction.  Each wave instead
+  // parks its 128 x 128 block in its own LDS region (rows padded to 272 bytes) and writes it out as 16 bytes
+  // per lane, 16 lanes per 256-byte row segment.  Needs 16-byte aligned rows: ldc % 8 == 0 and N % 8 == 0.
+  constexpr int EP_ROW = T::WTN * 2 + 16;
+  constexpr bool EP_FITS = OUT_BF16 && T::WTN == 128 && 4 * T::WTM * EP_ROW <= T::LDS_BYTES;
+  if (EP_FITS && (ldc & 7) == 0 && (N & 7) == 0) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    unsigned char* region = lds + wave * (T::WTM * EP_ROW);
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+      for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+        for (int eg = 0; eg < 4; ++eg) {
+          uint2 v;
+          v.x = pack_bf16x2(acc.v[a][b][4 * eg], acc.v[a][b][4 * eg + 1]);
+          v.y = pack_bf16x2(acc.v[a][b][4 * eg + 2], acc.v[a][b][4 * eg + 3]);
+          *reinterpret_cast<uint2*>(region + (a * 32 + (lane & 31)) * EP_ROW + (b * 32 + 8 * eg + 4 * (lane >> 5)) * 2) = v;
+        }
+    bf16_t* C = reinterpret_cast<bf16_t*>(Cout);
+    const int mw = m0 + (wave >> 1) * T::WTM, nw = n0 + (wave & 1) * T::WTN + (lane & 15) * 8;
+#pragma unroll 8
+    for (int it = 0; it < T::WTM / 4; ++it) {
+      const int row = it * 4 + (lane >> 4);
+      const uint4 v = *reinterpret_cast<const uint4*>(region + row * EP_ROW + (lane & 15) * 16);
+      if (mw + row < M && nw < N) *reinterpret_cast<uint4*>(C + (int64_t)(mw + row) * ldc + nw) = v;
+    }
+    return;
+  }
 #pragma unroll
   for (int a = 0; a < T::TM; ++a) {
 #pragma unroll
@@ -102,7 +133,7 @@ double launch_mfma_probe(const bf16_t* data, int iterations, int workgroups, flo
 
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
                          int64_t K, bf16_t* C, int64_t ldc, hipStream_t stream) {
-  typedef gemm::Tile<256, 256, 32, 4> F;
+  typedef gemm::Tile<256, 256, 32, 5, true> F;  // K-contiguous operands: stages loaded in cache-line pairs
   const int tiles_m = (int)((M + F::BM - 1) / F::BM), tiles_n = (int)((N + F::BN - 1) / F::BN);
   hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false>), dim3((unsigned)(tiles_m * tiles_n)),
                      dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (void*)C, ldc, tiles_m, tiles_n);

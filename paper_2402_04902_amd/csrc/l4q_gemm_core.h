@@ -65,9 +65,10 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
   tn = rem / gsz;
 }
 
-template <int BM_, int BN_, int BK_, int NS_>
+template <int BM_, int BN_, int BK_, int NS_, bool PAIR_ = false>
 struct Tile {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_;
+  static constexpr bool PAIR = PAIR_;                 // stages are loaded two at a time (see mainloop)
   static constexpr int NT = 256;                      // 4 wavefronts, 2 x 2
   static constexpr int WTM = BM / 2, WTN = BN / 2;    // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;  // 32 x 32 accumulator tiles per wave
@@ -88,6 +89,7 @@ struct Tile {
   static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-steps");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   static_assert(NS >= 3, "the last part of a stage's loads is issued after the wait for the next stage");
+  static_assert(!PAIR || (BK == 32 && NS == 5), "paired loading: 64-byte LDS rows, ring of five stages");
 };
 
 template <class T>
@@ -238,64 +240,173 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
   constexpr int NDB = T::TN * (B_KM ? 2 : 1);
   constexpr int NMF = T::TM * T::TN;
   constexpr int EXTRA = NDA + NDB + LPK > NMF ? NDA + NDB + LPK - NMF : 0;  // reads that share a matrix op
-  static_assert(2 * EXTRA <= NDA, "too many LDS reads per matrix op");
+  static_assert(2 * EXTRA <= NDA + NDB, "too many LDS reads per matrix op");
+  if constexpr (T::PAIR) {
+    // Paired loading for K-contiguous operands.  A stage takes 64 bytes of every operand row, half a 128-byte
+    // cache line; when the second half is requested a stage later the line has already left the 32 KiB vector
+    // cache, and the L2 delivers every line twice (measured: twice the read sectors of a 64-k stage).  Here the
+    // two stages that share a line, 2 j and 2 j + 1, are requested by back-to-back instructions, so the second
+    // request meets the line while it is still being filled.  Ring of five stages: while stage s (even) and
+    // s + 1 are consumed, pair (s + 2, s + 3) has landed or is landing, and pair (s + 4, s + 5) is issued during
+    // stage s + 1 into the slots that stages s - 1 and s vacated.  Each pair is therefore issued two full stages
+    // before its first use.  An odd stage count is rounded up: the extra stage is loaded as zeros.
+    static_assert(!T::PAIR || (!A_KM && !B_KM && T::KK == 2), "paired loading is for K-contiguous operands");
+    auto issue_pair = [&](int stage0, int slot0, int slot1, int part) {
+      const unsigned k0 = stage0 < nk ? (unsigned)stage0 * stage_bytes_a : PAST_END_OFFSET;
+      const unsigned k1 = stage0 + 1 < nk ? (unsigned)(stage0 + 1) * stage_bytes_a : PAST_END_OFFSET;
+      unsigned char* base0 = lds + slot0 * T::STAGE;
+      unsigned char* base1 = lds + slot1 * T::STAGE;
+      if (part == 0) {
 #pragma unroll
-  for (int s = 0; s < T::D; ++s) issue_loads(s, s, nk, 0, 1);
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-  __builtin_amdgcn_s_barrier();
-  read_frags_a(0, 0, 0);
-  read_frags_b(0, 0, 0);
-
-  // Steady state.  Per k-step: the LDS reads of the next k-step, 1/KK of the global loads for stage
-  // s + D (stages past the end get an out-of-range offset: no memory traffic, and the vmcnt arithmetic
-  // stays uniform), and TM x TN matrix ops, interleaved so that the other two kinds issue in the
-  // shadow of the matrix pipeline and the global loads of the four waves do not arrive in one burst.
-  // Program order is A reads, DMA loads, B reads: the DMA loads write LDS, so the compiler keeps
-  // them behind the reads before them and ahead of the reads after them.
-  int slot = 0;
-  for (int s = 0; s < nk; ++s) {
-    int pslot = slot + T::D;
-    if (pslot >= T::NS) pslot -= T::NS;
-    int nslot = slot + 1;
-    if (nslot == T::NS) nslot = 0;
+        for (int c = 0; c < T::A_INSTR; ++c) {
+          const int o = (wave * T::A_INSTR + c) * 1024;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base0 + o), 16, voffA[c] + k0, 0, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base1 + o), 16, voffA[c] + k1, 0, 0, 0);
+        }
+      } else {
 #pragma unroll
-    for (int kk = 0; kk < T::KK; ++kk) {
-      const bool last = kk + 1 == T::KK;
-      if (last) {
-        // Stage s + 1 must have landed for every wave: all but the loads of stages s + 2 .. s + D issued
-        // so far, i.e. (D - 2) whole stages plus this stage's first KK - 1 parts, may still be in flight.
-        // All of this wave's LDS reads have returned, so the slot refilled next is free once every wave is here.
-        __builtin_amdgcn_s_waitcnt(waitcnt_vm((T::D - 2) * LOADS + (T::KK - 1) * LPK));
-        __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
-        __builtin_amdgcn_s_barrier();
+        for (int c = 0; c < T::B_INSTR; ++c) {
+          const int o = T::A_BYTES + (wave * T::B_INSTR + c) * 1024;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)(base0 + o), 16, voffB[c] + k0, 0, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcB, (lds_ptr_t)(base1 + o), 16, voffB[c] + k1, 0, 0, 0);
+        }
       }
-      // after the last stage the reads below fetch stale LDS; the values are never used
-      read_frags_a(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
-      issue_loads(s + T::D, pslot, nk, kk, T::KK);
-      read_frags_b(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
-      mfma_block(kk & 1);
+    };
+    constexpr int PAIR_A = 2 * T::A_INSTR, PAIR_B = 2 * T::B_INSTR;  // loads of a pair's two parts
+    issue_pair(0, 0, 1, 0);
+    issue_pair(0, 0, 1, 1);
+    issue_pair(2, 2, 3, 0);
+    issue_pair(2, 2, 3, 1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(PAIR_A + PAIR_B));  // the first pair has landed
+    __builtin_amdgcn_s_barrier();
+    read_frags_a(0, 0, 0);
+    read_frags_b(0, 0, 0);
+    const int nk2 = (nk + 1) & ~1;
+    int slot = 0;
+    for (int s = 0; s < nk2; s += 2) {
+      int n1 = slot + 1;
+      if (n1 == T::NS) n1 = 0;
+      int n2 = n1 + 1;
+      if (n2 == T::NS) n2 = 0;
+      int p0 = slot + 4;
+      if (p0 >= T::NS) p0 -= T::NS;
+      // even stage: no loads.  Its partner stage landed together with it.
+      read_frags_a(slot, 1, 1);
+      read_frags_b(slot, 1, 1);
+      mfma_block(0);
 #pragma unroll
-      for (int q = 0; q < EXTRA; ++q) {  // where reads outnumber matrix ops, two reads per matrix op
+      for (int q = 0; q < NDA + NDB; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x008, NMF - NDA - NDB, 0);
+      __builtin_amdgcn_sched_barrier(0);  // the matrix ops above stay ahead of the wait: they cover the LDS latency
+      __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+      __builtin_amdgcn_s_barrier();  // every wave is done reading `slot`: the pair issued below may refill it
+      read_frags_a(n1, 0, 0);
+      read_frags_b(n1, 0, 0);
+      mfma_block(1);
 #pragma unroll
-      for (int q = 0; q < NDA - 2 * EXTRA; ++q) {
+      for (int q = 0; q < NDA + NDB; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, NMF - NDA - NDB, 0);  // the rest stay on this side of the barrier
+      // odd stage: issues the pair (s + 4, s + 5) into the slots of stages s - 1 and s
+      read_frags_a(n1, 1, 1);
+      read_frags_b(n1, 1, 1);
+      issue_pair(s + 4, p0, slot, 0);
+      mfma_block(0);
+#pragma unroll
+      for (int q = 0; q < NDA + NDB; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
 #pragma unroll
-      for (int q = 0; q < LPK; ++q) {
+      for (int q = 0; q < PAIR_A; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       }
+      // pair (s + 2, s + 3) was issued a stage and a half ago; only this stage's first part may still be in flight
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm(PAIR_A));
+      __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+      __builtin_amdgcn_s_barrier();
+      read_frags_a(n2, 0, 0);
+      read_frags_b(n2, 0, 0);
+      issue_pair(s + 4, p0, slot, 1);
+      mfma_block(1);
 #pragma unroll
-      for (int q = 0; q < NDB; ++q) {
+      for (int q = 0; q < NDA + NDB; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
+#pragma unroll
+      for (int q = 0; q < PAIR_B; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+      slot = n2;
     }
-    slot = nslot;
+  } else {
+#pragma unroll
+    for (int s = 0; s < T::D; ++s) issue_loads(s, s, nk, 0, 1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    __builtin_amdgcn_s_barrier();
+    read_frags_a(0, 0, 0);
+    read_frags_b(0, 0, 0);
+
+    // Steady state.  Per k-step: the LDS reads of the next k-step, 1/KK of the global loads for stage
+    // s + D (stages past the end get an out-of-range offset: no memory traffic, and the vmcnt arithmetic
+    // stays uniform), and TM x TN matrix ops, interleaved so that the other two kinds issue in the
+    // shadow of the matrix pipeline and the global loads of the four waves do not arrive in one burst.
+    // The LDS reads come first and the matrix ops left over come last, so that the wait for the reads
+    // at the next stage boundary finds them complete.  Program order is reads, then DMA loads: the DMA
+    // loads write LDS and the compiler keeps them behind the reads before them.
+    constexpr int REST = NMF - (NDA + NDB - EXTRA + LPK);
+    static_assert(REST >= 0, "more LDS reads and loads than matrix ops to hide them behind");
+    int slot = 0;
+    for (int s = 0; s < nk; ++s) {
+      int pslot = slot + T::D;
+      if (pslot >= T::NS) pslot -= T::NS;
+      int nslot = slot + 1;
+      if (nslot == T::NS) nslot = 0;
+#pragma unroll
+      for (int kk = 0; kk < T::KK; ++kk) {
+        const bool last = kk + 1 == T::KK;
+        if (last) {
+          // Stage s + 1 must have landed for every wave: all but the loads of stages s + 2 .. s + D issued
+          // so far, i.e. (D - 2) whole stages plus this stage's first KK - 1 parts, may still be in flight.
+          // All of this wave's LDS reads have returned, so the slot refilled next is free once every wave is here.
+          __builtin_amdgcn_sched_barrier(0);  // the matrix ops of the previous k-step are issued before the wait
+          __builtin_amdgcn_s_waitcnt(waitcnt_vm((T::D - 2) * LOADS + (T::KK - 1) * LPK));
+          __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+          __builtin_amdgcn_s_barrier();
+        }
+        // after the last stage the reads below fetch stale LDS; the values are never used
+        read_frags_a(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
+        read_frags_b(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
+        issue_loads(s + T::D, pslot, nk, kk, T::KK);
+        mfma_block(kk & 1);
+#pragma unroll
+        for (int q = 0; q < EXTRA; ++q) {  // where reads outnumber matrix ops, two reads per matrix op
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NDA + NDB - 2 * EXTRA; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < LPK; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        if constexpr (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+      }
+      slot = nslot;
+    }
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
   __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
