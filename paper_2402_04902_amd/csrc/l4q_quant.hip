@@ -38,16 +38,54 @@ __device__ __forceinline__ void unpack4(const uint2& r, float (&v)[4]) {
 }
 
 // acc[rr][c] = sum_k B[pw + rr, k] * A[k, jc + c], k ascending, for the MQ_RPW rows of a wave and the 4 columns
-// of a lane.  Rows past o are clamped (their sums are never used); no lane may skip this call because
-// B is read through other lanes' registers.
+// of a lane.  Rows past o are clamped (their sums are never used).  A row of B is wave-uniform: where rows
+// start on a 4-byte boundary it is fetched with scalar loads and each B[p, k] reaches the multiply-add as a
+// scalar operand; otherwise lane k fetches it and it is read back with v_readlane (no lane may then skip this
+// call).  Steps past the rank multiply by zero, which leaves the running sum unchanged bit for bit.
+template <class T> struct BWord;
+template <> struct BWord<float> { static constexpr int PER = 1; };   // B values per 32-bit word
+template <> struct BWord<bf16_t> { static constexpr int PER = 2; };
+__device__ __forceinline__ float bword_value(const float*, uint32_t w, int) { return __uint_as_float(w); }
+__device__ __forceinline__ float bword_value(const bf16_t*, uint32_t w, int half) {
+  return __uint_as_float(half ? (w & 0xFFFF0000u) : (w << 16));
+}
+
 template <class T>
 __device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restrict__ A, const T* __restrict__ B,
                                           unsigned jc, int64_t pw, int lane, float (&acc)[MQ_RPW][4]) {
   typedef typename Raw4<T>::type raw4_t;
+  constexpr int PER = BWord<T>::PER;
 #pragma unroll
   for (int rr = 0; rr < MQ_RPW; ++rr)
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
+  if ((d.r % PER) == 0) {  // rows of B are whole 32-bit words: scalar path, any rank
+    const int nw = d.r / PER;
+    const uint32_t* Bw = reinterpret_cast<const uint32_t*>(B);
+    const uint32_t* brow[MQ_RPW];
+#pragma unroll
+    for (int rr = 0; rr < MQ_RPW; ++rr) brow[rr] = Bw + (pw + rr < d.o ? pw + rr : d.o - 1) * nw;
+    const T* ak = A + jc;
+#pragma unroll 2
+    for (int w = 0; w < nw; ++w) {
+      uint32_t bw[MQ_RPW];
+#pragma unroll
+      for (int rr = 0; rr < MQ_RPW; ++rr) bw[rr] = brow[rr][w];
+#pragma unroll
+      for (int h = 0; h < PER; ++h) {
+        float a[4];
+        unpack4(*reinterpret_cast<const raw4_t*>(ak), a);
+        ak += d.i;
+#pragma unroll
+        for (int rr = 0; rr < MQ_RPW; ++rr) {
+          const float bk = bword_value((const T*)nullptr, bw[rr], h);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[c]);
+        }
+      }
+    }
+    return;
+  }
   for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
     raw4_t araw[MQ_KC];
 #pragma unroll
@@ -55,7 +93,6 @@ __device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restric
       const int kc = k0 + k < d.r ? k0 + k : d.r - 1;
       araw[k] = *reinterpret_cast<const raw4_t*>((A + (int64_t)kc * d.i) + jc);
     }
-    // B[p, k0 + lane] for lanes 0..15 of each row; zero past the rank so those steps add nothing
     float brow[MQ_RPW];
 #pragma unroll
     for (int rr = 0; rr < MQ_RPW; ++rr) {
@@ -70,7 +107,6 @@ __device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restric
       unpack4(araw[k], a);
 #pragma unroll
       for (int rr = 0; rr < MQ_RPW; ++rr) {
-        // b = 0 past the rank: acc + 0 * a and fma(0, a, acc) leave the running sum unchanged bit for bit
         const float bk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(brow[rr]), k));
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[c]);
@@ -79,7 +115,25 @@ __device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restric
   }
 }
 
-template <class T>
+// Eq. quant / l4q_Wquant on one element, in the operation order of quantize_elem(); the clamp is one median
+// instruction and "in range" is "the clamp changed nothing" (the same decision for every non-NaN w).
+struct QuantFast {
+  float w, code;
+  bool in_range;
+};
+__device__ __forceinline__ QuantFast quantize_fast(float wc, float s, float b, float qn, float qp) {
+  QuantFast q;
+  q.w = __fdiv_rn(wc - b, s);
+  const float cl = __builtin_amdgcn_fmed3f(q.w, qn, qp);
+  q.code = rintf(cl);
+  q.in_range = cl == q.w;
+  return q;
+}
+
+// MODE 0: any combination of outputs.  MODE 1: the forward pass (dequantized Wq only).  MODE 2: the fused
+// backward pass (Wq^T and the d(Wq)/d(scale) factor only).  The specialisations drop the arithmetic of the
+// outputs they do not write; all three compute w, the code and the mask with the same instructions.
+template <class T, int MODE>
 __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims d, const T* __restrict__ W0,
                                                                        const T* __restrict__ A,
                                                                        const T* __restrict__ B,
@@ -87,7 +141,7 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
                                                                        const float* __restrict__ zero,
                                                                        MergeQuantOut<T> out) {
   typedef typename Raw4<T>::type raw4_t;
-  __shared__ __attribute__((aligned(16))) unsigned char tile[MQ_COLS * MQ_TROW];
+  __shared__ __attribute__((aligned(16))) unsigned char tile[MODE == 1 ? 16 : MQ_COLS * MQ_TROW];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t jblk = (int64_t)blockIdx.x * MQ_COLS;
@@ -98,6 +152,8 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
   const int64_t pw = (int64_t)blockIdx.y * MQ_ROWS + wave * MQ_RPW;    // first row of this wave
   const int64_t G = d.i / d.g;
   const unsigned q = jc / (unsigned)d.g;  // 4 consecutive columns lie in one group because g % 4 == 0
+  const float zero4[4] = {0.f, 0.f, 0.f, 0.f};
+  constexpr bool want_wq = MODE != 2, want_t = MODE != 1, want_f = MODE != 1, want_misc = MODE == 0;
 
   // row data, requested up front
   raw4_t w0raw[MQ_RPW];
@@ -114,7 +170,7 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
   float acc[MQ_RPW][4];
   lora_rows<T>(d, A, B, jc, pw, lane, acc);
 
-  uint32_t tpack[4][MQ_RPW / 2];  // Wq of (column c, row pair) as two bf16, for the transposed output
+  float wqkeep[want_t ? MQ_RPW : 1][4];  // dequantized values of all rows, for the transposed output
 #pragma unroll
   for (int rr = 0; rr < MQ_RPW; ++rr) {
     const int64_t p = pw + rr;
@@ -126,49 +182,58 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       wc[c] = w0[c] + d.gamma * acc[rr][c];
-      const QuantOut qo = quantize_elem(wc[c], s, b, d.qn, d.qp);
-      wqv[c] = ok ? dequant_elem(qo.code, s, b) : 0.f;
-      fg[c] = qo.in_range ? qo.code - qo.w : qo.code;
-      cpack |= ((uint32_t)(uint8_t)(int8_t)(int)qo.code) << (8 * c);
-      mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
+      const QuantFast qo = quantize_fast(wc[c], s, b, d.qn, d.qp);
+      wqv[c] = dequant_elem(qo.code, s, b);
+      if (want_f) fg[c] = qo.in_range ? qo.code - qo.w : qo.code;
+      if (want_misc) {
+        cpack |= ((uint32_t)(uint8_t)(int8_t)(int)qo.code) << (8 * c);
+        mpack |= (qo.in_range ? 1u : 0u) << (8 * c);
+      }
+      if (want_t) wqkeep[want_t ? rr : 0][c] = wqv[c];
     }
-    // the dequantized weight is zero-padded up to its leading dimension (k-step of the GEMM)
-    if (out.wq && p < d.o && j0 < out.ld_wq) store4((out.wq + p * out.ld_wq) + j32, wqv);
+    const int64_t rowoff = p * d.i;  // wave-uniform
+    if (want_wq && (MODE == 1 || out.wq) && p < d.o) {
+      // the dequantized weight is zero-padded up to its leading dimension (k-step of the GEMM)
+      if (col_ok) store4((out.wq + p * out.ld_wq) + j32, wqv);
+      else if (j0 < out.ld_wq) store4((out.wq + p * out.ld_wq) + j32, zero4);
+    }
     if (ok) {
-      const int64_t rowoff = p * d.i;  // wave-uniform
-      if (out.codes) *reinterpret_cast<uint32_t*>((out.codes + rowoff) + j32) = cpack;
-      if (out.mask) *reinterpret_cast<uint32_t*>((out.mask + rowoff) + j32) = mpack;
-      if (out.wcomb) store4((out.wcomb + rowoff) + j32, wc);
-      if (out.fgrad) {
+      if (want_misc) {
+        if (out.codes) *reinterpret_cast<uint32_t*>((out.codes + rowoff) + j32) = cpack;
+        if (out.mask) *reinterpret_cast<uint32_t*>((out.mask + rowoff) + j32) = mpack;
+        if (out.wcomb) store4((out.wcomb + rowoff) + j32, wc);
+      }
+      if (want_f && (MODE == 2 || out.fgrad)) {
         typedef _Float16 h4 __attribute__((ext_vector_type(4)));
         h4 h = {(_Float16)fg[0], (_Float16)fg[1], (_Float16)fg[2], (_Float16)fg[3]};
         *reinterpret_cast<h4*>((out.fgrad + rowoff) + j32) = h;
       }
     }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const uint32_t h = f32_to_bf16(wqv[c]);
-      if (rr & 1) tpack[c][rr >> 1] |= h << 16;
-      else tpack[c][rr >> 1] = h;
-    }
   }
 
-  if (out.wqT) {  // uniform: transpose the 64 x 256 tile through LDS, rows past o are zeros
+  if (want_t && (MODE == 2 || out.wqT)) {  // uniform: transpose the 64 x 256 tile through LDS
+    // column c of this lane, rows of this wave: 8 bf16 = one 16-byte LDS write
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
+      uint32_t tp[MQ_RPW / 2];
+#pragma unroll
+      for (int h = 0; h < MQ_RPW / 2; ++h) tp[h] = pack_bf16x2(wqkeep[want_t ? 2 * h : 0][c], wqkeep[want_t ? 2 * h + 1 : 0][c]);
       unsigned char* dst = tile + (lane * 4 + c) * MQ_TROW + wave * (MQ_RPW * 2);
-      *reinterpret_cast<uint4*>(dst) = make_uint4(tpack[c][0], tpack[c][1], tpack[c][2], tpack[c][3]);
+      *reinterpret_cast<uint4*>(dst) = make_uint4(tp[0], tp[1], tp[2], tp[3]);
     }
     __syncthreads();
+    // rows past o (o % 8 == 0 in bf16 mode, so whole 16-byte pieces) and the padding up to ld_wqT are zeros
     const int64_t pblk = (int64_t)blockIdx.y * MQ_ROWS;
 #pragma unroll
     for (int it = 0; it < MQ_COLS * 8 / MQ_THREADS; ++it) {
       const int idx = threadIdx.x + it * MQ_THREADS;
       const int jr = idx >> 3, ch = idx & 7;
       const int64_t j = jblk + jr, p = pblk + ch * 8;
-      if (j < d.i && p < out.ld_wqT)
-        *reinterpret_cast<uint4*>(out.wqT + j * out.ld_wqT + p) =
-            *reinterpret_cast<const uint4*>(tile + jr * MQ_TROW + ch * 16);
+      if (j < d.i && p < out.ld_wqT) {
+        uint4 v = *reinterpret_cast<const uint4*>(tile + jr * MQ_TROW + ch * 16);
+        if (p >= d.o) v = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4*>(out.wqT + j * out.ld_wqT + p) = v;
+      }
     }
   }
 }
@@ -364,7 +429,13 @@ void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B,
                         const float* zero, const MergeQuantOut<T>& out, hipStream_t stream) {
   const int64_t rows = out.wqT && out.ld_wqT > d.o ? out.ld_wqT : d.o;
   dim3 grid((unsigned)((d.i + MQ_COLS - 1) / MQ_COLS), (unsigned)((rows + MQ_ROWS - 1) / MQ_ROWS));
-  hipLaunchKernelGGL(merge_quant_tile_kernel<T>, grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, scale, zero, out);
+  const bool misc = out.codes || out.wcomb || out.mask;
+  if (out.wq && !out.wqT && !out.fgrad && !misc)
+    hipLaunchKernelGGL((merge_quant_tile_kernel<T, 1>), grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, scale, zero, out);
+  else if (!out.wq && out.wqT && out.fgrad && !misc)
+    hipLaunchKernelGGL((merge_quant_tile_kernel<T, 2>), grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, scale, zero, out);
+  else
+    hipLaunchKernelGGL((merge_quant_tile_kernel<T, 0>), grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, scale, zero, out);
 }
 
 void launch_transpose_lora_b(const bf16_t* B, int64_t o, int r, bf16_t* BT, int64_t ld, hipStream_t stream) {
