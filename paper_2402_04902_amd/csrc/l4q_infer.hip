@@ -274,6 +274,229 @@ __global__ __launch_bounds__(QG_WAVES * 64) void qgemm_kernel(const bf16_t* __re
 #endif
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Streaming form of the same product for the common layouts: bits in {4, 8}, rows of packed words a
+// whole number of 128-byte cache lines, group size a multiple of the codes of a sub-step.
+//
+// One workgroup = ROWS weight rows (32, or 16 for up to 16 tokens: the 16x16x32 matrix op then does the
+// same work in a quarter of the matrix-core time), 4 waves; the row's 128-byte stages go round-robin to
+// the waves and each wave runs a private pipeline, so there is no barrier until the final sum.  A stage
+// (ROWS rows x 128 bytes) travels HBM -> LDS with buffer_load ... lds instructions whose lanes read whole
+// cache lines (8 lanes per row) -- the per-lane row ownership of qgemm_kernel touches 32 lines for 32
+// bytes each instead.  LDS keeps the rows 128 bytes apart; the 16-byte chunk c of row r sits at position
+// c ^ ((r / 2) % 8), which makes the fragment reads (lane = row) conflict-free.  In sub-step h a lane of
+// lane group kg reads chunk KG h + kg of its row: 128 / bits codes = 16 / bits operand fragments, the
+// f-th of which is its 8 k-slots in the f-th matrix op of the sub-step.
+// Ring of 4 stages per wave: three stages are in flight while one is consumed.  X fragments and scale /
+// zero are fetched one stage ahead into registers; every load is issued in a fixed order so that one
+// partial s_waitcnt covers the stage.
+constexpr int QS_NSW = 4;             // ring stages per wave
+
+template <int ROWS> struct QsMfma;
+template <> struct QsMfma<32> {
+  typedef f32x16_t acc_t;
+  static constexpr int NACC = 16;
+  static __device__ __forceinline__ acc_t mma(bf16x8_t a, bf16x8_t b, acc_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  // token (row of D) held in register e by a lane of lane group kg
+  static __device__ __forceinline__ int token(int e, int kg) { return 8 * (e >> 2) + 4 * kg + (e & 3); }
+};
+template <> struct QsMfma<16> {
+  typedef float acc_t __attribute__((ext_vector_type(4)));
+  static constexpr int NACC = 4;
+  static __device__ __forceinline__ acc_t mma(bf16x8_t a, bf16x8_t b, acc_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int token(int e, int kg) { return 4 * kg + e; }
+};
+
+template <int BITS, int ROWS>
+__global__ __launch_bounds__(256, 2) void qgemm_stream_kernel(const bf16_t* __restrict__ X,
+                                                               const uint32_t* __restrict__ packed,
+                                                               const float* __restrict__ scale,
+                                                               const float* __restrict__ zero,
+                                                               bf16_t* __restrict__ Y, int T, int t0, int o, int i,
+                                                               int g) {
+  constexpr int STAGE = ROWS * 128;  // bytes of a stage
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[4 * QS_NSW * STAGE];
+#if defined(__HIP_DEVICE_COMPILE__)
+  static_assert(BITS == 4 || BITS == 8, "bits");
+  typedef QsMfma<ROWS> M;
+  typedef typename M::acc_t acc_t;
+  constexpr int NACC = M::NACC;
+  constexpr int KG = 64 / ROWS;    // lane groups of the matrix op (k-slot groups)
+  constexpr int NH = 8 / KG;       // sub-steps per stage
+  constexpr int NDMA = ROWS / 8;   // wave-wide loads per stage
+  constexpr int CH = 128 / BITS;   // codes per 16-byte chunk
+  constexpr int KS = 8 * CH;       // codes per stage
+  constexpr int FR = CH / 8;       // operand fragments per chunk
+  constexpr int SUB = KG * CH;     // codes per sub-step
+  constexpr int NXL = NH * FR + 2 * NH;  // register loads per stage: X fragments, scale and zero per sub-step
+  constexpr float K0 = BITS == 8 ? 0.f : 128.f + (float)(1 << (BITS - 1));
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef gemm::lds_ptr_t lds_ptr_t;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ln = lane % ROWS, kg = lane / ROWS;
+  const int p0 = blockIdx.x * ROWS;
+  const int p = p0 + ln;
+  const int pc = p < o ? p : o - 1;
+  const int rb = i / 8 * BITS;     // bytes of a packed row
+  const int nst = rb / 128;        // stages of a row
+  const int G = i / g;
+  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
+
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(packed), 0, (int)((int64_t)o * rb), 0x00020000);
+  unsigned voff[NDMA];
+#pragma unroll
+  for (int q = 0; q < NDMA; ++q) {
+    const int r = 8 * q + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+    voff[q] = p0 + r < o ? (unsigned)((p0 + r) * rb + chunk * 16) : gemm::OOB_OFFSET;
+  }
+  unsigned char* ring = lds + wave * (QS_NSW * STAGE);
+  const unsigned frag_row = ln * 128;
+  const int swz = (ln >> 1) & 7;
+  const int tok = t0 + ln < T ? t0 + ln : T - 1;
+  const bf16_t* xrow = X + (int64_t)tok * i;
+  const float* srow = scale + (int64_t)pc * G;
+  const float* brow = zero + (int64_t)pc * G;
+  const int nj = wave < nst ? (nst - wave + 3) / 4 : 0;  // stages of this wave: wave, wave + 4, ...
+
+  auto issue_dma = [&](int j) {  // stage j of this wave into ring slot j % QS_NSW; past the end: no traffic
+    const unsigned kb = j < nj ? (unsigned)(wave + 4 * j) * 128u : gemm::PAST_END_OFFSET;
+    unsigned char* dst = ring + (j % QS_NSW) * STAGE;
+#pragma unroll
+    for (int q = 0; q < NDMA; ++q)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(dst + q * 1024), 16, voff[q] + kb, 0, 0, 0);
+  };
+  struct StageRegs {
+    uint4 x[NH][FR];
+    float s[NH], b[NH];
+  };
+  auto fetch_regs = [&](int j, StageRegs& R) {  // clamped: a fetch past the end is never consumed
+    const int st = wave + 4 * (j < nj ? j : (nj > 0 ? nj - 1 : 0));
+    const int k0 = (st < nst ? st : nst - 1) * KS;
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+      for (int f = 0; f < FR; ++f)
+        R.x[h][f] = *reinterpret_cast<const uint4*>(xrow + k0 + (KG * h + kg) * CH + 8 * f);
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {  // scale / zero of the group each sub-step lies in
+      const int grp = (k0 + h * SUB) / g;
+      R.s[h] = srow[grp];
+      R.b[h] = brow[grp];
+    }
+  };
+
+  acc_t acc;
+#pragma unroll
+  for (int e = 0; e < NACC; ++e) acc[e] = 0.f;
+
+  auto consume = [&](int j, const StageRegs& R) {
+    const bool live = j < nj;
+    const unsigned char* src = ring + (j % QS_NSW) * STAGE + frag_row;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(src + (((KG * h + kg) ^ swz) << 4));
+      acc_t tw, tx;
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) { tw[e] = 0.f; tx[e] = 0.f; }
+#pragma unroll
+      for (int f = 0; f < FR; ++f) {
+        u32x4 d;
+        if (BITS == 4) {
+          // 8 codes.  Byte r holds codes 2r (low nibble) and 2r + 1; times 0x1001 puts a copy of the byte 12 bits
+          // up, so one mask leaves code 2r in bits 0..3 and code 2r + 1 in bits 16..19: a bf16 pair 128 + u.
+          const uint32_t v = w[f];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
+            uint32_t pair;  // (spread & mask) | bias in one instruction: one constant in a scalar, one in a vector register
+            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
+            d[r] = pair;
+          }
+        } else {
+          const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];  // 4 + 4 codes
+          d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
+          d[1] = pack_bf16x2((float)((v0 >> 16) & 0xFFu) - 128.f, (float)(v0 >> 24) - 128.f);
+          d[2] = pack_bf16x2((float)(v1 & 0xFFu) - 128.f, (float)((v1 >> 8) & 0xFFu) - 128.f);
+          d[3] = pack_bf16x2((float)((v1 >> 16) & 0xFFu) - 128.f, (float)(v1 >> 24) - 128.f);
+        }
+        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+        const bf16x8_t xf = __builtin_bit_cast(bf16x8_t, R.x[h][f]);  // tokens past T: clamped row, never stored
+        tw = M::mma(xf, wf, tw);
+        tx = M::mma(xf, ones, tx);
+      }
+      // the sub-step lies inside one group: sum_k X (w~ s + b) = s sum_k X (w~ + K0) + (b - K0 s) sum_k X.
+      // A stage past the end (the pipeline always runs an even number) gets scale = zero = 0: it adds nothing.
+      const float sc = live ? R.s[h] : 0.f, bz = live ? R.b[h] - K0 * sc : 0.f;
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) acc[e] = fmaf(bz, tx[e], fmaf(sc, tw[e], acc[e]));
+    }
+  };
+
+  // Issue order (every wave, every iteration): registers of stage j + 1, then the DMA of stage j + 3.  When
+  // stage j is consumed, what was issued after its own loads is DMA j + 2, registers j + 1 and DMA j + 3.
+  StageRegs r0, r1;
+  issue_dma(0);
+  issue_dma(1);
+  fetch_regs(0, r0);
+  issue_dma(2);
+  __builtin_amdgcn_sched_barrier(0);  // the scheduler keeps each phase where it is written
+  for (int j = 0; j < nj; j += 2) {
+    fetch_regs(j + 1, r1);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_dma(j + 3);
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(NDMA + NXL + NDMA));
+    __builtin_amdgcn_sched_barrier(0);
+    consume(j, r0);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_regs(j + 2, r0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_dma(j + 4);
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(NDMA + NXL + NDMA));
+    __builtin_amdgcn_sched_barrier(0);
+    consume(j + 1, r1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
+  __syncthreads();  // every wave is done with its ring: the LDS is reused for the sum over the waves
+
+  // accumulator: lane = weight row, register e = token M::token(e, kg)
+  float* red = reinterpret_cast<float*>(lds);
+#pragma unroll
+  for (int e = 0; e < NACC; ++e) red[(wave * NACC + e) * 64 + lane] = acc[e];
+  __syncthreads();
+  {  // wave w finishes registers NACC / 4 * w .. + NACC / 4 - 1
+#pragma unroll
+    for (int e4 = 0; e4 < NACC / 4; ++e4) {
+      const int e = wave * (NACC / 4) + e4;
+      const float v = (red[(0 * NACC + e) * 64 + lane] + red[(1 * NACC + e) * 64 + lane]) +
+                      (red[(2 * NACC + e) * 64 + lane] + red[(3 * NACC + e) * 64 + lane]);
+      const int t = t0 + M::token(e, kg);
+      if (t < T && p < o) Y[(int64_t)t * o + p] = f32_to_bf16(v);
+    }
+  }
+#endif
+}
+
+// rows per workgroup the streaming kernel can use for this layer (0: not at all)
+int qgemm_stream_rows(const LayerDims& d, int tokens_in_pass) {
+  if (d.bits != 4 && d.bits != 8) return 0;
+  const int64_t rb = d.i / 8 * d.bits;
+  if (d.i % 8 != 0 || rb % 128 != 0 || d.o * rb >= (1ll << 31)) return 0;
+  const int ch = 128 / d.bits;
+  if (tokens_in_pass <= 16 && d.g % (4 * ch) == 0) return 16;
+  if (d.g % (2 * ch) == 0) return 32;
+  return 0;
+}
+
 }  // namespace
 
 void launch_pack_codes(const int8_t* codes, int64_t o, int64_t i, int bits, uint32_t* packed, hipStream_t stream) {
@@ -287,6 +510,23 @@ bool qgemm_supported(const LayerDims& d) { return (d.bits == 2 || d.bits == 3 ||
 void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, const float* scale, const float* zero,
                   bf16_t* Y, hipStream_t stream) {
   dim3 grid((unsigned)((d.o + 31) / 32));
+  // more than 32 tokens: the general kernel reads the weights once per 64 tokens, the streaming form once per 32
+  if (qgemm_stream_rows(d, 32) != 0 && (d.T <= 32 || d.g < 64)) {
+    const int step = d.T <= 16 && qgemm_stream_rows(d, 16) == 16 ? 16 : 32;
+    for (int t0 = 0; t0 < d.T; t0 += step) {  // the weight stream is read once per pass
+      const int rows = qgemm_stream_rows(d, (int)d.T - t0 < step ? (int)d.T - t0 : step);
+      dim3 sgrid((unsigned)((d.o + rows - 1) / rows));
+#define L4Q_QS(B, R)                                                                                              \
+  hipLaunchKernelGGL((qgemm_stream_kernel<B, R>), sgrid, dim3(256), 0, stream, X, packed, scale, zero, Y, (int)d.T, \
+                     t0, (int)d.o, (int)d.i, d.g)
+      if (d.bits == 4 && rows == 16) L4Q_QS(4, 16);
+      else if (d.bits == 4) L4Q_QS(4, 32);
+      else if (rows == 16) L4Q_QS(8, 16);
+      else L4Q_QS(8, 32);
+#undef L4Q_QS
+    }
+    return;
+  }
 #define L4Q_QGEMM(B, N, F)                                                                                  \
   hipLaunchKernelGGL((qgemm_kernel<B, N, F>), grid, dim3(QG_WAVES * 64), 0, stream, X, packed, scale, zero, Y, \
                      (int)d.T, (int)d.o, (int)d.i, d.g, d.qn)

@@ -42,6 +42,11 @@ def test_packed_export_bit_exact(dtype, bits):
     (1, 256, 72, 4, 64), (7, 512, 264, 4, 128), (64, 1024, 520, 3, 64), (33, 256, 40, 2, 8), (100, 320 * 2, 96, 8, 32),
     (16, 4096, 11008, 4, 128),      # LLaMA-7B up projection at a decode batch
     (64, 11008, 4096, 4, 128),      # down projection
+    (1, 4096, 11008, 4, 128), (1, 11008, 4096, 4, 128),   # single-token decode, both projections
+    (17, 11008, 1000, 4, 64),       # odd stage count (43), 17 tokens -> 32-row tiles, ragged rows
+    (5, 640, 88, 8, 64), (40, 1280, 200, 8, 128),         # 8-bit streaming form, 16- and 32-row tiles
+    (16, 384, 48, 4, 128),          # packed rows not a whole number of cache lines -> general kernel
+    (3, 256, 8, 4, 128),            # one stage, a single partial row tile
 ])
 def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g):
     import torch
