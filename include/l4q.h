@@ -77,7 +77,12 @@ enum {
    * workspace in binary32, quantizer gradients in a separate pass).  Slower; exists so the
    * fused epilogue can be cross-checked and as the path for group sizes the fused kernel
    * does not cover. */
-  L4Q_FLAG_UNFUSED_BACKWARD = 1
+  L4Q_FLAG_UNFUSED_BACKWARD = 1,
+  /* l4q_backward adds dA, dB, dscale and dzero to what the output arrays hold instead of overwriting
+   * them (gradient accumulation over micro-batches; App. C trains with an effective batch of 128).
+   * dX is always overwritten.  Each call's own contribution is computed as without the flag and
+   * added with one binary32 addition per element.  Ignored by the other entry points. */
+  L4Q_FLAG_ACCUMULATE_GRADS = 2
 };
 
 /* Shape rules: tokens, in_features, out_features, rank >= 1; group_size >= 4, group_size % 4

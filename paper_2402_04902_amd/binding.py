@@ -15,6 +15,7 @@ from .inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libl4q.so")
 
 FLAG_UNFUSED_BACKWARD = 1
+FLAG_ACCUMULATE_GRADS = 2
 INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",

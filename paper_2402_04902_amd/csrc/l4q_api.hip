@@ -23,7 +23,7 @@ inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 int check_desc(const l4q_desc* d, bool need_tokens) {
   if (!d) return L4Q_ERR_NULL;
   if (d->dtype != L4Q_DTYPE_F32 && d->dtype != L4Q_DTYPE_BF16) return L4Q_ERR_DTYPE;
-  if (d->flags & ~(int32_t)L4Q_FLAG_UNFUSED_BACKWARD) return L4Q_ERR_DTYPE;
+  if (d->flags & ~(int32_t)(L4Q_FLAG_UNFUSED_BACKWARD | L4Q_FLAG_ACCUMULATE_GRADS)) return L4Q_ERR_DTYPE;
   if (d->bits < 2 || d->bits > 8) return L4Q_ERR_BITS;
   if (d->in_features < 1 || d->out_features < 1 || d->rank < 1 || d->rank > 256) return L4Q_ERR_SHAPE;
   if (need_tokens && d->tokens < 1) return L4Q_ERR_SHAPE;
@@ -52,6 +52,7 @@ LayerDims dims_of(const l4q_desc* d) {
   L.gamma = d->alpha / (float)d->rank;
   L.qn = -(float)(1 << (d->bits - 1));
   L.qp = (float)((1 << (d->bits - 1)) - 1);
+  L.accumulate = (d->flags & L4Q_FLAG_ACCUMULATE_GRADS) != 0;
   return L;
 }
 
@@ -275,7 +276,7 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
       l4q::launch_transpose_lora_b(Bb, d.o, d.r, w.bT, w.opad, stream);
       dw_fused(d, w, (const bf16_t*)dY, (const bf16_t*)X, Ab, dscale, dzero, stream);
       l4q::launch_reduce_two_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, dA, w.dB_part, 2 * w.tiles_n,
-                                      d.o * d.r, dB, d.gamma, stream);
+                                      d.o * d.r, dB, d.gamma, d.accumulate, stream);
     } else {
       l4q::launch_gemm_bf16_kmajor_f32((const bf16_t*)dY, d.o, (const bf16_t*)X, d.i, d.o, d.i, d.T, w.dwq, d.i, stream);
       l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);

@@ -53,6 +53,7 @@ struct FusedArgs {
   float* dA_part;                     // [tiles_m, r, i]
   float* dB_part;                     // [2 * tiles_n, o, r]
   int tiles_m, tiles_n;
+  int accumulate;                     // add dscale / dzero to what the outputs hold
 };
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
@@ -100,6 +101,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
   }
 
   const int G = p.i / p.g;
+  auto put = [&](float* dst, float v) { *dst = p.accumulate ? *dst + v : v; };  // each element has one writer
   float keep_ds[T::TM], keep_db[T::TM];  // g == 256: this wave's half of the group, per row block
   f32x16_t accB[T::TM];
 
@@ -146,8 +148,8 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
       for (int b = 0; b < T::TN; ++b) {
         const int q = (col0 + b * 32) / 32;
         if (lh == 0 && row_ok && q < G) {
-          p.dscale[(int64_t)row * G + q] = ds_b[b];
-          p.dzero[(int64_t)row * G + q] = db_b[b];
+          put(p.dscale + (int64_t)row * G + q, ds_b[b]);
+          put(p.dzero + (int64_t)row * G + q, db_b[b]);
         }
       }
     } else if (p.g == 64) {
@@ -155,8 +157,8 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
       for (int b = 0; b < T::TN; b += 2) {
         const int q = (col0 + b * 32) / 64;
         if (lh == 0 && row_ok && q < G) {
-          p.dscale[(int64_t)row * G + q] = ds_b[b] + ds_b[b + 1];
-          p.dzero[(int64_t)row * G + q] = db_b[b] + db_b[b + 1];
+          put(p.dscale + (int64_t)row * G + q, ds_b[b] + ds_b[b + 1]);
+          put(p.dzero + (int64_t)row * G + q, db_b[b] + db_b[b + 1]);
         }
       }
     } else {
@@ -167,8 +169,8 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
       if (p.g == 128) {
         const int q = col0 / 128;
         if (lh == 0 && row_ok && q < G) {
-          p.dscale[(int64_t)row * G + q] = ds;
-          p.dzero[(int64_t)row * G + q] = db;
+          put(p.dscale + (int64_t)row * G + q, ds);
+          put(p.dzero + (int64_t)row * G + q, db);
         }
       } else if (wn == 1 && lh == 0) {  // g == 256: hand the right half to the left wave
         float* sc = reinterpret_cast<float*>(lds + EP_TILE) + (wm * 128 + a * 32 + l32) * 2;
@@ -226,8 +228,8 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
       const int row = m0 + wm * 128 + a * 32 + l32;
       const float* sc = reinterpret_cast<const float*>(lds + EP_TILE) + (wm * 128 + a * 32 + l32) * 2;
       if (row < p.o && q < G) {
-        p.dscale[(int64_t)row * G + q] = keep_ds[a] + sc[0];
-        p.dzero[(int64_t)row * G + q] = keep_db[a] + sc[1];
+        put(p.dscale + (int64_t)row * G + q, keep_ds[a] + sc[0]);
+        put(p.dzero + (int64_t)row * G + q, keep_db[a] + sc[1]);
       }
     }
   }
@@ -289,6 +291,7 @@ void launch_dw_fused(const LayerDims& d, const bf16_t* dY, const bf16_t* X, cons
   p.fgrad = fgrad; p.A = A; p.BT = BT; p.ld_bt = ld_bt;
   p.dscale = dscale; p.dzero = dzero; p.dA_part = dA_part; p.dB_part = dB_part;
   dw_fused_tiles(d, &p.tiles_m, &p.tiles_n);
+  p.accumulate = d.accumulate ? 1 : 0;
   hipLaunchKernelGGL(dw_fused_kernel, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(T::NT), 0, stream, p);
 }
 

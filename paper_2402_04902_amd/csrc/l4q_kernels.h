@@ -15,6 +15,7 @@ struct LayerDims {
   int r, bits, g;
   float gamma;   // (float)alpha / (float)r
   float qn, qp;  // Q_N, Q_P as floats
+  bool accumulate = false;  // backward: add dA, dB, dscale, dzero to what the outputs hold instead of overwriting
   int64_t G() const { return i / g; }
 };
 
@@ -82,9 +83,9 @@ constexpr int kDaRowBlock = 128;
 template <class T>
 void launch_dA(const LayerDims& d, const T* B, const float* dWp, float* partial, float* dA, hipStream_t stream);
 
-// out[e] = scale * sum_b partial[b * n + e], b ascending (fixed summation order)
+// out[e] = scale * sum_b partial[b * n + e], b ascending (fixed summation order); accumulate: added to out[e]
 void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, float scale, float* out,
-                            hipStream_t stream);
+                            bool accumulate, hipStream_t stream);
 
 // ---- AdamW step (App. C) on the four trainable tensors, in the order A, B, scale, zero ----
 struct AdamwArgs {
@@ -107,7 +108,7 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
 
 // outa = scale * sum of nba partials of na elements, outb likewise, in one launch (na, nb multiples of 4)
 void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* outa, const float* pb, int nbb,
-                                int64_t nb, float* outb, float scale, hipStream_t stream);
+                                int64_t nb, float* outb, float scale, bool accumulate, hipStream_t stream);
 
 // ---- weight-gradient GEMM with fused quantizer backward (bf16 mode) ----
 // dY [T, o], X [T, i] as the caller holds them; fgrad [o, i] binary16 from launch_merge_quant;

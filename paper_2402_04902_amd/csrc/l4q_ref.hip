@@ -131,8 +131,8 @@ __global__ __launch_bounds__(256) void quant_grads_kernel(LayerDims d, const T* 
         const float db_sum = wave_sum_width(db, width);
         if (active && (lane & (width - 1)) == 0) {
           const int64_t q = j0 / d.g;
-          dscale[p * G + q] = ds_sum;
-          dzero[p * G + q] = db_sum;
+          dscale[p * G + q] = d.accumulate ? dscale[p * G + q] + ds_sum : ds_sum;
+          dzero[p * G + q] = d.accumulate ? dzero[p * G + q] + db_sum : db_sum;
         }
         ds = 0.f;
         db = 0.f;
@@ -141,7 +141,10 @@ __global__ __launch_bounds__(256) void quant_grads_kernel(LayerDims d, const T* 
 #pragma unroll
     for (int k = 0; k < QG_KCHUNK; ++k) {
       const float tot = wave_sum_width(dBacc[k], 64);
-      if (lane == 0 && k < kn) dB[p * d.r + k0 + k] = d.gamma * tot;
+      if (lane == 0 && k < kn) {
+        const float v = d.gamma * tot;
+        dB[p * d.r + k0 + k] = d.accumulate ? dB[p * d.r + k0 + k] + v : v;
+      }
     }
   }
 }
@@ -177,18 +180,19 @@ __global__ __launch_bounds__(256) void dA_partial_kernel(LayerDims d, const T* _
 
 // pass 2 (also used by the fused backward): out[e] = scale * sum_b partial[b * n + e], b ascending
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int64_t nblocks,
-                                                               int64_t n, float scale, float* __restrict__ out) {
+                                                               int64_t n, float scale, float* __restrict__ out,
+                                                               bool accumulate) {
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (e >= n) return;
   float acc = 0.f;
   for (int64_t b = 0; b < nblocks; ++b) acc += partial[b * n + e];
-  out[e] = scale * acc;
+  out[e] = accumulate ? out[e] + scale * acc : scale * acc;
 }
 
 void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, float scale, float* out,
-                            hipStream_t stream) {
+                            bool accumulate, hipStream_t stream) {
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, partial,
-                     nblocks, n, scale, out);
+                     nblocks, n, scale, out, accumulate);
 }
 
 // Both reductions of the fused backward in one launch; 4 consecutive elements per thread (n % 4 == 0).
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(256) void reduce_two_partials_kernel(const float* _
                                                                    float* __restrict__ outa,
                                                                    const float* __restrict__ pb, int nbb, int64_t nb,
                                                                    float* __restrict__ outb, float scale,
-                                                                   int blocks_a) {
+                                                                   int blocks_a, bool accumulate) {
   const bool second = (int)blockIdx.x >= blocks_a;
   const float* __restrict__ part = second ? pb : pa;
   float* __restrict__ out = second ? outb : outa;
@@ -209,14 +213,19 @@ __global__ __launch_bounds__(256) void reduce_two_partials_kernel(const float* _
     const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)b * n + e);
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
   }
-  *reinterpret_cast<float4*>(out + e) = make_float4(scale * acc.x, scale * acc.y, scale * acc.z, scale * acc.w);
+  float4 r = make_float4(scale * acc.x, scale * acc.y, scale * acc.z, scale * acc.w);
+  if (accumulate) {
+    const float4 old = *reinterpret_cast<const float4*>(out + e);
+    r = make_float4(old.x + r.x, old.y + r.y, old.z + r.z, old.w + r.w);
+  }
+  *reinterpret_cast<float4*>(out + e) = r;
 }
 
 void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* outa, const float* pb, int nbb,
-                                int64_t nb, float* outb, float scale, hipStream_t stream) {
+                                int64_t nb, float* outb, float scale, bool accumulate, hipStream_t stream) {
   const int blocks_a = (int)((na / 4 + 255) / 256), blocks_b = (int)((nb / 4 + 255) / 256);
   hipLaunchKernelGGL(reduce_two_partials_kernel, dim3((unsigned)(blocks_a + blocks_b)), dim3(256), 0, stream, pa, nba,
-                     na, outa, pb, nbb, nb, outb, scale, blocks_a);
+                     na, outa, pb, nbb, nb, outb, scale, blocks_a, accumulate);
 }
 
 // ------------------------------------------------------------------ AdamW step on {A, B, scale, zero}
@@ -269,7 +278,7 @@ void launch_dA(const LayerDims& d, const T* B, const float* dWp, float* partial,
   hipLaunchKernelGGL(dA_partial_kernel<T>, grid, dim3(256), 0, stream, d, B, dWp, partial);
   const int64_t n = (int64_t)d.r * d.i;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, partial, nrb, n,
-                     d.gamma, dA);
+                     d.gamma, dA, d.accumulate);
 }
 
 template void launch_quant_grads<float>(const LayerDims&, const float*, const float*, const float*, const float*,

@@ -10,7 +10,7 @@ import pytest
 from paper_2402_04902_amd import inputs
 from paper_2402_04902_amd.inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
 
-from parity_util import check_discrete, check_float_outputs, host_qparams, oracle_all
+from parity_util import TOL, check_discrete, check_float_outputs, host_qparams, oracle_all, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -214,3 +214,35 @@ def test_backward_is_bit_reproducible():
         outs.append([t.clone() for t in (layer.Y, layer.dX, layer.dA, layer.dB, layer.dscale, layer.dzero)])
     for a, c in zip(*outs):
         assert torch.equal(a, c)
+
+
+# ------------------------------------------------------------------ gradient accumulation over micro-batches
+
+@pytest.mark.parametrize("dtype,flags", [(DTYPE_F32, 0), (DTYPE_BF16, 0), (DTYPE_BF16, 1)])
+def test_backward_accumulates_parameter_gradients(dtype, flags):
+    """Two micro-batches: the second backward call carries the accumulate flag.  dA, dB, dscale, dzero must hold the
+    oracle's sum of both contributions, dX the second micro-batch's alone."""
+    import torch
+    from paper_2402_04902_amd import binding
+    spec = LayerSpec("accum", 70, 256, 264, 4, 8.0, 4, 64, dtype)
+    print("case", spec.name, "dtype", dtype, "flags", flags, flush=True)
+    a1 = inputs.make_layer_inputs(spec, seed=11)
+    a2 = dict(a1)
+    other = inputs.make_layer_inputs(spec, seed=12)
+    a2["X"], a2["dY"] = other["X"], other["dY"]          # same parameters, another micro-batch
+    s, b = host_qparams(spec, a1, "asymm", 0.8)
+    _, _, _, _, g1 = oracle_all(spec, a1, s, b)
+    _, _, _, _, g2 = oracle_all(spec, a2, s, b)
+    layer = binding.upload(spec, a1, s, b, flags=flags)
+    layer.backward()
+    layer.X.copy_(torch.from_numpy(a2["X"]).to(layer.X.device).to(layer.X.dtype))
+    layer.dY.copy_(torch.from_numpy(a2["dY"]).to(layer.dY.device).to(layer.dY.dtype))
+    layer.desc.flags = flags | binding.FLAG_ACCUMULATE_GRADS
+    layer.backward()
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    for name, got, ref in [("dA", layer.dA, g1.dA + g2.dA), ("dB", layer.dB, g1.dB + g2.dB),
+                           ("dscale", layer.dscale, g1.dscale + g2.dscale), ("dzero", layer.dzero, g1.dzero + g2.dzero),
+                           ("dX", layer.dX, g2.dX)]:
+        err = rel_fro(got.double().cpu().numpy(), ref)
+        assert err <= tol, (name, err)
