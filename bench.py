@@ -152,6 +152,27 @@ def main() -> int:
         decode["T%d" % tok] = {"us_both_layers": us, "GB_per_s": nbytes / (us * 1e-6) / 1e9,
                                "frac_hbm_8TBs": nbytes / (us * 1e-6) / 8e12}
 
+    # the QAT-LoRA layer (Sec. 3.1) on the same workload: separate LoRA path, stored weight gradient
+    qws_f, qws_b = zip(*[binding.l4q_qatlora_workspace_bytes(l.desc) for l in layers])
+    qws = torch.empty(max(max(qws_f), max(qws_b)), dtype=torch.uint8, device="cuda:0")
+
+    def qat_step():
+        for l in layers:
+            binding.l4q_qatlora_forward(l.desc, l.X, l.W0, l.A, l.B, l.scale, l.zero, l.Y, qws)
+        for l in reversed(layers):
+            binding.l4q_qatlora_backward(l.desc, l.X, l.dY, l.W0, l.A, l.B, l.scale, l.zero, l.dX, l.dA, l.dB,
+                                         l.dscale, l.dzero, qws)
+    for _ in range(3):
+        qat_step()
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(10):
+        qat_step()
+    ev1.record()
+    torch.cuda.synchronize()
+    qat_ms = ev0.elapsed_time(ev1) / 10
+    del qws
+
     flops_per_step = sum(s.gemm_flops() for s in specs)
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = flops_per_step / (ms_per_step * 1e-3) / 1e12
@@ -179,6 +200,9 @@ def main() -> int:
                      "measured_mfma_only_tflops": mfma_only_tflops},
     }
     out["quantized_forward"] = decode
+    out["qat_lora_same_workload"] = {"ms_per_step": qat_ms, "workspace_bytes_fwd": max(qws_f),
+                                     "workspace_bytes_bwd": max(qws_b),
+                                     "l4q_speedup": qat_ms / ms_per_step}
     if not args.no_cpu_baseline:
         del layers
         torch.cuda.empty_cache()

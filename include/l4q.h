@@ -127,6 +127,25 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
                  void* dX, float* dA, float* dB, float* dscale, float* dzero,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* QAT-LoRA layer, the straightforward integration the paper starts from (Sec. 3.1): only the frozen weight
+ * goes through the quantizer and the LoRA path stays next to it in high precision,
+ *   Y  = X . Q(W0)^T + gamma (X A^T) B^T
+ *   dX = dY . Q(W0) + gamma (dY B) A;   dWq = dY^T X is written to the workspace in binary32 (the memory overhead
+ *   the section names) and d(scale), d(zero) are taken from it with Eq. quant_lsq_s / quant_lsq_b;
+ *   dA = gamma (dY B)^T X,  dB = gamma dY^T (X A^T)              (Eq. lora_backward).
+ * Arguments, layouts, dtypes, flags (L4Q_FLAG_ACCUMULATE_GRADS) and error behaviour as l4q_forward / l4q_backward;
+ * L4Q_FLAG_UNFUSED_BACKWARD has no effect.  The side products X A^T and dY B are binary32; in BF16 mode Y and dX
+ * are rounded once by the main product and once more when the LoRA term is added.  Provided to measure the
+ * memory / time gap to the L4Q layer on the same device; it shares the L4Q kernels. */
+int l4q_qatlora_workspace_bytes(const l4q_desc* desc, size_t* forward_bytes, size_t* backward_bytes);
+int l4q_qatlora_forward(const l4q_desc* desc, const void* X, const void* W0, const void* A, const void* B,
+                        const float* scale, const float* zero, void* Y,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+int l4q_qatlora_backward(const l4q_desc* desc, const void* X, const void* dY, const void* W0,
+                         const void* A, const void* B, const float* scale, const float* zero,
+                         void* dX, float* dA, float* dB, float* dscale, float* dzero,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Integer codes of the fully quantized layer (what inference consumes; Sec. 3.2, Eq. l4q_Wquant).
  *   codes [o,i] int8 in [Q_N, Q_P] (may be NULL);
  *   wcomb [o,i] float: the binary32 merged weight Wc the codes were taken from (may be NULL);

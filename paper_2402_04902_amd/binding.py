@@ -19,7 +19,8 @@ FLAG_ACCUMULATE_GRADS = 2
 INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
-            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward", "l4q_adamw_step", "l4q_cosine_lr"]
+            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward", "l4q_adamw_step", "l4q_cosine_lr",
+            "l4q_qatlora_workspace_bytes", "l4q_qatlora_forward", "l4q_qatlora_backward"]
 
 
 class L4QDesc(ctypes.Structure):
@@ -61,6 +62,12 @@ def load_library() -> ctypes.CDLL:
     lib.l4q_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
     lib.l4q_backward.restype = ctypes.c_int
     lib.l4q_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+    lib.l4q_qatlora_workspace_bytes.restype = ctypes.c_int
+    lib.l4q_qatlora_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
+    lib.l4q_qatlora_forward.restype = ctypes.c_int
+    lib.l4q_qatlora_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
+    lib.l4q_qatlora_backward.restype = ctypes.c_int
+    lib.l4q_qatlora_backward.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, vp, ctypes.c_size_t, vp]
     lib.l4q_export_codes.restype = ctypes.c_int
     lib.l4q_export_codes.argtypes = [dp, vp, vp, vp, fp, fp, vp, vp, vp, vp]
     lib.l4q_init_qparams.restype = ctypes.c_int
@@ -129,6 +136,28 @@ def l4q_backward(desc: L4QDesc, X, dY, W0, A, B, scale, zero, dX, dA, dB, dscale
                                        _ptr(dzero), _ptr(workspace),
                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
                                        _stream()), "l4q_backward")
+
+
+def l4q_qatlora_workspace_bytes(desc: L4QDesc) -> Tuple[int, int]:
+    f, b = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load_library().l4q_qatlora_workspace_bytes(ctypes.byref(desc), ctypes.byref(f), ctypes.byref(b)),
+           "l4q_qatlora_workspace_bytes")
+    return f.value, b.value
+
+
+def l4q_qatlora_forward(desc: L4QDesc, X, W0, A, B, scale, zero, Y, workspace) -> None:
+    _check(load_library().l4q_qatlora_forward(ctypes.byref(desc), _ptr(X), _ptr(W0), _ptr(A), _ptr(B), _ptr(scale),
+                                              _ptr(zero), _ptr(Y), _ptr(workspace),
+                                              0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                              _stream()), "l4q_qatlora_forward")
+
+
+def l4q_qatlora_backward(desc: L4QDesc, X, dY, W0, A, B, scale, zero, dX, dA, dB, dscale, dzero, workspace) -> None:
+    _check(load_library().l4q_qatlora_backward(ctypes.byref(desc), _ptr(X), _ptr(dY), _ptr(W0), _ptr(A), _ptr(B),
+                                               _ptr(scale), _ptr(zero), _ptr(dX), _ptr(dA), _ptr(dB), _ptr(dscale),
+                                               _ptr(dzero), _ptr(workspace),
+                                               0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                               _stream()), "l4q_qatlora_backward")
 
 
 def l4q_export_codes(desc: L4QDesc, W0, A, B, scale, zero, codes=None, wcomb=None, mask=None) -> None:

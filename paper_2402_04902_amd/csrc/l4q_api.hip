@@ -181,6 +181,49 @@ void dw_fused(const LayerDims& d, const BwdWs& w, const bf16_t* dY, const bf16_t
   }
 }
 
+struct QlFwdWs {
+  void* wq;       // [o, ipad] storage type
+  float* xa;      // [T, r]
+  int64_t ipad;
+  size_t bytes;
+};
+struct QlBwdWs {
+  float* wq32;    // [o, i]      (binary32 mode)
+  bf16_t* wqT;    // [i, opad]   (bf16)
+  float* dwq;     // [o, i]      the stored weight gradient
+  float* dyb;     // [T, r]
+  float* xa;      // [T, r]
+  float* part;    // [token blocks, r, max(i, o)]
+  int64_t opad;
+  size_t bytes;
+};
+
+QlFwdWs carve_ql_fwd(const l4q_desc* d, void* ws) {
+  Carver c(ws);
+  QlFwdWs w;
+  w.ipad = d->dtype == L4Q_DTYPE_BF16 ? (int64_t)align_up((size_t)d->in_features, 32) : d->in_features;
+  const size_t n = (size_t)d->out_features * (size_t)w.ipad;
+  w.wq = d->dtype == L4Q_DTYPE_BF16 ? (void*)c.take<bf16_t>(n) : (void*)c.take<float>(n);
+  w.xa = c.take<float>((size_t)d->tokens * (size_t)d->rank);
+  w.bytes = c.used;
+  return w;
+}
+
+QlBwdWs carve_ql_bwd(const l4q_desc* d, void* ws) {
+  Carver c(ws);
+  QlBwdWs w = {};
+  const size_t o = (size_t)d->out_features, i = (size_t)d->in_features, r = (size_t)d->rank, T = (size_t)d->tokens;
+  w.opad = (int64_t)align_up(o, 32);
+  if (d->dtype == L4Q_DTYPE_BF16) w.wqT = c.take<bf16_t>(i * (size_t)w.opad);
+  else w.wq32 = c.take<float>(o * i);
+  w.dwq = c.take<float>(o * i);
+  w.dyb = c.take<float>(T * r);
+  w.xa = c.take<float>(T * r);
+  w.part = c.take<float>((size_t)l4q::lora_tn_blocks((int64_t)T) * r * (i > o ? i : o));
+  w.bytes = c.used;
+  return w;
+}
+
 }  // namespace
 
 extern "C" {
@@ -394,6 +437,105 @@ int l4q_quantized_forward(const l4q_desc* desc, const void* X, const uint32_t* p
     if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
   (void)hipGetLastError();
   l4q::launch_qgemm(d, (const bf16_t*)X, packed, scale, zero, (bf16_t*)Y, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
+int l4q_qatlora_workspace_bytes(const l4q_desc* desc, size_t* forward_bytes, size_t* backward_bytes) {
+  const int st = check_desc(desc, true);
+  if (st != L4Q_OK) return st;
+  if (forward_bytes) *forward_bytes = carve_ql_fwd(desc, nullptr).bytes;
+  if (backward_bytes) *backward_bytes = carve_ql_bwd(desc, nullptr).bytes;
+  return L4Q_OK;
+}
+
+int l4q_qatlora_forward(const l4q_desc* desc, const void* X, const void* W0, const void* A, const void* B,
+                        const float* scale, const float* zero, void* Y, void* workspace, size_t workspace_bytes,
+                        void* hip_stream) {
+  const int st = check_desc(desc, true);
+  if (st != L4Q_OK) return st;
+  if (!X || !W0 || !A || !B || !scale || !zero || !Y) return L4Q_ERR_NULL;
+  if (!aligned(X, 16) || !aligned(W0, 16) || !aligned(A, 16) || !aligned(B, 16) || !aligned(scale, 16) ||
+      !aligned(zero, 16) || !aligned(Y, 16))
+    return L4Q_ERR_ALIGN;
+  const QlFwdWs w = carve_ql_fwd(desc, workspace);
+  if (!workspace || workspace_bytes < w.bytes) return L4Q_ERR_WORKSPACE;
+  if (!aligned(workspace, kWsAlign)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  LayerDims dq = d;   // the quantizer sees the frozen weight alone
+  dq.gamma = 0.f;
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16) {
+    bf16_t* wq = static_cast<bf16_t*>(w.wq);
+    l4q::MergeQuantOut<bf16_t> mq;
+    mq.wq = wq;
+    mq.ld_wq = w.ipad;
+    l4q::launch_merge_quant<bf16_t>(dq, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
+    gemm_nt((const bf16_t*)X, d.i, wq, w.ipad, d.T, d.o, w.ipad, d.i, (bf16_t*)Y, d.o, stream);
+    l4q::launch_lora_down<bf16_t>((const bf16_t*)X, d.T, d.i, (const bf16_t*)A, d.r, false, w.xa, stream);
+    l4q::launch_lora_up<bf16_t>((bf16_t*)Y, d.T, d.o, w.xa, (const bf16_t*)B, d.r, true, d.gamma, stream);
+  } else {
+    float* wq = static_cast<float*>(w.wq);
+    l4q::MergeQuantOut<float> mq;
+    mq.wq = wq;
+    mq.ld_wq = d.i;
+    l4q::launch_merge_quant<float>(dq, (const float*)W0, (const float*)A, (const float*)B, scale, zero, mq, stream);
+    l4q::launch_sgemm((const float*)X, d.i, 1, wq, 1, d.i, (float*)Y, d.o, d.T, d.o, d.i, 1.f, stream);
+    l4q::launch_lora_down<float>((const float*)X, d.T, d.i, (const float*)A, d.r, false, w.xa, stream);
+    l4q::launch_lora_up<float>((float*)Y, d.T, d.o, w.xa, (const float*)B, d.r, true, d.gamma, stream);
+  }
+  return launch_status();
+}
+
+int l4q_qatlora_backward(const l4q_desc* desc, const void* X, const void* dY, const void* W0, const void* A,
+                         const void* B, const float* scale, const float* zero, void* dX, float* dA, float* dB,
+                         float* dscale, float* dzero, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int st = check_desc(desc, true);
+  if (st != L4Q_OK) return st;
+  if (!X || !dY || !W0 || !A || !B || !scale || !zero || !dX || !dA || !dB || !dscale || !dzero) return L4Q_ERR_NULL;
+  const void* ptrs[] = {X, dY, W0, A, B, scale, zero, dX, dA, dB, dscale, dzero};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  const QlBwdWs w = carve_ql_bwd(desc, workspace);
+  if (!workspace || workspace_bytes < w.bytes) return L4Q_ERR_WORKSPACE;
+  if (!aligned(workspace, kWsAlign)) return L4Q_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  LayerDims dq = d;
+  dq.gamma = 0.f;
+  (void)hipGetLastError();
+  if (desc->dtype == L4Q_DTYPE_BF16) {
+    const bf16_t *Xb = (const bf16_t*)X, *dYb = (const bf16_t*)dY, *W0b = (const bf16_t*)W0, *Ab = (const bf16_t*)A,
+                 *Bb = (const bf16_t*)B;
+    l4q::MergeQuantOut<bf16_t> mq;
+    mq.wqT = w.wqT;
+    mq.ld_wqT = w.opad;
+    l4q::launch_merge_quant<bf16_t>(dq, W0b, Ab, Bb, scale, zero, mq, stream);
+    gemm_nt(dYb, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream);
+    l4q::launch_lora_down<bf16_t>(dYb, d.T, d.o, Bb, d.r, true, w.dyb, stream);
+    l4q::launch_lora_up<bf16_t>((bf16_t*)dX, d.T, d.i, w.dyb, Ab, d.r, false, d.gamma, stream);
+    // the weight gradient is materialised: scale and zero are updated from it
+    l4q::launch_gemm_bf16_kmajor_f32(dYb, d.o, Xb, d.i, d.o, d.i, d.T, w.dwq, d.i, stream);
+    l4q::launch_quant_grads<bf16_t>(dq, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);  // its dB term is gamma = 0
+    l4q::launch_lora_down<bf16_t>(Xb, d.T, d.i, Ab, d.r, false, w.xa, stream);
+    l4q::launch_lora_tn<bf16_t>(w.dyb, Xb, d.T, d.i, d.r, false, w.part, d.gamma, dA, d.accumulate, stream);
+    l4q::launch_lora_tn<bf16_t>(w.xa, dYb, d.T, d.o, d.r, true, w.part, d.gamma, dB, d.accumulate, stream);
+  } else {
+    const float *Xf = (const float*)X, *dYf = (const float*)dY, *W0f = (const float*)W0, *Af = (const float*)A,
+                *Bf = (const float*)B;
+    l4q::MergeQuantOut<float> mq;
+    mq.wq = w.wq32;
+    mq.ld_wq = d.i;
+    l4q::launch_merge_quant<float>(dq, W0f, Af, Bf, scale, zero, mq, stream);
+    l4q::launch_sgemm(dYf, d.o, 1, w.wq32, d.i, 1, (float*)dX, d.i, d.T, d.i, d.o, 1.f, stream);
+    l4q::launch_lora_down<float>(dYf, d.T, d.o, Bf, d.r, true, w.dyb, stream);
+    l4q::launch_lora_up<float>((float*)dX, d.T, d.i, w.dyb, Af, d.r, false, d.gamma, stream);
+    l4q::launch_sgemm(dYf, 1, d.o, Xf, d.i, 1, w.dwq, d.i, d.o, d.i, d.T, 1.f, stream);
+    l4q::launch_quant_grads<float>(dq, W0f, Af, Bf, scale, zero, w.dwq, dscale, dzero, dB, stream);
+    l4q::launch_lora_down<float>(Xf, d.T, d.i, Af, d.r, false, w.xa, stream);
+    l4q::launch_lora_tn<float>(w.dyb, Xf, d.T, d.i, d.r, false, w.part, d.gamma, dA, d.accumulate, stream);
+    l4q::launch_lora_tn<float>(w.xa, dYf, d.T, d.o, d.r, true, w.part, d.gamma, dB, d.accumulate, stream);
+  }
   return launch_status();
 }
 

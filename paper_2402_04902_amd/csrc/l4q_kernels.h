@@ -120,4 +120,19 @@ void launch_dw_fused(const LayerDims& d, const bf16_t* dY, const bf16_t* X, cons
                      const bf16_t* BT, int64_t ld_bt, float* dscale, float* dzero, float* dA_part, float* dB_part,
                      hipStream_t stream);
 
+
+// ---- rank-r side products of the QAT-LoRA layer (Sec. 3.1): U binary32 [T, r]; the small matrix M is read as
+// [r, n] (A) or, with m_is_n_by_r, as [n, r] (B) ----
+template <class S>
+void launch_lora_down(const S* Xs, int64_t T, int64_t n, const S* M, int r, bool m_is_n_by_r, float* U,
+                      hipStream_t stream);                    // U = Xs . M^T  (sum over n)
+template <class S>
+void launch_lora_up(S* Out, int64_t T, int64_t n, const float* U, const S* M, int r, bool m_is_n_by_r, float gamma,
+                    hipStream_t stream);                      // Out += gamma U . M
+int64_t lora_tn_blocks(int64_t T);                            // token blocks of the partial sums below
+// out = gamma * sum_t U[t,:]^T Xs[t,:] as [r, n], or as [n, r] with out_n_by_r; partial: lora_tn_blocks(T) * r * n floats
+template <class S>
+void launch_lora_tn(const float* U, const S* Xs, int64_t T, int64_t n, int r, bool out_n_by_r, float* partial,
+                    float gamma, float* out, bool accumulate, hipStream_t stream);
+
 }  // namespace l4q
