@@ -4,13 +4,16 @@
 // Packed layout: the unsigned field u = w~ - Q_N of column j occupies bits [n j, n j + n) of the
 // row's little-endian bit string; rows are n * i / 32 words.
 //
-// qgemm_kernel: one workgroup = 32 weight rows, 4 waves splitting k in interleaved 64-wide chunks.
+// Two kernels compute the product.  qgemm_stream_kernel (further down) covers 4- and 8-bit layers whose packed
+// rows are whole cache lines, up to 32 tokens per pass; qgemm_kernel covers every other layout and up to 64
+// tokens per pass:
+// qgemm_kernel: one workgroup = 32 weight rows, 8 waves splitting k in interleaved 64-wide chunks.
 // A lane owns one weight row: per chunk it loads the n words holding its 32 consecutive codes
-// (lane group 0: k 0..31 of the chunk, group 1: k 32..63), expands them to bf16 (w~ s + b, the same
-// values the training forward multiplies with) and feeds them to the matrix core as the row operand;
-// the token operand comes straight from X (L1/L2 resident at decode sizes).  The k-slot order inside
-// a chunk differs from memory order, identically for both operands, which a contraction allows.
-// Partial sums of the 4 waves meet in LDS.  The weight stream is read once: HBM-bound.
+// (lane group 0: k 0..31 of the chunk, group 1: k 32..63), turns them into bf16 operands (integer codes with the
+// affine part applied to the accumulator when g >= 64, else w~ s + b itself) and feeds them to the matrix core
+// as the row operand; the token operand comes straight from X (L1/L2 resident at decode sizes).  The k-slot
+// order inside a chunk differs from memory order, identically for both operands, which a contraction allows.
+// Partial sums of the 8 waves meet in LDS.  The weight stream is read once per pass: HBM-bound.
 #include "l4q_device.h"
 #include "l4q_gemm_core.h"
 #include "l4q_kernels.h"

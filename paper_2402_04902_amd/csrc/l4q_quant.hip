@@ -16,9 +16,10 @@ constexpr int kThreads = 256;
 // ------------------------------------------------------------------ merge + quantize, tiled
 // Block tile: MQ_ROWS weight rows x 256 columns, 8 waves.  A thread owns 4 consecutive columns (one
 // 8- or 16-byte load of W0 per row, 512 B / 1 KiB contiguous per wave) and its wave walks MQ_RPW
-// rows.  The rank loop runs k-outer in chunks of 16: A[k, 4 columns] is unpacked once and used for
-// all rows, B[p, k] is fetched once per row by lane k and read back as a scalar, and the running
-// sums of all rows stay in registers, which keeps the k-ascending summation order for any rank.
+// rows.  The rank loop runs k-outer: A[k, 4 columns] is unpacked once and used for all rows, B[p, k]
+// is wave-uniform and comes through scalar loads (or, for rows of B that do not start on a 4-byte
+// boundary, is fetched by lane k and read back with v_readlane), and the running sums of all rows stay
+// in registers, which keeps the k-ascending summation order for any rank.
 // Every load is unconditional (clamped address, value discarded where out of range) so that the
 // W0 / scale / zero loads of all rows are in flight while the rank loop runs.
 constexpr int MQ_ROWS = 64;
