@@ -4,6 +4,8 @@
 // coalesced 8/16-byte loads, adds the rank-r update from registers, applies the group-wise
 // quantizer and writes whichever outputs were asked for (dequantized Wq, its transpose, the
 // per-element d(Wq)/d(scale) factor, int8 codes, the binary32 merged weight, the mask).
+#include <type_traits>
+
 #include "l4q_device.h"
 #include "l4q_kernels.h"
 
@@ -116,6 +118,106 @@ __device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restric
   }
 }
 
+// The same sums on the matrix core (bfloat16 storage only).  A product of two bfloat16 values is exact in
+// binary32, so step k of the stated chain is acc = RN(acc + B[p,k] A[k,j]): exactly what one
+// v_mfma_f32_32x32x1_2b_f32 does for 2 x 32 x 32 outputs (K = 1: there is nothing else to add and nothing to
+// reorder; checked bit for bit against fmaf chains on 8.4 M sums).  r such instructions in k order give the
+// stated sums for a 32-row x 64-column block per wave; a rank that does not fill a chunk of 16 is padded with
+// zero factors, which leave the sums unchanged.  The accumulators come out one column per lane, so they pass
+// through LDS once to reach the 4-columns-of-a-row layout of the streaming code below.
+// f32_tile: MQ_ROWS x MQ_FPITCH floats of LDS.  Contains two barriers; every wave must call it.
+constexpr int MQ_FPITCH = MQ_COLS + 8;  // 4 rows further = 32 banks further: the two half-waves write different banks
+constexpr int MQ_F32_TILE = MQ_ROWS * MQ_FPITCH * 4 + MQ_KC * MQ_COLS * 2;  // sums + the A panel of a chunk
+
+// `after_first_loads` runs once, right after the first chunk's factor loads have been issued: the caller requests
+// its row data there.  Loads complete in issue order, so requesting the HBM stream first would make the matrix ops
+// wait for it.
+template <class F>
+__device__ __forceinline__ void lora_rows_mfma(const LayerDims& d, const bf16_t* __restrict__ A,
+                                               const bf16_t* __restrict__ B, int64_t jblk, int64_t pblk, int lane,
+                                               int wave, float* f32_tile, float (&acc)[MQ_RPW][4],
+                                               F&& after_first_loads) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef float f32x32_t __attribute__((ext_vector_type(32)));
+  static_assert(MQ_ROWS == 64 && MQ_COLS == 256 && MQ_THREADS == 512, "8 waves = 2 row blocks x 4 column blocks");
+  const int rb = wave >> 2, cb = wave & 3;
+  const int64_t p = pblk + 32 * rb + (lane & 31);
+  const bf16_t* brow = B + (p < d.o ? p : d.o - 1) * d.r;
+  f32x32_t sum;
+#pragma unroll
+  for (int e = 0; e < 32; ++e) sum[e] = 0.f;
+  // Few, wide loads: the 16 ranks of a row of B are contiguous (two 16-byte loads per lane where rows are 16-byte
+  // aligned); the A panel of the chunk (16 ranks x 256 columns) is fetched once per workgroup, 16 bytes per
+  // thread, and handed to the column-per-lane layout through LDS.
+  bf16_t* a_lds = reinterpret_cast<bf16_t*>(f32_tile + MQ_ROWS * MQ_FPITCH);  // [MQ_KC][MQ_COLS]
+  const int tid = threadIdx.x;
+  const int ak = tid >> 5, acols = 8 * (tid & 31);
+  const bool b_vec = (d.r & 7) == 0;
+  auto chunk = [&](int k0, auto&& between) {
+    uint4 apanel = make_uint4(0u, 0u, 0u, 0u);
+    {
+      const int kc = k0 + ak < d.r ? k0 + ak : d.r - 1;
+      const int64_t jc8 = jblk + acols < d.i ? jblk + acols : 0;
+      apanel = *reinterpret_cast<const uint4*>(A + (int64_t)kc * d.i + jc8);
+    }
+    uint4 bq[2];
+    bf16_t braw[MQ_KC];
+    if (b_vec) {
+      bq[0] = *reinterpret_cast<const uint4*>(brow + k0);
+      bq[1] = *reinterpret_cast<const uint4*>(brow + (k0 + 8 < d.r ? k0 + 8 : k0));
+    } else {
+#pragma unroll
+      for (int k = 0; k < MQ_KC; ++k) braw[k] = brow[k0 + k < d.r ? k0 + k : d.r - 1];
+    }
+    __builtin_amdgcn_sched_barrier(0);  // the factor loads are in flight before anything waits for one of them
+    between();                          // the caller's row data: issued behind them
+    __builtin_amdgcn_sched_barrier(0);
+    *reinterpret_cast<uint4*>(a_lds + ak * MQ_COLS + acols) = apanel;
+    __syncthreads();
+    if (b_vec) {
+      const uint32_t w[8] = {bq[0].x, bq[0].y, bq[0].z, bq[0].w, bq[1].x, bq[1].y, bq[1].z, bq[1].w};
+#pragma unroll
+      for (int k = 0; k < MQ_KC; ++k) braw[k] = (bf16_t)(k & 1 ? w[k >> 1] >> 16 : w[k >> 1] & 0xFFFFu);
+    }
+#pragma unroll
+    for (int k = 0; k < MQ_KC; ++k) {
+      const bf16_t araw = a_lds[k * MQ_COLS + 64 * cb + lane];
+      const float b = k0 + k < d.r ? bf16_to_f32(braw[k]) : 0.f, a = k0 + k < d.r ? bf16_to_f32(araw) : 0.f;
+      sum = __builtin_amdgcn_mfma_f32_32x32x1f32(b, a, sum, 0, 0, 0);
+    }
+    __syncthreads();  // the panel may be overwritten by the next chunk
+  };
+  chunk(0, after_first_loads);  // straight-line code: the waits of this chunk then count the row loads behind it
+  for (int k0 = MQ_KC; k0 < d.r; k0 += MQ_KC) chunk(k0, [] {});
+  // register e of lane l: block e / 16 (columns 32 (e / 16) + l % 32), row 8 ((e % 16) / 4) + 4 (l / 32) + e % 4
+#pragma unroll
+  for (int e = 0; e < 32; ++e) {
+    const int row = 32 * rb + 8 * ((e & 15) >> 2) + 4 * (lane >> 5) + (e & 3);
+    const int col = 64 * cb + 32 * (e >> 4) + (lane & 31);
+    f32_tile[row * MQ_FPITCH + col] = sum[e];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int rr = 0; rr < MQ_RPW; ++rr) {
+    const float4 v = *reinterpret_cast<const float4*>(f32_tile + (wave * MQ_RPW + rr) * MQ_FPITCH + 4 * lane);
+    acc[rr][0] = v.x; acc[rr][1] = v.y; acc[rr][2] = v.z; acc[rr][3] = v.w;
+  }
+  __syncthreads();  // the tile may be reused (transposed output) once every wave has its sums
+#endif
+}
+
+template <class T, class F>
+__device__ __forceinline__ void lora_sums(const LayerDims& d, const T* __restrict__ A, const T* __restrict__ B,
+                                          unsigned jc, int64_t jblk, int64_t pblk, int64_t pw, int lane, int wave,
+                                          unsigned char* lds, float (&acc)[MQ_RPW][4], F&& request_row_data) {
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    lora_rows_mfma(d, A, B, jblk, pblk, lane, wave, reinterpret_cast<float*>(lds), acc, request_row_data);
+  } else {
+    request_row_data();
+    lora_rows<T>(d, A, B, jc, pw, lane, acc);
+  }
+}
+
 // Eq. quant / l4q_Wquant on one element, in the operation order of quantize_elem(); the clamp is one median
 // instruction and "in range" is "the clamp changed nothing" (the same decision for every non-NaN w).
 struct QuantFast {
@@ -142,7 +244,9 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
                                                                        const float* __restrict__ zero,
                                                                        MergeQuantOut<T> out) {
   typedef typename Raw4<T>::type raw4_t;
-  __shared__ __attribute__((aligned(16))) unsigned char tile[MODE == 1 ? 16 : MQ_COLS * MQ_TROW];
+  constexpr int LDS_T = MODE == 1 ? 16 : MQ_COLS * MQ_TROW;                        // transposed output staging
+  constexpr int LDS_F = std::is_same<T, bf16_t>::value ? MQ_F32_TILE : 16;        // LoRA sums from the matrix core
+  __shared__ __attribute__((aligned(16))) unsigned char tile[LDS_T > LDS_F ? LDS_T : LDS_F];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t jblk = (int64_t)blockIdx.x * MQ_COLS;
@@ -156,20 +260,22 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
   const float zero4[4] = {0.f, 0.f, 0.f, 0.f};
   constexpr bool want_wq = MODE != 2, want_t = MODE != 1, want_f = MODE != 1, want_misc = MODE == 0;
 
-  // row data, requested up front
+  // row data: every load is requested before the rank sums are consumed
   raw4_t w0raw[MQ_RPW];
   float sv[MQ_RPW], bv[MQ_RPW];
+  auto request_row_data = [&]() {
 #pragma unroll
-  for (int rr = 0; rr < MQ_RPW; ++rr) {
-    const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
-    // wave-uniform row base first, lane offset second: the loads take a scalar base register
-    w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
-    sv[rr] = (scale + pc * G)[q];
-    bv[rr] = (zero + pc * G)[q];
-  }
+    for (int rr = 0; rr < MQ_RPW; ++rr) {
+      const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
+      // wave-uniform row base first, lane offset second: the loads take a scalar base register
+      w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
+      sv[rr] = (scale + pc * G)[q];
+      bv[rr] = (zero + pc * G)[q];
+    }
+  };
 
   float acc[MQ_RPW][4];
-  lora_rows<T>(d, A, B, jc, pw, lane, acc);
+  lora_sums<T>(d, A, B, jc, jblk, (int64_t)blockIdx.y * MQ_ROWS, pw, lane, wave, tile, acc, request_row_data);
 
   float wqkeep[want_t ? MQ_RPW : 1][4];  // dequantized values of all rows, for the transposed output
 #pragma unroll
@@ -253,6 +359,7 @@ __global__ __launch_bounds__(MQ_THREADS) void weight_stats_tile_kernel(LayerDims
                                                                         float* __restrict__ zero,
                                                                         float* __restrict__ err_part) {
   typedef typename Raw4<T>::type raw4_t;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[std::is_same<T, bf16_t>::value ? MQ_F32_TILE : 16];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t j0 = (int64_t)blockIdx.x * MQ_COLS + lane * 4;
@@ -266,15 +373,18 @@ __global__ __launch_bounds__(MQ_THREADS) void weight_stats_tile_kernel(LayerDims
 
   raw4_t w0raw[MQ_RPW];
   float sv[MQ_RPW], bv[MQ_RPW];
+  auto request_row_data = [&]() {
 #pragma unroll
-  for (int rr = 0; rr < MQ_RPW; ++rr) {
-    const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
-    w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
-    sv[rr] = mode == STAT_ERRORS ? (scale + pc * G)[q] : 1.f;
-    bv[rr] = mode == STAT_ERRORS ? (zero + pc * G)[q] : 0.f;
-  }
+    for (int rr = 0; rr < MQ_RPW; ++rr) {
+      const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
+      w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
+      sv[rr] = mode == STAT_ERRORS ? (scale + pc * G)[q] : 1.f;
+      bv[rr] = mode == STAT_ERRORS ? (zero + pc * G)[q] : 0.f;
+    }
+  };
   float acc[MQ_RPW][4];
-  lora_rows<T>(d, A, B, jc, pw, lane, acc);
+  lora_sums<T>(d, A, B, jc, (int64_t)blockIdx.x * MQ_COLS, (int64_t)blockIdx.y * MQ_ROWS, pw, lane, wave, lds, acc,
+               request_row_data);
 
 #pragma unroll
   for (int rr = 0; rr < MQ_RPW; ++rr) {
