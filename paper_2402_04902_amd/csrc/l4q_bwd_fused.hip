@@ -100,6 +100,25 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     }
   }
 
+  // The d(Wq)/d(scale) factors this lane needs: 64 pieces of 4 consecutive columns, one per (row block, column tile,
+  // register group), all requested here so that their latency (the factor array is streamed once from HBM) is paid
+  // once per tile and not once per row block.  Rows and columns past the matrix are clamped to a valid address; their
+  // accumulators are exactly zero, so whatever finite factor is read there contributes nothing.
+  typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+  h4 fpre[T::TM][T::TN][4];
+#pragma unroll
+  for (int a = 0; a < T::TM; ++a) {
+    const int frow_i = m0 + wm * 128 + a * 32 + l32;
+    const uint16_t* frow = p.fgrad + (int64_t)(frow_i < p.o ? frow_i : p.o - 1) * p.i;
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+      for (int eg = 0; eg < 4; ++eg) {
+        const int j = n0 + wn * 128 + b * 32 + 8 * eg + 4 * lh;
+        fpre[a][b][eg] = *reinterpret_cast<const h4*>(frow + (j < p.i ? j : p.i - 4));
+      }
+  }
+
   const int G = p.i / p.g;
   auto put = [&](float* dst, float v) { *dst = p.accumulate ? *dst + v : v; };  // each element has one writer
   float keep_ds[T::TM], keep_db[T::TM];  // g == 256: this wave's half of the group, per row block
@@ -117,10 +136,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
       db_b[b] = 0.f;
 #pragma unroll
       for (int eg = 0; eg < 4; ++eg) {
-        const int j = n0 + wn * 128 + b * 32 + 8 * eg + 4 * lh;
-        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-        h4 fh = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
-        if (row_ok && j < p.i) fh = *reinterpret_cast<const h4*>(p.fgrad + (int64_t)row * p.i + j);
+        const h4 fh = fpre[a][b][eg];
         float xm[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -219,6 +235,17 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     }
   }
 
+  // B^T fragments of the dA product (lane = rank index, 8 consecutive rows): all 16 k-steps requested before the
+  // barrier, so the product below does not wait for them one batch at a time
+  uint4 bt_all[16];
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks) {
+    const int64_t prow = (int64_t)m0 + ks * 16 + lh * 8;
+    const bool live = l32 < p.r && prow < p.ld_bt;
+    const uint4 v = *reinterpret_cast<const uint4*>(p.BT + (int64_t)(live ? l32 : 0) * p.ld_bt + (live ? prow : 0));
+    bt_all[ks] = live ? v : make_uint4(0, 0, 0, 0);
+  }
+
   __syncthreads();
 
   if (p.g == 256 && wn == 0 && lh == 0) {
@@ -240,12 +267,9 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
   for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
     for (int e = 0; e < 16; ++e) ca[nb][e] = 0.f;
-#pragma unroll 4
+#pragma unroll
   for (int ks = 0; ks < 16; ++ks) {
-    const int64_t prow = (int64_t)m0 + ks * 16 + lh * 8;
-    uint4 bt = make_uint4(0, 0, 0, 0);
-    if (l32 < p.r && prow < p.ld_bt) bt = *reinterpret_cast<const uint4*>(p.BT + (int64_t)l32 * p.ld_bt + prow);
-    const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bt);
+    const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bt_all[ks]);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       const int jl = wave * 64 + nb * 32 + l32;
