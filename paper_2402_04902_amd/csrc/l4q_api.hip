@@ -313,14 +313,16 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     mq.ld_wqT = w.opad;
     mq.fgrad = w.fgrad;  // null when unfused
     l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, mq, stream);
-    gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream);
-    // dWq = dY^T . X, both operands read as they lie in memory
+    // dWq = dY^T . X, both operands read as they lie in memory.  The fused kernel goes first: the factor array the
+    // merge pass has just written is then still in the memory-side cache when the epilogues ask for it.
     if (w.fused) {
       l4q::launch_transpose_lora_b(Bb, d.o, d.r, w.bT, w.opad, stream);
       dw_fused(d, w, (const bf16_t*)dY, (const bf16_t*)X, Ab, dscale, dzero, stream);
       l4q::launch_reduce_two_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, dA, w.dB_part, 2 * w.tiles_n,
                                       d.o * d.r, dB, d.gamma, d.accumulate, stream);
-    } else {
+    }
+    gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream);
+    if (!w.fused) {
       l4q::launch_gemm_bf16_kmajor_f32((const bf16_t*)dY, d.o, (const bf16_t*)X, d.i, d.o, d.i, d.T, w.dwq, d.i, stream);
       l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);
       l4q::launch_dA<bf16_t>(d, Bb, w.dwq, w.dA_part, dA, stream);

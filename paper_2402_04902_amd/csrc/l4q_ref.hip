@@ -196,21 +196,37 @@ void launch_reduce_partials(const float* partial, int64_t nblocks, int64_t n, fl
 }
 
 // Both reductions of the fused backward in one launch; 4 consecutive elements per thread (n % 4 == 0).
+// A block is 64 element quads x 4 slices of the partial index: slice q sums partials [q*per, (q+1)*per) in
+// ascending order and the four slice sums are added in ascending q, so the summation order is fixed.
 __global__ __launch_bounds__(256) void reduce_two_partials_kernel(const float* __restrict__ pa, int nba, int64_t na,
                                                                    float* __restrict__ outa,
                                                                    const float* __restrict__ pb, int nbb, int64_t nb,
                                                                    float* __restrict__ outb, float scale,
                                                                    int blocks_a, bool accumulate) {
+  __shared__ float4 slice_sum[3][64];
   const bool second = (int)blockIdx.x >= blocks_a;
   const float* __restrict__ part = second ? pb : pa;
   float* __restrict__ out = second ? outb : outa;
   const int nblocks = second ? nbb : nba;
   const int64_t n = second ? nb : na;
-  const int64_t e = ((int64_t)(second ? blockIdx.x - blocks_a : blockIdx.x) * 256 + threadIdx.x) * 4;
-  if (e >= n) return;
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int64_t e = ((int64_t)(second ? blockIdx.x - blocks_a : blockIdx.x) * 64 + lane) * 4;
+  const int per = (nblocks + 3) / 4;
+  const int b0 = q * per, b1 = min(nblocks, b0 + per);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int b = 0; b < nblocks; ++b) {  // ascending: the summation order is fixed
-    const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)b * n + e);
+  if (e < n) {
+#pragma unroll 4
+    for (int b = b0; b < b1; ++b) {
+      const float4 v = *reinterpret_cast<const float4*>(part + (int64_t)b * n + e);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+  }
+  if (q > 0) slice_sum[q - 1][lane] = acc;
+  __syncthreads();
+  if (q > 0 || e >= n) return;
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const float4 v = slice_sum[k][lane];
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
   }
   float4 r = make_float4(scale * acc.x, scale * acc.y, scale * acc.z, scale * acc.w);
@@ -223,7 +239,7 @@ __global__ __launch_bounds__(256) void reduce_two_partials_kernel(const float* _
 
 void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* outa, const float* pb, int nbb,
                                 int64_t nb, float* outb, float scale, bool accumulate, hipStream_t stream) {
-  const int blocks_a = (int)((na / 4 + 255) / 256), blocks_b = (int)((nb / 4 + 255) / 256);
+  const int blocks_a = (int)((na / 4 + 63) / 64), blocks_b = (int)((nb / 4 + 63) / 64);
   hipLaunchKernelGGL(reduce_two_partials_kernel, dim3((unsigned)(blocks_a + blocks_b)), dim3(256), 0, stream, pa, nba,
                      na, outa, pb, nbb, nb, outb, scale, blocks_a, accumulate);
 }
