@@ -489,6 +489,172 @@ __global__ __launch_bounds__(256, 2) void qgemm_stream_kernel(const bf16_t* __re
 #endif
 }
 
+// The same pipeline for the smallest batches (single-token decode first of all), 16-row tiles.  In the kernel above
+// every stage costs a wave 8 wave-wide register loads of X fragments and 4 of scale / zero, which together occupy the
+// vector-memory path four times as long as the two loads that bring the weights themselves.  Here the activations
+// of the whole pass (T rows of X, at most QD_X_MAX bytes) and the tile's scale / zero rows are put into LDS once per
+// workgroup, and the stage loop issues nothing but the weight stream: fragments, scale and zero are LDS reads
+// (lanes of one token and k-group read the same address, which the LDS serves as a broadcast).  NSW = ring stages
+// per wave: 4 when several workgroups share a compute unit, 8 when there is at most one per unit and a wave has to
+// keep more of the stream in flight by itself.
+constexpr int QD_X_MAX = 96 * 1024;   // bytes of X held in LDS
+constexpr int QD_SB_MAX = 16 * 1024;  // bytes of scale + zero held in LDS
+constexpr int QD_LDS_MAX = 160 * 1024; // LDS of a compute unit
+
+template <int BITS, int NSW>
+__global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __restrict__ X,
+                                                               const uint32_t* __restrict__ packed,
+                                                               const float* __restrict__ scale,
+                                                               const float* __restrict__ zero,
+                                                               bf16_t* __restrict__ Y, int T, int o, int i, int g,
+                                                               int x_bytes, int sb_pitch) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char dlds[];
+#if defined(__HIP_DEVICE_COMPILE__)
+  static_assert(BITS == 4 || BITS == 8, "bits");
+  constexpr int ROWS = 16;
+  constexpr int STAGE = ROWS * 128;
+  typedef QsMfma<ROWS> M;
+  typedef typename M::acc_t acc_t;
+  constexpr int NACC = M::NACC;
+  constexpr int KG = 64 / ROWS, NH = 8 / KG, NDMA = ROWS / 8;
+  constexpr int CH = 128 / BITS, KS = 8 * CH, FR = CH / 8, SUB = KG * CH;
+  constexpr float K0 = BITS == 8 ? 0.f : 128.f + (float)(1 << (BITS - 1));
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef gemm::lds_ptr_t lds_ptr_t;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ln = lane % ROWS, kg = lane / ROWS;
+  const int p0 = blockIdx.x * ROWS;
+  const int p = p0 + ln;
+  const int rb = i / 8 * BITS;
+  const int nst = rb / 128;
+  const int G = i / g;
+  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
+
+  unsigned char* ring = dlds + wave * (NSW * STAGE);
+  unsigned char* xl = dlds + 4 * NSW * STAGE;                // [T][i] bf16, as in memory
+  float* sl = reinterpret_cast<float*>(xl + x_bytes);           // [16][sb_pitch], odd pitch: conflict-free columns
+  float* bl = sl + ROWS * sb_pitch;
+
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(packed), 0, (int)((int64_t)o * rb), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcX = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(X), 0, (int)((int64_t)T * i * 2), 0x00020000);
+  unsigned voff[NDMA];
+#pragma unroll
+  for (int q = 0; q < NDMA; ++q) {
+    const int r = 8 * q + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+    voff[q] = p0 + r < o ? (unsigned)((p0 + r) * rb + chunk * 16) : gemm::OOB_OFFSET;
+  }
+  const int nj = wave < nst ? (nst - wave + 3) / 4 : 0;
+  auto issue_dma = [&](int j) {
+    const unsigned kb = j < nj ? (unsigned)(wave + 4 * j) * 128u : gemm::PAST_END_OFFSET;
+    unsigned char* dst = ring + (j % NSW) * STAGE;
+#pragma unroll
+    for (int q = 0; q < NDMA; ++q)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(dst + q * 1024), 16, voff[q] + kb, 0, 0, 0);
+  };
+
+  // the first NSW - 1 weight stages, then X (1 KiB pieces round-robin over the waves; bytes past the end of X read
+  // as zero), then scale / zero of the tile's rows through registers into the padded LDS rows
+#pragma unroll
+  for (int j = 0; j < NSW - 1; ++j) issue_dma(j);
+  for (int q = wave; q < x_bytes / 1024; q += 4)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xl + q * 1024), 16, (unsigned)(q * 1024 + lane * 16), 0,
+                                             0, 0);
+  for (int idx = threadIdx.x; idx < ROWS * G; idx += 256) {
+    const int row = idx / G, grp = idx - row * G;
+    const int64_t src = (int64_t)(p0 + row < o ? p0 + row : o - 1) * G + grp;
+    sl[row * sb_pitch + grp] = scale[src];
+    bl[row * sb_pitch + grp] = zero[src];
+  }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
+  __syncthreads();
+
+  const unsigned frag_row = ln * 128;
+  const int swz = (ln >> 1) & 7;
+  const int tok = ln < T ? ln : T - 1;
+  const unsigned char* xrow = xl + (size_t)tok * i * 2;
+  const float* srow = sl + ln * sb_pitch;
+  const float* brow = bl + ln * sb_pitch;
+
+  acc_t acc;
+#pragma unroll
+  for (int e = 0; e < NACC; ++e) acc[e] = 0.f;
+
+  for (int j = 0; j < nj; ++j) {
+    issue_dma(j + NSW - 1);
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm((NSW - 1) * NDMA));  // stage j has landed; the NSW - 1 after it may be in flight
+    __builtin_amdgcn_sched_barrier(0);                       // the LDS reads below stay behind the wait
+    const unsigned char* src = ring + (j % NSW) * STAGE + frag_row;
+    const int k0 = (wave + 4 * j) * KS;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(src + (((KG * h + kg) ^ swz) << 4));
+      const int grp = (k0 + h * SUB) / g;
+      const float sc = srow[grp], bz = brow[grp] - K0 * sc;
+      acc_t tw, tx;
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) { tw[e] = 0.f; tx[e] = 0.f; }
+#pragma unroll
+      for (int f = 0; f < FR; ++f) {
+        u32x4 d;
+        if (BITS == 4) {
+          const uint32_t v = w[f];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
+            uint32_t pair;
+            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
+            d[r] = pair;
+          }
+        } else {
+          const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];
+          d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
+          d[1] = pack_bf16x2((float)((v0 >> 16) & 0xFFu) - 128.f, (float)(v0 >> 24) - 128.f);
+          d[2] = pack_bf16x2((float)(v1 & 0xFFu) - 128.f, (float)((v1 >> 8) & 0xFFu) - 128.f);
+          d[3] = pack_bf16x2((float)((v1 >> 16) & 0xFFu) - 128.f, (float)(v1 >> 24) - 128.f);
+        }
+        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+        const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xrow + (size_t)(k0 + (KG * h + kg) * CH + 8 * f) * 2);
+        tw = M::mma(xf, wf, tw);
+        tx = M::mma(xf, ones, tx);
+      }
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) acc[e] = fmaf(bz, tx[e], fmaf(sc, tw[e], acc[e]));
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
+  __syncthreads();  // every wave is done with its ring: the LDS is reused for the sum over the waves
+
+  float* red = reinterpret_cast<float*>(dlds);
+#pragma unroll
+  for (int e = 0; e < NACC; ++e) red[(wave * NACC + e) * 64 + lane] = acc[e];
+  __syncthreads();
+  {
+    const int e = wave;  // wave w finishes register w: token 4 kg + w
+    const float v = (red[(0 * NACC + e) * 64 + lane] + red[(1 * NACC + e) * 64 + lane]) +
+                    (red[(2 * NACC + e) * 64 + lane] + red[(3 * NACC + e) * 64 + lane]);
+    const int t = M::token(e, kg);
+    if (t < T && p < o) Y[(int64_t)t * o + p] = f32_to_bf16(v);
+  }
+#endif
+}
+
+int compute_units() {  // of the current device; asked once per device
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 // rows per workgroup the streaming kernel can use for this layer (0: not at all)
 int qgemm_stream_rows(const LayerDims& d, int tokens_in_pass) {
   if (d.bits != 4 && d.bits != 8) return 0;
@@ -514,6 +680,34 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
                   bf16_t* Y, hipStream_t stream) {
   dim3 grid((unsigned)((d.o + 31) / 32));
   // more than 32 tokens: the general kernel reads the weights once per 64 tokens, the streaming form once per 32
+  // smallest batches: activations and the tile's scale / zero in LDS
+  if (d.T <= 16 && qgemm_stream_rows(d, (int)d.T) == 16) {
+    const int64_t xb = (d.T * d.i * 2 + 1023) / 1024 * 1024;
+    const int64_t G = d.i / d.g, pitch = G | 1;
+    const int64_t sbb = 2 * 16 * pitch * 4;
+    const int64_t tiles = (d.o + 15) / 16;
+    int nsw = tiles <= compute_units() ? 8 : 4;
+    if (4 * nsw * 16 * 128 + xb + sbb > QD_LDS_MAX) nsw = 4;
+    if (xb <= QD_X_MAX && sbb <= QD_SB_MAX && 4 * nsw * 16 * 128 + xb + sbb <= QD_LDS_MAX) {
+      const size_t lds_bytes = (size_t)(4 * nsw * 16 * 128 + xb + sbb);
+      dim3 sgrid((unsigned)tiles);
+      // more than 64 KiB of dynamic LDS has to be allowed per function and device
+#define L4Q_QD(B, N)                                                                                                \
+  do {                                                                                                              \
+    if (lds_bytes > 64 * 1024)                                                                                      \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode_kernel<B, N>),                          \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                                   \
+    hipLaunchKernelGGL((qgemm_decode_kernel<B, N>), sgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y, \
+                       (int)d.T, (int)d.o, (int)d.i, d.g, (int)xb, (int)pitch);                                     \
+  } while (0)
+      if (d.bits == 4 && nsw == 4) L4Q_QD(4, 4);
+      else if (d.bits == 4) L4Q_QD(4, 8);
+      else if (nsw == 4) L4Q_QD(8, 4);
+      else L4Q_QD(8, 8);
+#undef L4Q_QD
+      return;
+    }
+  }
   if (qgemm_stream_rows(d, 32) != 0 && (d.T <= 32 || d.g < 64)) {
     const int step = d.T <= 16 && qgemm_stream_rows(d, 16) == 16 ? 16 : 32;
     for (int t0 = 0; t0 < d.T; t0 += step) {  // the weight stream is read once per pass

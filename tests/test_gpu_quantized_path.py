@@ -47,6 +47,11 @@ def test_packed_export_bit_exact(dtype, bits):
     (5, 640, 88, 8, 64), (40, 1280, 200, 8, 128),         # 8-bit streaming form, 16- and 32-row tiles
     (16, 384, 48, 4, 128),          # packed rows not a whole number of cache lines -> general kernel
     (3, 256, 8, 4, 128),            # one stage, a single partial row tile
+    # activations held in LDS (small batches): both projections at 2..12 tokens, ragged row tile, even and odd
+    # group counts per row, 8-bit, a row length whose activations no longer fit (falls back to register fragments)
+    (2, 4096, 11008, 4, 128), (12, 4096, 11008, 4, 128), (4, 11008, 4096, 4, 128), (5, 11008, 4096, 4, 128),
+    (3, 1024, 1000, 4, 128), (2, 768, 40, 4, 256), (9, 2048, 520, 8, 64), (13, 4096, 264, 4, 64),
+    (1, 28672, 64, 4, 128), (16, 4096, 72, 4, 128),
 ])
 def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g):
     import torch
