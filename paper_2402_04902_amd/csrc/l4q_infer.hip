@@ -643,6 +643,271 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
 #endif
 }
 
+// Batches of 33 .. 64 tokens per pass on wide layers.  One workgroup = 64 weight rows, one 16-row tile per wave, every wave
+// walking the whole row (no k-split), so the four waves consume the same k-stage at the same time and can share its
+// activations: a stage of X (TB x 16 tokens x 128 / BITS x 8 k-values) is put into LDS once per workgroup by DMA,
+// swizzled (chunk c of token t at position c ^ (t % 16)) so that the fragment reads of 16 tokens hit 16 different
+// bank groups.  The weights are streamed exactly as in the kernels above (private ring per wave).  The ring is as deep
+// as 160 KB of LDS allow for the stage size (8 stages for one token block, 3 for four): memory returns in order, so
+// the weight stream from HBM and the activations from the L2 share one prefetch distance.  One barrier per stage
+// makes the shared part visible and frees the slot that is refilled next.
+// The zero-point term needs sum_k X per (token, group), which does not depend on the weight row: wave w forms it for
+// token block w with one extra matrix op per fragment (against ones) and adds it to a table in LDS; after the loop
+// every lane adds sum_g (zero - K0 scale)[row, g] * table[token, g] to its outputs, the first factor staged through
+// the LDS the rings have left.  The scales of the 64 rows sit in LDS too (odd row pitch), so the stage loop issues
+// DMA loads only and its partial waits are exact.
+constexpr int qt_ring_stages(int token_blocks) { return token_blocks == 1 ? 8 : token_blocks == 2 ? 5 : token_blocks == 3 ? 4 : 3; }
+constexpr int QT_ROWQ = 6;  // 16-byte pieces of a 64-row scale / zero block per thread: groups per row <= 96
+
+template <int BITS, int TB>
+__global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restrict__ X,
+                                                         const uint32_t* __restrict__ packed,
+                                                         const float* __restrict__ scale,
+                                                         const float* __restrict__ zero, bf16_t* __restrict__ Y,
+                                                         int T, int t0, int o, int i, int g, int sx_pitch) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char tlds[];
+#if defined(__HIP_DEVICE_COMPILE__)
+  static_assert(BITS == 4 || BITS == 8, "bits");
+  static_assert(TB >= 1 && TB <= 4, "token blocks of 16");
+  typedef QsMfma<16> M;
+  typedef typename M::acc_t acc_t;
+  constexpr int KG = 4, NH = 2, NDMA = 2;
+  constexpr int QT_NS = qt_ring_stages(TB);
+  constexpr int CH = 128 / BITS, KS = 8 * CH, FR = CH / 8, SUB = KG * CH;
+  constexpr int WSTAGE = 16 * 128;            // bytes of a weight stage of one wave
+  constexpr int XROW = KS * 2;                // bytes of a token's activations in a stage
+  constexpr int XSTAGE = TB * 16 * XROW;      // bytes of the shared activation stage
+  constexpr int NXW = XSTAGE / 1024 / 4;      // wave-wide activation loads per wave and stage
+  constexpr int LOADS = NDMA + NXW;           // DMA loads per wave and stage
+  constexpr float K0 = BITS == 8 ? 0.f : 128.f + (float)(1 << (BITS - 1));
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef gemm::lds_ptr_t lds_ptr_t;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ln = lane % 16, kg = lane / 16;
+  const int p0 = blockIdx.x * 64 + wave * 16;  // first row of this wave's tile
+  const int p = p0 + ln;
+  const int pc = p < o ? p : o - 1;
+  const int rb = i / 8 * BITS;
+  const int nst = rb / 128;
+  const int G = i / g;
+  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
+
+  unsigned char* wring = tlds + wave * (QT_NS * WSTAGE);
+  unsigned char* xring = tlds + 4 * QT_NS * WSTAGE;
+  float* sx = reinterpret_cast<float*>(xring + QT_NS * XSTAGE);  // [TB * 16][sx_pitch] sums of X per token and group
+  float* sl = sx + TB * 16 * sx_pitch;                           // [64][sx_pitch] scale of the workgroup's rows
+
+  const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(packed), 0, (int)((int64_t)o * rb), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcX = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(X), 0, (int)((int64_t)T * i * 2), 0x00020000);
+  unsigned voffW[NDMA], voffX[NXW];
+#pragma unroll
+  for (int q = 0; q < NDMA; ++q) {
+    const int r = 8 * q + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+    voffW[q] = p0 + r < o ? (unsigned)((p0 + r) * rb + chunk * 16) : gemm::OOB_OFFSET;
+  }
+#pragma unroll
+  for (int q = 0; q < NXW; ++q) {  // this wave's pieces of the shared stage: LDS bytes [(wave NXW + q) 1024 + 16 lane, +16)
+    const int pos = (wave * NXW + q) * 1024 + lane * 16;
+    const int tok = pos / XROW, cpos = (pos % XROW) / 16;
+    const int chunk = cpos ^ (tok & 15);
+    voffX[q] = t0 + tok < T ? (unsigned)(((int64_t)(t0 + tok) * i) * 2 + chunk * 16) : gemm::OOB_OFFSET;
+  }
+  auto issue_dma = [&](int j) {  // stage j into ring slot j % QT_NS; past the end of k: zeros, no traffic
+    const bool live = j < nst;
+    const unsigned kw = live ? (unsigned)j * 128u : gemm::PAST_END_OFFSET;
+    const unsigned kx = live ? (unsigned)j * (unsigned)XROW : gemm::PAST_END_OFFSET;
+    unsigned char* wdst = wring + (j % QT_NS) * WSTAGE;
+    unsigned char* xdst = xring + (j % QT_NS) * XSTAGE + wave * NXW * 1024;
+#pragma unroll
+    for (int q = 0; q < NDMA; ++q)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcW, (lds_ptr_t)(wdst + q * 1024), 16, voffW[q] + kw, 0, 0, 0);
+#pragma unroll
+    for (int q = 0; q < NXW; ++q)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xdst + q * 1024), 16, voffX[q] + kx, 0, 0, 0);
+  };
+  const float* srow = sl + (wave * 16 + ln) * sx_pitch;
+
+  // The scale / zero rows of the workgroup's 64 weight rows are one contiguous block of 64 G floats (rows past the
+  // matrix read as zero through the buffer range): each thread fetches up to QT_ROWQ pieces of 4 floats, all requested
+  // before the first is used, and scatters them into rows of odd pitch.
+  const __amdgpu_buffer_rsrc_t rsrcS = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(scale), 0, (int)((int64_t)o * G * 4), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(zero), 0, (int)((int64_t)o * G * 4), 0x00020000);
+  auto load_rows = [&](const __amdgpu_buffer_rsrc_t& rsrc, float4 (&rows)[QT_ROWQ]) {
+#pragma unroll
+    for (int q = 0; q < QT_ROWQ; ++q) {
+      const int idx = (q * 256 + (int)threadIdx.x) * 4;
+      const unsigned off = idx < 64 * G ? (unsigned)(((int64_t)blockIdx.x * 64 * G + idx) * 4) : gemm::OOB_OFFSET;
+      rows[q] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
+    }
+  };
+  auto store_rows = [&](const float4 (&rows)[QT_ROWQ], auto&& put) {
+#pragma unroll
+    for (int q = 0; q < QT_ROWQ; ++q) {
+      const int idx = (q * 256 + (int)threadIdx.x) * 4;
+      const float v[4] = {rows[q].x, rows[q].y, rows[q].z, rows[q].w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int row = (idx + c) / G, grp = (idx + c) - row * G;
+        if (idx + c < 64 * G) put(row * sx_pitch + grp, v[c]);
+      }
+    }
+  };
+
+  acc_t acc[TB];
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[tb][e] = 0.f;
+
+  const unsigned frag_row = ln * 128;
+  const int swz = (ln >> 1) & 7;
+
+  const int own = wave < TB ? wave : TB - 1;
+  auto consume = [&](int j) {
+    const unsigned char* wsrc = wring + (j % QT_NS) * WSTAGE + frag_row;
+    const unsigned char* xsrc = xring + (j % QT_NS) * XSTAGE;
+    const int st = j < nst ? j : nst - 1;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      // every LDS read of the sub-step is issued before the first use: one exposed latency per sub-step
+      const u32x4 w = *reinterpret_cast<const u32x4*>(wsrc + (((KG * h + kg) ^ swz) << 4));
+      bf16x8_t xf[FR][TB], xo[FR];
+#pragma unroll
+      for (int f = 0; f < FR; ++f) {
+        const int cpos = ((KG * h + kg) * FR + f) ^ ln;  // swizzled chunk position of this lane's token
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+          xf[f][tb] = *reinterpret_cast<const bf16x8_t*>(xsrc + (tb * 16 + ln) * XROW + cpos * 16);
+        // this wave sums token block `own` (waves beyond the last block repeat it and discard the result); a second
+        // read of that fragment instead of a branch on the wave index keeps the sub-step one straight block
+        xo[f] = *reinterpret_cast<const bf16x8_t*>(xsrc + (own * 16 + ln) * XROW + cpos * 16);
+      }
+      const int grp = (st * KS + h * SUB) / g;
+      const float sc = srow[grp];
+      __builtin_amdgcn_sched_barrier(0);
+      acc_t tw[TB], tx;
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tw[tb][e] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) tx[e] = 0.f;
+#pragma unroll
+      for (int f = 0; f < FR; ++f) {
+        u32x4 d;
+        if (BITS == 4) {
+          const uint32_t v = w[f];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
+            uint32_t pair;
+            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
+            d[r] = pair;
+          }
+        } else {
+          const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];
+          d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
+          d[1] = pack_bf16x2((float)((v0 >> 16) & 0xFFu) - 128.f, (float)(v0 >> 24) - 128.f);
+          d[2] = pack_bf16x2((float)(v1 & 0xFFu) - 128.f, (float)((v1 >> 8) & 0xFFu) - 128.f);
+          d[3] = pack_bf16x2((float)((v1 >> 16) & 0xFFu) - 128.f, (float)(v1 >> 24) - 128.f);
+        }
+        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) tw[tb] = M::mma(xf[f][tb], wf, tw[tb]);
+        tx = M::mma(xo[f], ones, tx);
+      }
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[tb][e] = fmaf(sc, tw[tb][e], acc[tb][e]);
+      if (wave < TB && ln == 0 && j < nst) {  // every column of tx holds the same sums: one lane per token writes
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float* cell = sx + (wave * 16 + M::token(e, kg)) * sx_pitch + grp;
+          *cell += tx[e];  // the only writer of this cell
+        }
+      }
+    }
+  };
+
+  // The first QT_NS - 1 stages are requested, then the tables are set up: sums zeroed, scales of the 64 rows copied in.
+#pragma unroll
+  for (int j = 0; j < QT_NS - 1; ++j) issue_dma(j);
+  for (int idx = threadIdx.x; idx < TB * 16 * sx_pitch; idx += 256) sx[idx] = 0.f;
+  {
+    float4 rows[QT_ROWQ];
+    load_rows(rsrcS, rows);
+    store_rows(rows, [&](int at, float v) { sl[at] = v; });
+  }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));  // these stages and the table loads have landed
+  __builtin_amdgcn_sched_barrier(0);
+  // From here on the only vector-memory operations are the DMA loads: after the DMA of stage j + 1, by the end of
+  // stage j, the DMA of stages j + 2 .. j + QT_NS - 1 has been issued.
+  static_assert((QT_NS - 2) * LOADS <= 63, "vmcnt is a 6-bit counter");
+  for (int j = 0; j < nst; j += 2) {
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_lgkm0());
+    __builtin_amdgcn_s_barrier();  // stage j is complete for every wave; every wave is done with stage j - 1
+    __builtin_amdgcn_sched_barrier(0);
+    issue_dma(j + QT_NS - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(j);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm((QT_NS - 2) * LOADS));  // stage j + 1 has landed
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_lgkm0());
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    issue_dma(j + QT_NS);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(j + 1);  // with an odd stage count this is a stage of zeros: it adds nothing
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm((QT_NS - 2) * LOADS));  // stage j + 2 has landed
+  }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
+  __syncthreads();  // the sum table is complete and the rings are free
+
+  // (zero - K0 scale) of the workgroup's 64 rows into the ring space, rows padded to an odd pitch
+  float* bzl = reinterpret_cast<float*>(tlds);
+  const int bz_pitch = sx_pitch;
+  {
+    float4 srows[QT_ROWQ], zrows[QT_ROWQ];
+    load_rows(rsrcS, srows);
+    load_rows(rsrcZ, zrows);
+#pragma unroll
+    for (int q = 0; q < QT_ROWQ; ++q) {
+      zrows[q].x -= K0 * srows[q].x; zrows[q].y -= K0 * srows[q].y;
+      zrows[q].z -= K0 * srows[q].z; zrows[q].w -= K0 * srows[q].w;
+    }
+    store_rows(zrows, [&](int at, float v) { bzl[at] = v; });
+  }
+  __syncthreads();
+
+  // zero-point term and store: register e of token block tb is token 16 tb + 4 kg + e of row p
+  const float* bzrow = bzl + (wave * 16 + ln) * bz_pitch;
+  for (int grp = 0; grp < G; ++grp) {
+    const float bz = bzrow[grp];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        acc[tb][e] = fmaf(bz, sx[(tb * 16 + M::token(e, kg)) * sx_pitch + grp], acc[tb][e]);
+  }
+#pragma unroll
+  for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int t = t0 + tb * 16 + M::token(e, kg);
+      if (t < T && p < o) Y[(int64_t)t * o + p] = f32_to_bf16(acc[tb][e]);
+    }
+#endif
+}
+
 int compute_units() {  // of the current device; asked once per device
   static int cached[64] = {0};
   int dev = 0;
@@ -705,6 +970,46 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
       else if (nsw == 4) L4Q_QD(8, 4);
       else L4Q_QD(8, 8);
 #undef L4Q_QD
+      return;
+    }
+  }
+  // larger batches: 64-row tiles that share each activation stage through LDS, up to 64 tokens per pass
+  if (qgemm_stream_rows(d, 16) == 16) {
+    const int xrow = 8 * (128 / d.bits) * 2;
+    const int64_t G = d.i / d.g, pitch = G | 1;
+    // LDS of a pass of tb token blocks: rings, sum table, scale table; the zero-point table reuses the rings
+    const auto rings_of = [&](int tb) {
+      return (int64_t)qt_ring_stages(tb) * (4 * 2048 + (int64_t)tb * 16 * xrow);
+    };
+    const auto lds_of = [&](int tb) { return rings_of(tb) + (int64_t)(tb * 16 + 64) * pitch * 4; };
+    int tb_max = 0;
+    for (int tb = 1; tb <= 4; ++tb)
+      if (lds_of(tb) <= QD_LDS_MAX && 64 * pitch * 4 <= rings_of(tb) && 64 * G <= QT_ROWQ * 1024) tb_max = tb;
+    // Worth it only when the 64-row tiles give most compute units a workgroup, and beyond 32 tokens: a wave walks its
+    // whole row alone here, which for fewer tokens loses to the k-split of the streaming kernel (measured at
+    // [11008 x 4096]: 19 vs 22 us at 16 tokens, 26 vs 25 at 32, 38 vs 55 at 64).
+    if ((d.o + 63) / 64 < compute_units() / 2 || d.T <= 32) tb_max = 0;
+    if (tb_max > 0) {
+      dim3 tgrid((unsigned)((d.o + 63) / 64));
+      for (int t0 = 0; t0 < d.T; t0 += 16 * tb_max) {
+        const int n = (int)d.T - t0 < 16 * tb_max ? (int)d.T - t0 : 16 * tb_max;
+        const int tb = (n + 15) / 16;
+        const size_t lds_bytes = (size_t)lds_of(tb);
+#define L4Q_QT(B, N)                                                                                                 \
+  do {                                                                                                               \
+    if (lds_bytes > 64 * 1024)                                                                                       \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_tile_kernel<B, N>),                             \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                             \
+    hipLaunchKernelGGL((qgemm_tile_kernel<B, N>), tgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y,    \
+                       (int)d.T, t0, (int)d.o, (int)d.i, d.g, (int)pitch);                                           \
+  } while (0)
+        if (d.bits == 4) {
+          if (tb == 1) L4Q_QT(4, 1); else if (tb == 2) L4Q_QT(4, 2); else if (tb == 3) L4Q_QT(4, 3); else L4Q_QT(4, 4);
+        } else {
+          if (tb == 1) L4Q_QT(8, 1); else if (tb == 2) L4Q_QT(8, 2); else if (tb == 3) L4Q_QT(8, 3); else L4Q_QT(8, 4);
+        }
+#undef L4Q_QT
+      }
       return;
     }
   }
