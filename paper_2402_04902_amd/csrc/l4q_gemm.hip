@@ -17,15 +17,11 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // Direct-to-LDS ring pipeline (l4q_gemm_core.h) + plain store epilogue.  Operands below 1 GiB.
 // ---------------------------------------------------------------------------------------------
-template <class T, bool OUT_BF16, bool A_KM = false, bool B_KM = false>
-__global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                                   const bf16_t* __restrict__ B, int64_t ldb, int M,
-                                                                   int N, int K, void* __restrict__ Cout,
-                                                                   int64_t ldc, int tiles_m, int tiles_n) {
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
-  int tile_m, tile_n;
-  gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-  const int m0 = tile_m * T::BM, n0 = tile_n * T::BN;
+// One macro tile: main loop, then the store epilogue.
+template <class T, bool OUT_BF16, bool A_KM, bool B_KM>
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                                          int64_t ldb, int M, int N, int K, void* __restrict__ Cout, int64_t ldc,
+                                          int m0, int n0, unsigned char* lds) {
   gemm::Accum<T> acc;
 #pragma unroll
   for (int a = 0; a < T::TM; ++a)
@@ -86,6 +82,17 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* 
   }
 }
 
+template <class T, bool OUT_BF16, bool A_KM = false, bool B_KM = false>
+__global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                   const bf16_t* __restrict__ B, int64_t ldb, int M,
+                                                                   int N, int K, void* __restrict__ Cout,
+                                                                   int64_t ldc, int tiles_m, int tiles_n) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+  int tile_m, tile_n;
+  gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  gemm_tile<T, OUT_BF16, A_KM, B_KM>(A, lda, B, ldb, M, N, K, Cout, ldc, tile_m * T::BM, tile_n * T::BN, lds);
+}
+
 // Matrix-core-only loop with the GEMM's register shape (4 x 4 accumulator tiles, 8 fragments per wave) and
 // no memory traffic inside the loop: what the matrix pipeline sustains on this chip for the given data.
 __global__ __launch_bounds__(256) void mfma_probe_kernel(const bf16_t* __restrict__ data, int iterations,
@@ -129,6 +136,18 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const bf16_t* __restric
 double launch_mfma_probe(const bf16_t* data, int iterations, int workgroups, float* sink, hipStream_t stream) {
   hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, data, iterations, sink);
   return (double)workgroups * 4.0 * (double)iterations * 16.0 * (2.0 * 32 * 32 * 16);
+}
+
+int device_compute_units() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
 }
 
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,

@@ -908,18 +908,6 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
 #endif
 }
 
-int compute_units() {  // of the current device; asked once per device
-  static int cached[64] = {0};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
-}
-
 // rows per workgroup the streaming kernel can use for this layer (0: not at all)
 int qgemm_stream_rows(const LayerDims& d, int tokens_in_pass) {
   if (d.bits != 4 && d.bits != 8) return 0;
@@ -951,7 +939,7 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     const int64_t G = d.i / d.g, pitch = G | 1;
     const int64_t sbb = 2 * 16 * pitch * 4;
     const int64_t tiles = (d.o + 15) / 16;
-    int nsw = tiles <= compute_units() ? 8 : 4;
+    int nsw = tiles <= device_compute_units() ? 8 : 4;
     if (4 * nsw * 16 * 128 + xb + sbb > QD_LDS_MAX) nsw = 4;
     if (xb <= QD_X_MAX && sbb <= QD_SB_MAX && 4 * nsw * 16 * 128 + xb + sbb <= QD_LDS_MAX) {
       const size_t lds_bytes = (size_t)(4 * nsw * 16 * 128 + xb + sbb);
@@ -988,7 +976,7 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     // Worth it only when the 64-row tiles give most compute units a workgroup, and beyond 32 tokens: a wave walks its
     // whole row alone here, which for fewer tokens loses to the k-split of the streaming kernel (measured at
     // [11008 x 4096]: 19 vs 22 us at 16 tokens, 26 vs 25 at 32, 38 vs 55 at 64).
-    if ((d.o + 63) / 64 < compute_units() / 2 || d.T <= 32) tb_max = 0;
+    if ((d.o + 63) / 64 < device_compute_units() / 2 || d.T <= 32) tb_max = 0;
     if (tb_max > 0) {
       dim3 tgrid((unsigned)((d.o + 63) / 64));
       for (int t0 = 0; t0 < d.T; t0 += 16 * tb_max) {

@@ -51,6 +51,9 @@ template <class T>
 void launch_quant_errors(const LayerDims& d, const T* W0, const T* A, const T* B, const float* scale,
                          const float* zero, float* partial, float* out2, hipStream_t stream);
 
+// compute units of the current device (asked once per device, then cached)
+int device_compute_units();
+
 // ---- bf16 MFMA GEMM  C[M,N] = A[M,K] . B[N,K]^T, fp32 accumulate, bf16 output ----
 // A, B row-major and K-contiguous with leading dimensions lda, ldb (elements, multiples of 8).  B must hold
 // zeros for k in [K_true, K) where K is rounded up to 32; A may be read past its row end there.
