@@ -53,12 +53,82 @@ def cpu_baseline(specs, host_inputs):
             "sample": "whole workload: one fwd+bwd of both layers at T=4096 (float64 numpy oracle, OpenBLAS matmul)"}
 
 
+def device_layers(specs, seed):
+    """Layers of a configuration with inputs drawn on the GPU (same distributions as the host generator, no
+    outlier mask; timing only, no parity), one workspace shared by all of them."""
+    import torch
+    from paper_2402_04902_amd import binding
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed)
+    dev, bf = torch.device("cuda:0"), torch.bfloat16
+
+    def randn(shape, std):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std).to(bf)
+    f32 = dict(dtype=torch.float32, device=dev)
+    need = [binding.l4q_workspace_bytes(binding.make_desc(sp)) for sp in specs]
+    ws = torch.empty(max(max(f, b) for f, b in need), dtype=torch.uint8, device=dev)
+    layers = []
+    for sp, (fb, bb) in zip(specs, need):
+        T, i, o, r, G = sp.tokens, sp.in_features, sp.out_features, sp.rank, sp.groups
+        a_bound = 1.0 / (i ** 0.5)
+        A = ((torch.rand((r, i), generator=gen, device=dev) * 2 - 1) * a_bound).to(bf)
+        layer = binding.DeviceLayer(
+            spec=sp, desc=binding.make_desc(sp), X=randn((T, i), 1.0), W0=randn((o, i), 0.02), A=A,
+            B=randn((o, r), 1e-3), dY=randn((T, o), 1e-2), scale=torch.empty((o, G), **f32),
+            zero=torch.empty((o, G), **f32), Y=torch.empty((T, o), dtype=bf, device=dev),
+            dX=torch.empty((T, i), dtype=bf, device=dev), dA=torch.empty((r, i), **f32),
+            dB=torch.empty((o, r), **f32), dscale=torch.empty((o, G), **f32), dzero=torch.empty((o, G), **f32),
+            ws=ws, fwd_bytes=fb, bwd_bytes=bb)
+        binding.l4q_init_qparams(layer.desc, layer.W0, layer.A, layer.B, binding.INIT_ASYMM, layer.scale, layer.zero)
+        layers.append(layer)
+    return layers
+
+
+def measure_config(specs, seed, steps=5, warmup=2):
+    """fwd+bwd of every layer of a configuration: ms per pass (median, min), TFLOP/s, memory figures."""
+    import torch
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    before = torch.cuda.memory_allocated()
+    layers = device_layers(specs, seed)
+    resident = torch.cuda.memory_allocated() - before
+
+    def step():
+        for layer in layers:
+            layer.forward()
+        for layer in reversed(layers):
+            layer.backward()
+    for _ in range(warmup):
+        step()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evs[0].record()
+    for k in range(steps):
+        step()
+        evs[k + 1].record()
+    torch.cuda.synchronize()
+    ms = sorted(evs[k].elapsed_time(evs[k + 1]) for k in range(steps))
+    flops = sum(sp.gemm_flops() for sp in specs)
+    med = ms[len(ms) // 2]
+    out = {"layers": len(specs), "tokens": specs[0].tokens, "bits": specs[0].bits,
+           "ms_median": med, "ms_min": ms[0], "TFLOP_per_s": flops / (med * 1e-3) / 1e12,
+           "kept_fwd_to_bwd_bytes": sum(sp.tokens * sp.in_features * 2 for sp in specs),
+           "plain_lora_would_keep_bytes": sum(sp.tokens * (sp.in_features + sp.rank) * 2 for sp in specs),
+           "workspace_bytes": int(layers[0].ws.numel()),
+           "resident_bytes_inputs_outputs_workspace": int(resident),
+           "peak_allocated_delta_bytes": int(torch.cuda.max_memory_allocated() - before)}
+    del layers
+    torch.cuda.empty_cache()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short timings of the other published configurations (C2, C4, C5)")
     ap.add_argument("--tokens", type=int, default=4096, help=argparse.SUPPRESS)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for the FETCH_SIZE/WRITE_SIZE counters)")
@@ -102,11 +172,15 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     binding.l4q_profile_gemm(True)
+    step_events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    step_events[0].record()
+    for k in range(args.steps):
         step()
+        step_events[k + 1].record()  # recorded, not waited for: per-step figures without a host sync inside
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_step = sorted(step_events[k].elapsed_time(step_events[k + 1]) for k in range(args.steps))
     gemm_ms, gemm_launches, gemm_flops = binding.l4q_profile_gemm_read()
     binding.l4q_profile_gemm(False)
 
@@ -183,7 +257,8 @@ def main() -> int:
     out = {
         "metric": "L4Q linear fwd+bwd TFLOP/s & % bf16 MFMA peak (LLaMA-7B MLP, 4-bit g128)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "ms_per_step_median": per_step[len(per_step) // 2],
+        "ms_per_step_min": per_step[0], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "pct_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
         "config": {"workload": "LLaMA-7B MLP up [11008x4096] + down [4096x11008], T=%d, r=16, alpha=32, "
@@ -203,9 +278,19 @@ def main() -> int:
     out["qat_lora_same_workload"] = {"ms_per_step": qat_ms, "workspace_bytes_fwd": max(qws_f),
                                      "workspace_bytes_bwd": max(qws_b),
                                      "l4q_speedup": qat_ms / ms_per_step}
+    del layers, packs
+    torch.cuda.empty_cache()
+    if not args.no_other_configs:
+        # the other published configurations, timed briefly (5 passes each); C3 above is the headline
+        c4 = inputs.config4()
+        out["other_configs"] = {
+            "C2_llama7b_attn_4096x4096": measure_config(inputs.config2(), 20),
+            "C4_llama7b_mlp_3bit_g128": measure_config(c4[:2], 40),
+            "C4_llama7b_up_3bit_g64": measure_config(c4[2:3], 41),
+            "C4_llama7b_up_3bit_g256": measure_config(c4[3:4], 42),
+            "C5_mistral7b_seven_layers_T8192": measure_config(inputs.config5(), 50),
+        }
     if not args.no_cpu_baseline:
-        del layers
-        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(specs, host_inputs)
     print(json.dumps(out))
     return 0
