@@ -247,6 +247,24 @@ def main() -> int:
     qat_ms = ev0.elapsed_time(ev1) / 10
     del qws
 
+    # context: the six plain GEMMs of a step through the vendor library (torch.matmul -> hipBLASLt), same shapes and
+    # operand layouts, no quantizer work at all; not part of the product path
+    def vendor_six():
+        for l in layers:
+            torch.matmul(l.X, l.W0.t(), out=l.Y)                     # Y  = X W^T
+        for l in reversed(layers):
+            torch.matmul(l.dY, l.W0, out=l.dX)                       # dX = dY W
+            torch.matmul(l.dY.t(), l.X)                              # dW = dY^T X
+    for _ in range(3):
+        vendor_six()
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(10):
+        vendor_six()
+    ev1.record()
+    torch.cuda.synchronize()
+    vendor_ms = ev0.elapsed_time(ev1) / 10
+
     flops_per_step = sum(s.gemm_flops() for s in specs)
     ms_per_step = elapsed * 1e3 / args.steps
     tflops = flops_per_step / (ms_per_step * 1e-3) / 1e12
@@ -290,6 +308,9 @@ def main() -> int:
             "C4_llama7b_up_3bit_g256": measure_config(c4[3:4], 42),
             "C5_mistral7b_seven_layers_T8192": measure_config(inputs.config5(), 50),
         }
+    out["vendor_gemm_reference"] = {"what": "the step's six GEMMs alone via torch.matmul (hipBLASLt), bf16",
+                                    "ms": vendor_ms, "TFLOP_per_s": flops_per_step / (vendor_ms * 1e-3) / 1e12,
+                                    "l4q_step_over_vendor_gemms": ms_per_step / vendor_ms}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, host_inputs)
     print(json.dumps(out))
