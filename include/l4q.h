@@ -85,8 +85,8 @@ enum {
   L4Q_FLAG_ACCUMULATE_GRADS = 2
 };
 
-/* Shape rules: tokens, in_features, out_features, rank >= 1; group_size >= 4, group_size % 4
- * == 0, in_features % group_size == 0; 2 <= bits <= 8; rank <= 256.
+/* Shape rules: tokens, in_features, out_features, rank >= 1; group_size a power of two >= 4,
+ * in_features % group_size == 0; 2 <= bits <= 8; rank <= 256.
  * BF16 additionally: group_size % 8 == 0 and out_features % 8 == 0 (16-byte rows), and each of
  * tokens*in_features, tokens*out_features, out_features*in_features below 2^29 - 2^20 elements. */
 typedef struct l4q_desc {

@@ -81,6 +81,32 @@ def test_bf16_small_shapes(T, i, o, r, bits, g, shrink):
         assert rep["clipped"] > 0
 
 
+def _random_cases(count=16, seed=2402):
+    """Seeded draw of layer shapes: group a power of two, in-features a multiple of it, ranks on both sides of the
+    fused epilogue's limit, every code width, both storage types, scale shrunk so that some weights clip."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        bf16 = k % 3 != 0
+        g = int(rng.choice([8, 16, 32, 64, 128, 256] if bf16 else [4, 8, 32, 64]))
+        i = g * int(rng.integers(1, 13 if g <= 64 else 7))
+        o = 8 * int(rng.integers(1, 90)) if bf16 else int(rng.integers(1, 300))
+        T = int(rng.integers(1, 600))
+        r = int(rng.choice([1, 4, 8, 16, 64]))
+        bits = int(rng.choice([2, 3, 4, 8]))
+        shrink = float(rng.choice([1.0, 0.8, 0.6]))
+        cases.append((k, T, i, o, r, bits, g, DTYPE_BF16 if bf16 else DTYPE_F32, shrink))
+    return cases
+
+
+@pytest.mark.parametrize("k,T,i,o,r,bits,g,dtype,shrink", _random_cases())
+def test_random_shapes(k, T, i, o, r, bits, g, dtype, shrink):
+    spec = LayerSpec(f"rand{k}_{T}x{i}x{o}", T, i, o, r, 2.0 * r, bits, g, dtype)
+    rep, _, _ = run_case(spec, seed=1000 + k, shrink=shrink)
+    if shrink < 1.0:
+        assert rep["clipped"] > 0
+
+
 @pytest.mark.parametrize("T,i,o,r,bits,g", [(300, 640, 264, 16, 4, 128), (513, 768, 1032, 8, 4, 64)])
 def test_bf16_unfused_backward_flag(T, i, o, r, bits, g):
     """The unfused backward (dWq through the workspace) must agree with the oracle as well."""
