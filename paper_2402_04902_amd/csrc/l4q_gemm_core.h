@@ -247,9 +247,10 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     // cache, and the L2 delivers every line twice (measured: twice the read sectors of a 64-k stage).  Here the
     // two stages that share a line, 2 j and 2 j + 1, are requested by back-to-back instructions, so the second
     // request meets the line while it is still being filled.  Ring of five stages: while stage s (even) and
-    // s + 1 are consumed, pair (s + 2, s + 3) has landed or is landing, and pair (s + 4, s + 5) is issued during
-    // stage s + 1 into the slots that stages s - 1 and s vacated.  Each pair is therefore issued two full stages
-    // before its first use.  An odd stage count is rounded up: the extra stage is loaded as zeros.
+    // s + 1 are consumed, pair (s + 2, s + 3) has landed or is landing, and pair (s + 4, s + 5) is issued from the
+    // middle of stage s on, as soon as every wave has left stage s, into the slots that stages s - 1 and s vacated.
+    // Each pair is therefore issued two and a half stages before its first use.  An odd stage count is rounded up:
+    // the extra stage is loaded as zeros.
     static_assert(!T::PAIR || (!A_KM && !B_KM && T::KK == 2), "paired loading is for K-contiguous operands");
     auto issue_pair = [&](int stage0, int slot0, int slot1, int part) {
       const unsigned k0 = stage0 < nk ? (unsigned)stage0 * stage_bytes_a : PAST_END_OFFSET;
@@ -290,7 +291,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
       if (n2 == T::NS) n2 = 0;
       int p0 = slot + 4;
       if (p0 >= T::NS) p0 -= T::NS;
-      // even stage: no loads.  Its partner stage landed together with it.
+      // stage s, first half: no loads.  Its partner stage landed together with it.
       read_frags_a(slot, 1, 1);
       read_frags_b(slot, 1, 1);
       mfma_block(0);
@@ -303,20 +304,14 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
       __builtin_amdgcn_sched_barrier(0);  // the matrix ops above stay ahead of the wait: they cover the LDS latency
       __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
       __builtin_amdgcn_s_barrier();  // every wave is done reading `slot`: the pair issued below may refill it
+      // stage s, second half, and stage s + 1, first half: the two parts of pair (s + 4, s + 5) go into the slots
+      // of stages s - 1 and s as early as those are free (the operands come from the L2 of another XCD or from the
+      // memory side more often than not, and every k-step of lead counts: issuing half a stage later costs 1-2 %,
+      // a whole stage later 8 %)
       read_frags_a(n1, 0, 0);
       read_frags_b(n1, 0, 0);
-      mfma_block(1);
-#pragma unroll
-      for (int q = 0; q < NDA + NDB; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, NMF - NDA - NDB, 0);  // the rest stay on this side of the barrier
-      // odd stage: issues the pair (s + 4, s + 5) into the slots of stages s - 1 and s
-      read_frags_a(n1, 1, 1);
-      read_frags_b(n1, 1, 1);
       issue_pair(s + 4, p0, slot, 0);
-      mfma_block(0);
+      mfma_block(1);
 #pragma unroll
       for (int q = 0; q < NDA + NDB; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -327,15 +322,10 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       }
-      // pair (s + 2, s + 3) was issued a stage and a half ago; only this stage's first part may still be in flight
-      __builtin_amdgcn_sched_barrier(0);
-      __builtin_amdgcn_s_waitcnt(waitcnt_vm(PAIR_A));
-      __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
-      __builtin_amdgcn_s_barrier();
-      read_frags_a(n2, 0, 0);
-      read_frags_b(n2, 0, 0);
+      read_frags_a(n1, 1, 1);
+      read_frags_b(n1, 1, 1);
       issue_pair(s + 4, p0, slot, 1);
-      mfma_block(1);
+      mfma_block(0);
 #pragma unroll
       for (int q = 0; q < NDA + NDB; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -346,6 +336,21 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       }
+      // pair (s + 2, s + 3) was issued an iteration ago; only the pair issued above may still be in flight
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm(PAIR_A + PAIR_B));
+      __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
+      __builtin_amdgcn_s_barrier();
+      // stage s + 1, second half: no loads
+      read_frags_a(n2, 0, 0);
+      read_frags_b(n2, 0, 0);
+      mfma_block(1);
+#pragma unroll
+      for (int q = 0; q < NDA + NDB; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, NMF - NDA - NDB, 0);
       slot = n2;
     }
   } else {
