@@ -312,11 +312,11 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     mq.wqT = w.wqT;
     mq.ld_wqT = w.opad;
     mq.fgrad = w.fgrad;  // null when unfused
+    mq.bT = w.fused ? w.bT : nullptr;
     l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, mq, stream);
     // dWq = dY^T . X, both operands read as they lie in memory.  The fused kernel goes first: the factor array the
     // merge pass has just written is then still in the memory-side cache when the epilogues ask for it.
     if (w.fused) {
-      l4q::launch_transpose_lora_b(Bb, d.o, d.r, w.bT, w.opad, stream);
       dw_fused(d, w, (const bf16_t*)dY, (const bf16_t*)X, Ab, dscale, dzero, stream);
       l4q::launch_reduce_two_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, dA, w.dB_part, 2 * w.tiles_n,
                                       d.o * d.r, dB, d.gamma, d.accumulate, stream);

@@ -27,6 +27,7 @@ struct MergeQuantOut {
   int64_t ld_wq = 0;
   bf16_t* wqT = nullptr;     // Wq^T [i, ld_wqT] bf16; columns o..ld_wqT-1 are written as zeros (bf16 mode only)
   int64_t ld_wqT = 0;        // multiple of 8
+  bf16_t* bT = nullptr;      // B^T [r, ld_wqT] bf16 for the fused backward; columns o..ld_wqT-1 zeros (bf16 mode only)
   uint16_t* fgrad = nullptr; // [o,i] binary16: d(Wq)/d(scale) = code - w in range, code (= Q_N or Q_P) when clipped;
                              // |value| <= 1/2 exactly when the element is in range
   int8_t* codes = nullptr;   // [o,i]
@@ -37,8 +38,6 @@ template <class T>
 void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B, const float* scale,
                         const float* zero, const MergeQuantOut<T>& out, hipStream_t stream);
 
-// B^T [r, ld] from the LoRA factor B [o, r]; columns o..ld-1 zero
-void launch_transpose_lora_b(const bf16_t* B, int64_t o, int r, bf16_t* BT, int64_t ld, hipStream_t stream);
 
 // ---- per-group min/max initialisation (App. B, Eq. quant_inits) ----
 template <class T>
@@ -115,7 +114,7 @@ void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* out
 
 // ---- weight-gradient GEMM with fused quantizer backward (bf16 mode) ----
 // dY [T, o], X [T, i] as the caller holds them; fgrad [o, i] binary16 from launch_merge_quant;
-// BT [r, ld_bt] from launch_transpose_lora_b.  Writes dscale, dzero [o, G] and the partial sums
+// BT [r, ld_bt]: B^T as the backward merge pass leaves it (MergeQuantOut::bT).  Writes dscale, dzero [o, G] and the partial sums
 // dA_part [tiles_m, r, i], dB_part [2 * tiles_n, o, r] (no gamma applied yet).
 bool dw_fused_supported(const LayerDims& d);
 void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n);

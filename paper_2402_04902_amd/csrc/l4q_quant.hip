@@ -318,6 +318,19 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
     }
   }
 
+  if constexpr (MODE == 2 && std::is_same<T, bf16_t>::value) {
+    // The first column tile of every row block also leaves B^T for its 64 rows (the fused weight-gradient kernel's
+    // dA product reads B that way): r x 64 elements, zeros past o up to the padded width.
+    if (blockIdx.x == 0 && out.bT) {
+      const int64_t pblk = (int64_t)blockIdx.y * MQ_ROWS;
+      for (int idx = threadIdx.x; idx < d.r * MQ_ROWS; idx += MQ_THREADS) {
+        const int k = idx / MQ_ROWS;
+        const int64_t p = pblk + idx % MQ_ROWS;
+        if (p < out.ld_wqT) out.bT[(int64_t)k * out.ld_wqT + p] = p < d.o ? B[p * d.r + k] : (bf16_t)0;
+      }
+    }
+  }
+
   if (want_t && (MODE == 2 || out.wqT)) {  // uniform: transpose the 64 x 256 tile through LDS
     // column c of this lane, rows of this wave: 8 bf16 = one 16-byte LDS write
 #pragma unroll
@@ -473,14 +486,6 @@ __global__ __launch_bounds__(256) void sum_error_pairs_kernel(const float* __res
   }
 }
 
-// B^T [r, ld] from B [o, r] (bf16), columns o..ld-1 zero
-__global__ __launch_bounds__(256) void transpose_lora_b_kernel(const bf16_t* __restrict__ B, int64_t o, int r,
-                                                                bf16_t* __restrict__ BT, int64_t ld) {
-  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (p >= ld) return;
-  for (int k = 0; k < r; ++k) BT[(int64_t)k * ld + p] = p < o ? B[p * r + k] : (bf16_t)0;
-}
-
 // One wave per weight row; each lane owns 4 consecutive columns per 256-column step.
 template <class T>
 __global__ __launch_bounds__(kThreads) void init_qparams_kernel(LayerDims d, const T* __restrict__ W0,
@@ -547,11 +552,6 @@ void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B,
     hipLaunchKernelGGL((merge_quant_tile_kernel<T, 2>), grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, scale, zero, out);
   else
     hipLaunchKernelGGL((merge_quant_tile_kernel<T, 0>), grid, dim3(MQ_THREADS), 0, stream, d, W0, A, B, scale, zero, out);
-}
-
-void launch_transpose_lora_b(const bf16_t* B, int64_t o, int r, bf16_t* BT, int64_t ld, hipStream_t stream) {
-  hipLaunchKernelGGL(transpose_lora_b_kernel, dim3((unsigned)((ld + 255) / 256)), dim3(256), 0, stream, B, o, r, BT,
-                     ld);
 }
 
 template <class T>
