@@ -29,7 +29,7 @@ namespace l4q {
 
 namespace {
 
-typedef gemm::Tile<256, 256, 32, 4> T;
+typedef gemm::Tile<256, 256, 32, 5> T;
 static_assert(T::WTM == 128 && T::WTN == 128 && T::TM == 4 && T::TN == 4, "epilogue is written for 128 x 128 wave tiles");
 
 constexpr int EP_ROWB = 256 * 2 + 16;             // bytes per [j] row of the transposed tile: 256 p + pad
@@ -80,8 +80,30 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     for (int b = 0; b < T::TN; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
-  gemm::mainloop<T, true, true>(p.dY, p.o, p.X, p.i, p.o, p.i, p.K, m0, n0, lds, acc);
-  // LDS is free from here on (mainloop ends with a barrier after the last fragment read)
+  // The d(Wq)/d(scale) factors of the tile (128 KiB of a weight-sized array streamed once from HBM) are needed right
+  // after the main loop.  Three quarters of them ride on the loads the loop issues for the three stages past the
+  // end of K: tail stage q brings the factor rows of row block a = q (32 rows of the upper and of the lower wave
+  // row) into the ring slot that stage would have used, 512 bytes per row, the 16-byte chunk c of row l at position
+  // c ^ l so that the 32 rows a wave reads together spread over the banks.  Rows past the matrix lie beyond the
+  // buffer and read as zero; columns past it get an out-of-range offset.
+  typedef gemm::TailLoads<T::A_INSTR, T::B_INSTR> FTail;
+  static_assert(T::D == 4 && T::A_INSTR == 4 && T::B_INSTR == 4 && T::STAGE == 64 * 512, "factor rows per tail stage");
+  FTail ftail;
+  ftail.base = p.fgrad;
+  ftail.bytes = (int)((int64_t)p.o * p.i * 2);
+  ftail.stage_bytes = (unsigned)(32 * p.i * 2);
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int lr = (wave * 4 + c) * 2 + (lane >> 5);  // row inside the 32-row block
+    const int col = n0 + (((lane & 31) ^ lr) << 3);   // first of the 8 columns this lane fetches
+    const bool ok = col < p.i && m0 + lr < p.o;
+    ftail.voff_a[c] = ok ? (unsigned)(((int64_t)(m0 + lr) * p.i + col) * 2) : gemm::OOB_OFFSET;
+    ftail.voff_b[c] = ok && m0 + 128 + lr < p.o ? (unsigned)(((int64_t)(m0 + 128 + lr) * p.i + col) * 2)
+                                                 : gemm::OOB_OFFSET;
+  }
+  gemm::mainloop<T, true, true, FTail>(p.dY, p.o, p.X, p.i, p.o, p.i, p.K, m0, n0, lds, acc, ftail);
+  // the operand stages are consumed (mainloop ends with a barrier after the last fragment read); slots
+  // (nk + q) % 4, q = 0 .. 2, hold the factor rows
 
   // ---- fragments of the LoRA factor A for the dB product: lane = rank index, 8 k-slots = the same
   //      column pattern the accumulator registers 8h .. 8h+7 of a lane group have
@@ -100,24 +122,26 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     }
   }
 
-  // The d(Wq)/d(scale) factors this lane needs: 64 pieces of 4 consecutive columns, one per (row block, column tile,
-  // register group), all requested here so that their latency (the factor array is streamed once from HBM) is paid
-  // once per tile and not once per row block.  Rows and columns past the matrix are clamped to a valid address; their
-  // accumulators are exactly zero, so whatever finite factor is read there contributes nothing.
+  // The factors this lane needs: 64 pieces of 4 consecutive columns, one per (row block, column tile, register
+  // group).  Row block 3 comes from memory (requested first; it is used last); blocks 0 .. 2 are read out of the
+  // ring slots, after which the LDS is free for the epilogue.  Rows and columns past the matrix: the memory loads are
+  // clamped to a valid address and the LDS pieces are zeros; their accumulators are exactly zero either way.
   typedef _Float16 h4 __attribute__((ext_vector_type(4)));
   h4 fpre[T::TM][T::TN][4];
+  {
+    const int nk = (p.K + T::BK - 1) / T::BK;
 #pragma unroll
-  for (int a = 0; a < T::TM; ++a) {
-    const int frow_i = m0 + wm * 128 + a * 32 + l32;
-    const uint16_t* frow = p.fgrad + (int64_t)(frow_i < p.o ? frow_i : p.o - 1) * p.i;
+    for (int a = 0; a < 4; ++a) {
+      const unsigned char* rowp = lds + ((nk + a) % T::NS) * T::STAGE + wm * (32 * 512) + l32 * 512 + lh * 8;
 #pragma unroll
-    for (int b = 0; b < T::TN; ++b)
+      for (int b = 0; b < T::TN; ++b)
 #pragma unroll
-      for (int eg = 0; eg < 4; ++eg) {
-        const int j = n0 + wn * 128 + b * 32 + 8 * eg + 4 * lh;
-        fpre[a][b][eg] = *reinterpret_cast<const h4*>(frow + (j < p.i ? j : p.i - 4));
-      }
+        for (int eg = 0; eg < 4; ++eg)
+          fpre[a][b][eg] = *reinterpret_cast<const h4*>(rowp + (((wn * 16 + b * 4 + eg) ^ l32) << 4));
+    }
   }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_lgkm0());
+  __builtin_amdgcn_s_barrier();  // every wave has its factors in registers: the LDS is free from here on
 
   const int G = p.i / p.g;
   auto put = [&](float* dst, float v) { *dst = p.accumulate ? *dst + v : v; };  // each element has one writer
@@ -296,7 +320,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
 
 bool dw_fused_supported(const LayerDims& d) {
   const bool g_ok = d.g == 32 || d.g == 64 || d.g == 128 || d.g == 256;
-  return g_ok && d.r <= 32;
+  return g_ok && d.r <= 32 && d.i < (1 << 22);  // 32-bit offsets of factor rows up to 255 past the last one
 }
 
 void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n) {

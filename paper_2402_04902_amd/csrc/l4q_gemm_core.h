@@ -117,10 +117,29 @@ struct Accum {
 // whatever follows in memory for k >= K: the caller pairs it with an operand that is exactly zero there
 // (K-major, or zero-padded storage).
 // On return every wave has passed a barrier after its last LDS read, so LDS may be reused.
-template <class T, bool A_KM = false, bool B_KM = false>
+//
+// Tail loads (non-paired loop).  The loop keeps issuing loads for the D stages past the end of K so that its wait
+// arithmetic stays uniform; by default they carry an out-of-range offset and move nothing.  A caller whose epilogue
+// needs a block of memory right after the loop can have those D x (A_INSTR + B_INSTR) loads per wave fetch it
+// instead: tail stage q = 0 .. D - 1 lands in ring slot (nk + q) % NS, load c of the A part at byte
+// (wave A_INSTR + c) 1024 + 16 lane of the slot, load c of the B part A_BYTES further on, each lane reading 16 bytes
+// at byte offset voff_a[c] / voff_b[c] + q * stage_bytes of the buffer (out-of-range offsets read as zero).
+struct NoTailLoads {
+  static constexpr bool ENABLED = false;
+};
+template <int NA, int NB>
+struct TailLoads {
+  static constexpr bool ENABLED = true;
+  const void* base;                 // the buffer the tail loads read: base address and size in bytes (< 2 GiB)
+  int bytes;
+  unsigned voff_a[NA], voff_b[NB];  // per lane
+  unsigned stage_bytes;             // added once per tail stage
+};
+
+template <class T, bool A_KM = false, bool B_KM = false, class Tail = NoTailLoads>
 __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
                                          int64_t ldb, int M, int N, int K, int m0, int n0, unsigned char* lds,
-                                         Accum<T>& acc) {
+                                         Accum<T>& acc, const Tail& tail = Tail()) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the declaration
   static_assert((!A_KM || T::BM == 256) && (!B_KM || T::BN == 256), "K-major staging is written for 256-wide tiles");
   typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -181,11 +200,9 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
   if constexpr (A_KM) setup_km(km_off_a, T::TM, wm * T::WTM);
   if constexpr (B_KM) setup_km(km_off_b, T::TN, wn * T::WTN);
 
-  // part `part` of `nparts` of a stage's loads
-  auto issue_loads = [&](int stage, int slot, int nstages, int part, int nparts) {
-    const bool live = stage < nstages;
-    const unsigned ka = live ? (unsigned)stage * stage_bytes_a : PAST_END_OFFSET;
-    const unsigned kb = live ? (unsigned)stage * stage_bytes_b : PAST_END_OFFSET;
+  // part `part` of `nparts` of the loads of stage `stage` < nk into ring slot `slot`
+  auto issue_loads = [&](int stage, int slot, int part, int nparts) {
+    const unsigned ka = (unsigned)stage * stage_bytes_a, kb = (unsigned)stage * stage_bytes_b;
     unsigned char* base = lds + slot * T::STAGE;
 #pragma unroll
     for (int c = 0; c < T::A_INSTR; ++c)
@@ -197,6 +214,32 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
       if (c * nparts / T::B_INSTR == part)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rsrcB, (lds_ptr_t)(base + T::A_BYTES + (wave * T::B_INSTR + c) * 1024), 16, voffB[c] + kb, 0, 0, 0);
+  };
+  // the same number of loads for tail stage q (stage nk + q): the caller's block, or nothing (out-of-range offsets)
+  auto issue_tail = [&](int q, int slot, int part, int nparts) {
+    unsigned char* base = lds + slot * T::STAGE;
+    __amdgpu_buffer_rsrc_t rt = rsrcA;
+    unsigned kq = PAST_END_OFFSET;
+    if constexpr (Tail::ENABLED) {
+      rt = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(tail.base), 0, tail.bytes, 0x00020000);
+      kq = (unsigned)q * tail.stage_bytes;
+    }
+#pragma unroll
+    for (int c = 0; c < T::A_INSTR; ++c)
+      if (c * nparts / T::A_INSTR == part) {
+        unsigned v = voffA[c];
+        if constexpr (Tail::ENABLED) v = tail.voff_a[c];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_ptr_t)(base + (wave * T::A_INSTR + c) * 1024), 16, v + kq,
+                                                 0, 0, 0);
+      }
+#pragma unroll
+    for (int c = 0; c < T::B_INSTR; ++c)
+      if (c * nparts / T::B_INSTR == part) {
+        unsigned v = voffB[c];
+        if constexpr (Tail::ENABLED) v = tail.voff_b[c];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rt, (lds_ptr_t)(base + T::A_BYTES + (wave * T::B_INSTR + c) * 1024),
+                                                 16, v + kq, 0, 0, 0);
+      }
   };
 
   bf16x8_t fa[2][T::TM], fb[2][T::TN];
@@ -241,6 +284,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
   constexpr int NMF = T::TM * T::TN;
   constexpr int EXTRA = NDA + NDB + LPK > NMF ? NDA + NDB + LPK - NMF : 0;  // reads that share a matrix op
   static_assert(2 * EXTRA <= NDA + NDB, "too many LDS reads per matrix op");
+  static_assert(!Tail::ENABLED || !T::PAIR, "tail loads are wired into the non-paired loop");
   if constexpr (T::PAIR) {
     // Paired loading for K-contiguous operands.  A stage takes 64 bytes of every operand row, half a 128-byte
     // cache line; when the second half is requested a stage later the line has already left the 32 KiB vector
@@ -355,7 +399,10 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     }
   } else {
 #pragma unroll
-    for (int s = 0; s < T::D; ++s) issue_loads(s, s, nk, 0, 1);
+    for (int s = 0; s < T::D; ++s) {
+      if (s < nk) issue_loads(s, s, 0, 1);
+      else issue_tail(s - nk, s, 0, 1);
+    }
     __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __builtin_amdgcn_s_barrier();
     read_frags_a(0, 0, 0);
@@ -371,7 +418,8 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     constexpr int REST = NMF - (NDA + NDB - EXTRA + LPK);
     static_assert(REST >= 0, "more LDS reads and loads than matrix ops to hide them behind");
     int slot = 0;
-    for (int s = 0; s < nk; ++s) {
+    // one stage; `load_part(kk)` issues part kk of the loads of stage s + D into the slot stage s - 1 has left
+    auto stage = [&](auto&& load_part) {
       int pslot = slot + T::D;
       if (pslot >= T::NS) pslot -= T::NS;
       int nslot = slot + 1;
@@ -391,7 +439,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         // after the last stage the reads below fetch stale LDS; the values are never used
         read_frags_a(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
         read_frags_b(last ? nslot : slot, last ? 0 : kk + 1, (kk + 1) & 1);
-        issue_loads(s + T::D, pslot, nk, kk, T::KK);
+        load_part(pslot, kk);
         mfma_block(kk & 1);
 #pragma unroll
         for (int q = 0; q < EXTRA; ++q) {  // where reads outnumber matrix ops, two reads per matrix op
@@ -411,7 +459,13 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         if constexpr (REST > 0) __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
       }
       slot = nslot;
-    }
+    };
+    // The stages whose look-ahead stage still lies inside K, then the last D whose loads are the tail loads: two
+    // copies of the same straight-line body, no selection inside it.
+    const int n_inside = nk > T::D ? nk - T::D : 0;
+    int s = 0;
+    for (; s < n_inside; ++s) stage([&](int pslot, int kk) { issue_loads(s + T::D, pslot, kk, T::KK); });
+    for (; s < nk; ++s) stage([&](int pslot, int kk) { issue_tail(s + T::D - nk, pslot, kk, T::KK); });
   }
   __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
   __builtin_amdgcn_s_waitcnt(waitcnt_lgkm0());
