@@ -38,6 +38,28 @@ def test_packed_export_bit_exact(dtype, bits):
     assert got.shape == want.shape and np.array_equal(got, want)
 
 
+def _random_forward_cases(count=20, seed=4902):
+    """Seeded draw of decode-size problems: every code width, group sizes 8 .. 256, 1 .. 100 tokens, ragged row
+    counts, row lengths that do and do not make whole cache lines of packed codes."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        bits = int(rng.choice([2, 3, 4, 8]))
+        g = int(rng.choice([8, 16, 32, 64, 128, 256]))
+        i = 64 * int(rng.integers(1, 40))
+        while i % g != 0:
+            i += 64
+        o = 8 * int(rng.integers(1, 160))
+        T = int(rng.choice([1, 1, 2, 3, 5, 8, 12, 13, 16, 17, 31, 32, 33, 48, 64, 65, 100]))
+        cases.append((k, T, i, o, bits, g))
+    return cases
+
+
+@pytest.mark.parametrize("k,T,i,o,bits,g", _random_forward_cases())
+def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
+    test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
+
+
 @pytest.mark.parametrize("T,i,o,bits,g", [
     (1, 256, 72, 4, 64), (7, 512, 264, 4, 128), (64, 1024, 520, 3, 64), (33, 256, 40, 2, 8), (100, 320 * 2, 96, 8, 32),
     (16, 4096, 11008, 4, 128),      # LLaMA-7B up projection at a decode batch
