@@ -166,7 +166,8 @@ int l4q_export_packed(const l4q_desc* desc, const void* W0, const void* A, const
 /* Forward pass of the fully quantized layer from the packed codes alone (no W0, A, B):
  *   Y[T,o] = X[T,i] . (w~ scale + zero)^T        (Eq. l4q_forward with Eq. l4q_Wdequant)
  * BF16 only (X, Y bfloat16); bits in {2,3,4,8}; in_features % 64 == 0.  Meant for decode-sized T:
- * the weight stream is re-read for every 64 tokens.  Needs no workspace. */
+ * the packed weights are streamed once per pass of at most 64 tokens (32 or 48 for some shapes), so the
+ * cost grows with T beyond that.  Needs no workspace. */
 int l4q_quantized_forward(const l4q_desc* desc, const void* X, const uint32_t* packed,
                           const float* scale, const float* zero, void* Y, void* hip_stream);
 
