@@ -35,7 +35,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
   // parks its 128 x 128 block in its own LDS region (rows padded to 272 bytes) and writes it out as 16 bytes
   // per lane, 16 lanes per 256-byte row segment.  Needs 16-byte aligned rows: ldc % 8 == 0 and N % 8 == 0.
   constexpr int EP_ROW = T::WTN * 2 + 16;
-  constexpr bool EP_FITS = OUT_BF16 && T::WTN == 128 && 4 * T::WTM * EP_ROW <= T::LDS_BYTES;
+  constexpr int EP_LPR = T::WTN / 8;  // lanes that cover a row of the wave's block with 16 bytes each
+  constexpr bool EP_FITS = OUT_BF16 && (T::WTN == 128 || T::WTN == 64) && T::NW * T::WTM * EP_ROW <= T::LDS_BYTES;
   if (EP_FITS && (ldc & 7) == 0 && (N & 7) == 0) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -52,11 +53,12 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
           *reinterpret_cast<uint2*>(region + (a * 32 + (lane & 31)) * EP_ROW + (b * 32 + 8 * eg + 4 * (lane >> 5)) * 2) = v;
         }
     bf16_t* C = reinterpret_cast<bf16_t*>(Cout);
-    const int mw = m0 + (wave >> 1) * T::WTM, nw = n0 + (wave & 1) * T::WTN + (lane & 15) * 8;
+    const int mw = m0 + (wave / T::WAVES_N) * T::WTM;
+    const int nw = n0 + (wave % T::WAVES_N) * T::WTN + (lane % EP_LPR) * 8;
 #pragma unroll 8
-    for (int it = 0; it < T::WTM / 4; ++it) {
-      const int row = it * 4 + (lane >> 4);
-      const uint4 v = *reinterpret_cast<const uint4*>(region + row * EP_ROW + (lane & 15) * 16);
+    for (int it = 0; it < T::WTM * EP_LPR / 64; ++it) {
+      const int row = it * (64 / EP_LPR) + lane / EP_LPR;
+      const uint4 v = *reinterpret_cast<const uint4*>(region + row * EP_ROW + (lane % EP_LPR) * 16);
       if (mw + row < M && nw < N) *reinterpret_cast<uint4*>(C + (int64_t)(mw + row) * ldc + nw) = v;
     }
     return;
@@ -152,7 +154,9 @@ int device_compute_units() {
 
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
                          int64_t K, bf16_t* C, int64_t ldc, hipStream_t stream) {
-  typedef gemm::Tile<256, 256, 32, 5, true> F;  // K-contiguous operands: stages loaded in cache-line pairs
+  // K-contiguous operands: stages loaded in cache-line pairs; 8 waves (2 x 4, two per SIMD, 128 x 64 each): a second
+  // wave on the SIMD keeps the matrix pipe busy while the first waits for a barrier or for operands (1.5 % over 2 x 2)
+  typedef gemm::Tile<256, 256, 32, 5, true, 4> F;
   const int tiles_m = (int)((M + F::BM - 1) / F::BM), tiles_n = (int)((N + F::BN - 1) / F::BN);
   hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false>), dim3((unsigned)(tiles_m * tiles_n)),
                      dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (void*)C, ldc, tiles_m, tiles_n);

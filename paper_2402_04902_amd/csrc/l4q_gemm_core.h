@@ -65,19 +65,21 @@ __device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n,
   tn = rem / gsz;
 }
 
-template <int BM_, int BN_, int BK_, int NS_, bool PAIR_ = false>
+template <int BM_, int BN_, int BK_, int NS_, bool PAIR_ = false, int WAVES_N_ = 2>
 struct Tile {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, NS = NS_;
   static constexpr bool PAIR = PAIR_;                 // stages are loaded two at a time (see mainloop)
-  static constexpr int NT = 256;                      // 4 wavefronts, 2 x 2
-  static constexpr int WTM = BM / 2, WTN = BN / 2;    // wave tile
+  static constexpr int WAVES_M = 2, WAVES_N = WAVES_N_;  // wavefronts: 2 x 2, or 2 x 4 (two per SIMD)
+  static constexpr int NW = WAVES_M * WAVES_N;
+  static constexpr int NT = 64 * NW;
+  static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
   static constexpr int TM = WTM / 32, TN = WTN / 32;  // 32 x 32 accumulator tiles per wave
   static constexpr int CPR = BK / 8;                  // 16-byte chunks per LDS row
   static constexpr int ROWB = BK * 2;                 // bytes per LDS row
   static constexpr int RW = 256 / ROWB;               // rows per 256 bytes
   static constexpr int RPI = 64 / CPR;                // rows filled by one wave-wide load
-  static constexpr int A_INSTR = BM / RPI / 4;        // loads per wave per stage, operand A
-  static constexpr int B_INSTR = BN / RPI / 4;
+  static constexpr int A_INSTR = BM / RPI / NW;       // loads per wave per stage, operand A
+  static constexpr int B_INSTR = BN / RPI / NW;
   static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
   static constexpr int STAGE = A_BYTES + B_BYTES;
   static constexpr int KK = BK / 16;                  // MFMA k-steps per stage
@@ -85,7 +87,7 @@ struct Tile {
   static constexpr int LDS_BYTES = NS * STAGE;
   static_assert(BK == 32 || BK == 64, "BK");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
-  static_assert(BM % (RPI * 4) == 0 && BN % (RPI * 4) == 0, "load split");
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "load split");
   static_assert(KK % 2 == 0, "fragment double buffering assumes an even number of k-steps");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
   static_assert(NS >= 3, "the last part of a stage's loads is issued after the wait for the next stage");
@@ -147,7 +149,8 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS bases in SGPRs
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
+  static_assert((!A_KM && !B_KM) || T::NW == 4, "K-major staging is written for 2 x 2 waves");
 
   const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<bf16_t*>(A), 0, (int)((int64_t)(A_KM ? K : M) * lda * 2), 0x00020000);
@@ -318,6 +321,27 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
       }
     };
     constexpr int PAIR_A = 2 * T::A_INSTR, PAIR_B = 2 * T::B_INSTR;  // loads of a pair's two parts
+    // the matrix ops of a k-step that are not paired with an LDS read share the loads issued in that k-step
+    constexpr int AVAIL = NMF - NDA - NDB;
+    static_assert(AVAIL > 0 && (PAIR_A <= AVAIL || PAIR_A == 2 * AVAIL) && (PAIR_B <= AVAIL || PAIR_B == 2 * AVAIL),
+                  "one or two loads per remaining matrix op");
+    auto spread_loads = [](auto n) {
+      constexpr int NL = decltype(n)::value;
+      if constexpr (NL <= AVAIL) {
+#pragma unroll
+        for (int q = 0; q < NL; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        if constexpr (AVAIL > NL) __builtin_amdgcn_sched_group_barrier(0x008, AVAIL - NL, 0);
+      } else {
+#pragma unroll
+        for (int q = 0; q < AVAIL; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+        }
+      }
+    };
     issue_pair(0, 0, 1, 0);
     issue_pair(0, 0, 1, 1);
     issue_pair(2, 2, 3, 0);
@@ -361,11 +385,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-#pragma unroll
-      for (int q = 0; q < PAIR_A; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
+      spread_loads(std::integral_constant<int, PAIR_A>{});
       read_frags_a(n1, 1, 1);
       read_frags_b(n1, 1, 1);
       issue_pair(s + 4, p0, slot, 1);
@@ -375,11 +395,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
-#pragma unroll
-      for (int q = 0; q < PAIR_B; ++q) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
+      spread_loads(std::integral_constant<int, PAIR_B>{});
       // pair (s + 2, s + 3) was issued an iteration ago; only the pair issued above may still be in flight
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_waitcnt(waitcnt_vm(PAIR_A + PAIR_B));
@@ -479,8 +495,8 @@ template <class T>
 __device__ __forceinline__ void acc_coords(int a, int b, int eg, int& m, int& n) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  m = (wave >> 1) * T::WTM + a * 32 + (lane & 31);
-  n = (wave & 1) * T::WTN + b * 32 + 8 * eg + 4 * (lane >> 5);
+  m = (wave / T::WAVES_N) * T::WTM + a * 32 + (lane & 31);
+  n = (wave % T::WAVES_N) * T::WTN + b * 32 + 8 * eg + 4 * (lane >> 5);
 }
 
 }  // namespace gemm
