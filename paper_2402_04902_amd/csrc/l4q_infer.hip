@@ -294,6 +294,33 @@ __global__ __launch_bounds__(QG_WAVES * 64) void qgemm_kernel(const bf16_t* __re
 // Ring of 4 stages per wave: three stages are in flight while one is consumed.  X fragments and scale /
 // zero are fetched one stage ahead into registers; every load is issued in a fixed order so that one
 // partial s_waitcnt covers the stage.
+// Operand fragment f (8 consecutive codes) of a 16-byte chunk of packed codes, as bf16 values without a convert.
+// 4 bits: byte r holds codes 2r (low nibble) and 2r + 1; times 0x1001 puts a copy of the byte 12 bits up, so one mask
+// leaves code 2r in bits 0..3 and code 2r + 1 in bits 16..19, and OR-ing 0x4300 into both halves makes the bf16 pair
+// 128 + u (the caller's K0 takes the 128 and the code offset out again).  8 bits: code - 128, converted.
+typedef uint32_t code_chunk_t __attribute__((ext_vector_type(4)));
+template <int BITS>
+__device__ __forceinline__ bf16x8_t code_fragment(const code_chunk_t& w, int f) {
+  code_chunk_t d;
+  if (BITS == 4) {
+    const uint32_t v = w[f];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
+      uint32_t pair;  // (spread & mask) | bias in one instruction: one constant in a scalar, one in a vector register
+      asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
+      d[r] = pair;
+    }
+  } else {
+    const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];  // 4 + 4 codes
+    d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
+    d[1] = pack_bf16x2((float)((v0 >> 16) & 0xFFu) - 128.f, (float)(v0 >> 24) - 128.f);
+    d[2] = pack_bf16x2((float)(v1 & 0xFFu) - 128.f, (float)((v1 >> 8) & 0xFFu) - 128.f);
+    d[3] = pack_bf16x2((float)((v1 >> 16) & 0xFFu) - 128.f, (float)(v1 >> 24) - 128.f);
+  }
+  return __builtin_bit_cast(bf16x8_t, d);
+}
+
 constexpr int QS_NSW = 4;             // ring stages per wave
 
 template <int ROWS> struct QsMfma;
@@ -412,26 +439,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_stream_kernel(const bf16_t* __re
       for (int e = 0; e < NACC; ++e) { tw[e] = 0.f; tx[e] = 0.f; }
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
-        u32x4 d;
-        if (BITS == 4) {
-          // 8 codes.  Byte r holds codes 2r (low nibble) and 2r + 1; times 0x1001 puts a copy of the byte 12 bits
-          // up, so one mask leaves code 2r in bits 0..3 and code 2r + 1 in bits 16..19: a bf16 pair 128 + u.
-          const uint32_t v = w[f];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
-            uint32_t pair;  // (spread & mask) | bias in one instruction: one constant in a scalar, one in a vector register
-            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
-            d[r] = pair;
-          }
-        } else {
-          const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];  // 4 + 4 codes
-          d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
-          d[1] = pack_bf16x2((float)((v0 >> 16) & 0xFFu) - 128.f, (float)(v0 >> 24) - 128.f);
-          d[2] = pack_bf16x2((float)(v1 & 0xFFu) - 128.f, (float)((v1 >> 8) & 0xFFu) - 128.f);
-          d[3] = pack_bf16x2((float)((v1 >> 16) & 0xFFu) - 128.f, (float)(v1 >> 24) - 128.f);
-        }
-        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+        const bf16x8_t wf = code_fragment<BITS>(w, f);
         const bf16x8_t xf = __builtin_bit_cast(bf16x8_t, R.x[h][f]);  // tokens past T: clamped row, never stored
         tw = M::mma(xf, wf, tw);
         tx = M::mma(xf, ones, tx);
@@ -600,24 +608,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
       for (int e = 0; e < NACC; ++e) { tw[e] = 0.f; tx[e] = 0.f; }
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
-        u32x4 d;
-        if (BITS == 4) {
-          const uint32_t v = w[f];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
-            uint32_t pair;
-            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
-            d[r] = pair;
-          }
-        } else {
-          const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];
-          d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
-          d[1] = pack_bf16x2((float)((v0 >> 16) & 0xFFu) - 128.f, (float)(v0 >> 24) - 128.f);
-          d[2] = pack_bf16x2((float)(v1 & 0xFFu) - 128.f, (float)((v1 >> 8) & 0xFFu) - 128.f);
-          d[3] = pack_bf16x2((float)((v1 >> 16) & 0xFFu) - 128.f, (float)(v1 >> 24) - 128.f);
-        }
-        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+        const bf16x8_t wf = code_fragment<BITS>(w, f);
         const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xrow + (size_t)(k0 + (KG * h + kg) * CH + 8 * f) * 2);
         tw = M::mma(xf, wf, tw);
         tx = M::mma(xf, ones, tx);
@@ -801,24 +792,7 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
       for (int e = 0; e < 4; ++e) tx[e] = 0.f;
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
-        u32x4 d;
-        if (BITS == 4) {
-          const uint32_t v = w[f];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
-            uint32_t pair;
-            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
-            d[r] = pair;
-          }
-        } else {
-          const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];
-          d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
-          d[1] = pack_bf16x2((float)((v0 >> 16) & 0xFFu) - 128.f, (float)(v0 >> 24) - 128.f);
-          d[2] = pack_bf16x2((float)(v1 & 0xFFu) - 128.f, (float)((v1 >> 8) & 0xFFu) - 128.f);
-          d[3] = pack_bf16x2((float)((v1 >> 16) & 0xFFu) - 128.f, (float)(v1 >> 24) - 128.f);
-        }
-        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+        const bf16x8_t wf = code_fragment<BITS>(w, f);
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) tw[tb] = M::mma(xf[f][tb], wf, tw[tb]);
         tx = M::mma(xo[f], ones, tx);
