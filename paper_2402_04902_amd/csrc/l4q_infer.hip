@@ -678,7 +678,6 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   const int ln = lane % 16, kg = lane / 16;
   const int p0 = blockIdx.x * 64 + wave * 16;  // first row of this wave's tile
   const int p = p0 + ln;
-  const int pc = p < o ? p : o - 1;
   const int rb = i / 8 * BITS;
   const int nst = rb / 128;
   const int G = i / g;
