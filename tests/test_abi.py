@@ -102,6 +102,31 @@ def test_descriptor_layout_matches_header():
     assert binding.L4QDesc.alpha.offset == 36 and binding.L4QDesc.flags.offset == 44
 
 
+def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
+    """include/l4q.h compiles as C99 on its own, and a C program reports the struct layout and enum values the
+    ctypes binding assumes."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "layout.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "l4q.h"\n'
+        'int main(void) {\n'
+        '  printf("%zu %zu %zu %zu %d %d %d %d\\n", sizeof(l4q_desc), offsetof(l4q_desc, rank),\n'
+        '         offsetof(l4q_desc, alpha), offsetof(l4q_desc, flags), (int)L4Q_DTYPE_BF16,\n'
+        '         (int)L4Q_FLAG_UNFUSED_BACKWARD, (int)L4Q_FLAG_ACCUMULATE_GRADS, (int)L4Q_ERR_SHAPE);\n'
+        '  return 0;\n}\n')
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(v) for v in out] == [ctypes.sizeof(binding.L4QDesc), binding.L4QDesc.rank.offset,
+                                     binding.L4QDesc.alpha.offset, binding.L4QDesc.flags.offset, DTYPE_BF16,
+                                     binding.FLAG_UNFUSED_BACKWARD, binding.FLAG_ACCUMULATE_GRADS, -2]
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2402_04902_amd")
     for dirpath, _, files in os.walk(pkg):
