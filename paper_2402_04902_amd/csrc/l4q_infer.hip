@@ -634,7 +634,8 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
 #endif
 }
 
-// Batches of 33 .. 64 tokens per pass on wide layers.  One workgroup = 64 weight rows, one 16-row tile per wave, every wave
+// Batches of up to 64 tokens per pass on wide layers (the smallest ones only when their activations do not fit the
+// kernel above).  One workgroup = 64 weight rows, one 16-row tile per wave, every wave
 // walking the whole row (no k-split), so the four waves consume the same k-stage at the same time and can share its
 // activations: a stage of X (TB x 16 tokens x 128 / BITS x 8 k-values) is put into LDS once per workgroup by DMA,
 // swizzled (chunk c of token t at position c ^ (t % 16)) so that the fragment reads of 16 tokens hit 16 different
@@ -643,9 +644,10 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
 // the weight stream from HBM and the activations from the L2 share one prefetch distance.  One barrier per stage
 // makes the shared part visible and frees the slot that is refilled next.
 // The zero-point term needs sum_k X per (token, group), which does not depend on the weight row: wave w forms it for
-// token block w with one extra matrix op per fragment (against ones) and adds it to a table in LDS; after the loop
-// every lane adds sum_g (zero - K0 scale)[row, g] * table[token, g] to its outputs, the first factor staged through
-// the LDS the rings have left.  The scales of the 64 rows sit in LDS too (odd row pitch), so the stage loop issues
+// token block w with one extra matrix op per fragment (against ones), chained over the sub-steps of a group, and
+// stores the running sum into a table in LDS (no read-modify-write: a wave alone on its SIMD pays every LDS round trip
+// in full); after the loop every lane adds sum_g (zero - K0 scale)[row, g] * table[token, g] to its outputs, the first
+// factor fetched before the loop, held in registers and staged through the LDS the rings have left.  The scales of the 64 rows sit in LDS too (odd row pitch), so the stage loop issues
 // DMA loads only and its partial waits are exact.
 constexpr int qt_ring_stages(int token_blocks) { return token_blocks == 1 ? 8 : token_blocks == 2 ? 5 : token_blocks == 3 ? 4 : 3; }
 constexpr int QT_ROWQ = 6;  // 16-byte pieces of a 64-row scale / zero block per thread: groups per row <= 96
@@ -737,15 +739,26 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
       rows[q] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
     }
   };
-  auto store_rows = [&](const float4 (&rows)[QT_ROWQ], auto&& put) {
+  // table position (row * pitch + group) of the first float of each piece, and its group: one division per piece,
+  // done once; the other three floats follow by comparison (a piece crosses at most two row ends, as G >= 2)
+  int piece_at[QT_ROWQ], piece_grp[QT_ROWQ];
+#pragma unroll
+  for (int q = 0; q < QT_ROWQ; ++q) {
+    const int idx = (q * 256 + (int)threadIdx.x) * 4;
+    const int row = idx / G;
+    piece_grp[q] = idx - row * G;
+    piece_at[q] = row * sx_pitch + piece_grp[q];
+  }
+  auto store_rows = [&](const float4 (&rows)[QT_ROWQ], float* table) {
 #pragma unroll
     for (int q = 0; q < QT_ROWQ; ++q) {
       const int idx = (q * 256 + (int)threadIdx.x) * 4;
       const float v[4] = {rows[q].x, rows[q].y, rows[q].z, rows[q].w};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const int row = (idx + c) / G, grp = (idx + c) - row * G;
-        if (idx + c < 64 * G) put(row * sx_pitch + grp, v[c]);
+        const int at_grp = piece_grp[q] + c;
+        const int wraps = (at_grp >= G ? 1 : 0) + (at_grp >= 2 * G ? 1 : 0);
+        if (idx + c < 64 * G) table[piece_at[q] + c + wraps * (sx_pitch - G)] = v[c];
       }
     }
   };
@@ -760,6 +773,10 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   const int swz = (ln >> 1) & 7;
 
   const int own = wave < TB ? wave : TB - 1;
+  acc_t tx;          // running sums of X over the group in progress, token block `own`
+  int tx_grp = -1;   // that group
+#pragma unroll
+  for (int e = 0; e < 4; ++e) tx[e] = 0.f;
   auto consume = [&](int j) {
     const unsigned char* wsrc = wring + (j % QT_NS) * WSTAGE + frag_row;
     const unsigned char* xsrc = xring + (j % QT_NS) * XSTAGE;
@@ -782,13 +799,16 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
       const int grp = (st * KS + h * SUB) / g;
       const float sc = srow[grp];
       __builtin_amdgcn_sched_barrier(0);
-      acc_t tw[TB], tx;
+      acc_t tw[TB];
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) tw[tb][e] = 0.f;
+      if (grp != tx_grp) {  // a group starts (the groups are whole numbers of sub-steps)
+        tx_grp = grp;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) tx[e] = 0.f;
+        for (int e = 0; e < 4; ++e) tx[e] = 0.f;
+      }
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
         const bf16x8_t wf = code_fragment<BITS>(w, f);
@@ -800,24 +820,30 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
       for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[tb][e] = fmaf(sc, tw[tb][e], acc[tb][e]);
-      if (wave < TB && ln == 0 && j < nst) {  // every column of tx holds the same sums: one lane per token writes
+      // Every column of tx holds the same sums: one lane per token stores the running sum of the group (plain stores,
+      // the last one of a group leaves the whole sum; this wave is the only writer of the cell).
+      if (wave < TB && ln == 0 && j < nst) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float* cell = sx + (wave * 16 + M::token(e, kg)) * sx_pitch + grp;
-          *cell += tx[e];  // the only writer of this cell
-        }
+        for (int e = 0; e < 4; ++e) sx[(wave * 16 + M::token(e, kg)) * sx_pitch + grp] = tx[e];
       }
     }
   };
 
-  // The first QT_NS - 1 stages are requested, then the tables are set up: sums zeroed, scales of the 64 rows copied in.
+  // The first QT_NS - 1 stages are requested, then the scale / zero rows of the 64 weight rows are fetched: the scales
+  // go into their table, (zero - K0 scale) stays in registers until the rings are free.
 #pragma unroll
   for (int j = 0; j < QT_NS - 1; ++j) issue_dma(j);
-  for (int idx = threadIdx.x; idx < TB * 16 * sx_pitch; idx += 256) sx[idx] = 0.f;
+  float4 bzrows[QT_ROWQ];
   {
-    float4 rows[QT_ROWQ];
-    load_rows(rsrcS, rows);
-    store_rows(rows, [&](int at, float v) { sl[at] = v; });
+    float4 srows[QT_ROWQ];
+    load_rows(rsrcS, srows);
+    load_rows(rsrcZ, bzrows);
+    store_rows(srows, sl);
+#pragma unroll
+    for (int q = 0; q < QT_ROWQ; ++q) {
+      bzrows[q].x -= K0 * srows[q].x; bzrows[q].y -= K0 * srows[q].y;
+      bzrows[q].z -= K0 * srows[q].z; bzrows[q].w -= K0 * srows[q].w;
+    }
   }
   __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));  // these stages and the table loads have landed
   __builtin_amdgcn_sched_barrier(0);
@@ -848,21 +874,12 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   // (zero - K0 scale) of the workgroup's 64 rows into the ring space, rows padded to an odd pitch
   float* bzl = reinterpret_cast<float*>(tlds);
   const int bz_pitch = sx_pitch;
-  {
-    float4 srows[QT_ROWQ], zrows[QT_ROWQ];
-    load_rows(rsrcS, srows);
-    load_rows(rsrcZ, zrows);
-#pragma unroll
-    for (int q = 0; q < QT_ROWQ; ++q) {
-      zrows[q].x -= K0 * srows[q].x; zrows[q].y -= K0 * srows[q].y;
-      zrows[q].z -= K0 * srows[q].z; zrows[q].w -= K0 * srows[q].w;
-    }
-    store_rows(zrows, [&](int at, float v) { bzl[at] = v; });
-  }
+  store_rows(bzrows, bzl);
   __syncthreads();
 
   // zero-point term and store: register e of token block tb is token 16 tb + 4 kg + e of row p
   const float* bzrow = bzl + (wave * 16 + ln) * bz_pitch;
+#pragma unroll 4
   for (int grp = 0; grp < G; ++grp) {
     const float bz = bzrow[grp];
 #pragma unroll
@@ -946,10 +963,14 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     int tb_max = 0;
     for (int tb = 1; tb <= 4; ++tb)
       if (lds_of(tb) <= QD_LDS_MAX && 64 * pitch * 4 <= rings_of(tb) && 64 * G <= QT_ROWQ * 1024) tb_max = tb;
-    // Worth it only when the 64-row tiles give most compute units a workgroup, and beyond 32 tokens: a wave walks its
-    // whole row alone here, which for fewer tokens loses to the k-split of the streaming kernel (measured at
-    // [11008 x 4096]: 19 vs 22 us at 16 tokens, 26 vs 25 at 32, 38 vs 55 at 64).
-    if ((d.o + 63) / 64 < device_compute_units() / 2 || d.T <= 32) tb_max = 0;
+    // One workgroup per compute unit at a time: worth it when the 64-row tiles keep most units busy over the rounds
+    // they need.  Measured at [11008 x 4096] (172 tiles on 256 units) against the k-split streaming kernel: 17 vs 23 us
+    // at 16 tokens, 23 vs 31 at 32, 33 vs 59 at 64; at [8192 x 8192] (128 tiles) 29 vs 29, 40 vs 30, 59 vs 59.
+    {
+      const int64_t tiles = (d.o + 63) / 64, cus = device_compute_units();
+      const int64_t rounds = (tiles + cus - 1) / cus;
+      if (8 * tiles < 5 * rounds * cus) tb_max = 0;
+    }
     if (tb_max > 0) {
       dim3 tgrid((unsigned)((d.o + 63) / 64));
       for (int t0 = 0; t0 < d.T; t0 += 16 * tb_max) {

@@ -74,9 +74,12 @@ def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
     (2, 4096, 11008, 4, 128), (12, 4096, 11008, 4, 128), (4, 11008, 4096, 4, 128), (5, 11008, 4096, 4, 128),
     (3, 1024, 1000, 4, 128), (2, 768, 40, 4, 256), (9, 2048, 520, 8, 64), (13, 4096, 264, 4, 64),
     (1, 28672, 64, 4, 128), (16, 4096, 72, 4, 128),
-    # more than 32 tokens on a wide layer: 64-row tiles sharing the activation stage (4, 3 and 1 token blocks per
-    # pass, a ragged last row tile, odd stage count, 8-bit)
-    (64, 4096, 11008, 4, 128), (70, 1024, 8200, 4, 128), (40, 768, 8264, 8, 64), (48, 11008, 8192, 4, 128),
+    # wide layers (enough 64-row tiles for most compute units): tiles sharing the activation stage, 4, 3, 2 and 1
+    # token blocks per pass, a ragged last row tile, odd stage count, 8-bit, groups of two sub-steps (4-bit g = 256,
+    # 8-bit g = 128), long rows that leave LDS for two token blocks only, a small batch too long for the LDS-resident
+    # form
+    (64, 4096, 11008, 4, 128), (70, 1024, 10248, 4, 128), (40, 896, 10312, 8, 128), (48, 11008, 10240, 4, 128),
+    (24, 2048, 10304, 4, 256), (13, 4096, 10240, 4, 64),
 ])
 def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g):
     import torch
