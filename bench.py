@@ -204,14 +204,16 @@ def main() -> int:
         binding.l4q_export_packed(layer.desc, layer.W0, layer.A, layer.B, layer.scale, layer.zero, pk,
                                   layer.ws[: sp.out_features * sp.in_features])
         packs.append(pk)
+    qfws = [torch.empty(max(256, binding.l4q_quantized_forward_workspace_bytes(l.desc)), dtype=torch.uint8,
+                       device="cuda:0") for l in layers]
     for tok in (1, 16, 64):
         descs = [binding.make_desc(l.spec.with_(tokens=tok)) for l in layers]
         xs = [l.X[:tok] for l in layers]
         ys = [l.Y[:tok] for l in layers]
 
         def qstep():
-            for d_, x_, p_, l_, y_ in zip(descs, xs, packs, layers, ys):
-                binding.l4q_quantized_forward(d_, x_, p_, l_.scale, l_.zero, y_)
+            for d_, x_, p_, l_, y_, w_ in zip(descs, xs, packs, layers, ys, qfws):
+                binding.l4q_quantized_forward(d_, x_, p_, l_.scale, l_.zero, y_, w_)
         for _ in range(5):
             qstep()
         torch.cuda.synchronize()

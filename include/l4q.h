@@ -167,9 +167,19 @@ int l4q_export_packed(const l4q_desc* desc, const void* W0, const void* A, const
  *   Y[T,o] = X[T,i] . (w~ scale + zero)^T        (Eq. l4q_forward with Eq. l4q_Wdequant)
  * BF16 only (X, Y bfloat16); bits in {2,3,4,8}; in_features % 64 == 0.  Meant for decode-sized T:
  * the packed weights are streamed once per pass of at most 64 tokens (32 or 48 for some shapes), so the
- * cost grows with T beyond that.  Needs no workspace. */
+ * cost grows with T beyond that.
+ * workspace (device memory, 256-byte aligned) is optional: NULL / 0 is always accepted.  Layers with few output
+ * rows and long rows run faster at more than 16 tokens when given l4q_quantized_forward_workspace_bytes() of it
+ * (the row is then cut into k-slices over the compute units, whose partial sums are added in a fixed order);
+ * a workspace smaller than that is ignored.  The result does not depend on the stream's other work, but with and
+ * without the workspace it may differ in the last bit of the fp32 sum before the rounding to bfloat16. */
 int l4q_quantized_forward(const l4q_desc* desc, const void* X, const uint32_t* packed,
-                          const float* scale, const float* zero, void* Y, void* hip_stream);
+                          const float* scale, const float* zero, void* Y,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace l4q_quantized_forward can make use of for this layer (0 for most shapes; does not depend on
+ * `tokens`). */
+int l4q_quantized_forward_workspace_bytes(const l4q_desc* desc, size_t* bytes);
 
 /* Quantization-parameter initialisation from the merged weight (Sec. 3.3, Eq. l4q_quant_init;
  * App. B, Eq. quant_inits).  Writes scale, zero [o,G].

@@ -19,7 +19,7 @@ FLAG_ACCUMULATE_GRADS = 2
 INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
-            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward", "l4q_adamw_step", "l4q_cosine_lr",
+            "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward", "l4q_quantized_forward_workspace_bytes", "l4q_adamw_step", "l4q_cosine_lr",
             "l4q_qatlora_workspace_bytes", "l4q_qatlora_forward", "l4q_qatlora_backward"]
 
 
@@ -82,7 +82,9 @@ def load_library() -> ctypes.CDLL:
     lib.l4q_export_packed.restype = ctypes.c_int
     lib.l4q_export_packed.argtypes = [dp, vp, vp, vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
     lib.l4q_quantized_forward.restype = ctypes.c_int
-    lib.l4q_quantized_forward.argtypes = [dp, vp, vp, fp, fp, vp, vp]
+    lib.l4q_quantized_forward.argtypes = [dp, vp, vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
+    lib.l4q_quantized_forward_workspace_bytes.restype = ctypes.c_int
+    lib.l4q_quantized_forward_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
     lib.l4q_adamw_step.restype = ctypes.c_int
     lib.l4q_adamw_step.argtypes = [dp, ctypes.POINTER(L4QAdamW)] + [fp] * 10 + [vp, vp, vp]
     lib.l4q_cosine_lr.restype = ctypes.c_float
@@ -184,9 +186,18 @@ def l4q_export_packed(desc: L4QDesc, W0, A, B, scale, zero, packed, workspace) -
            "l4q_export_packed")
 
 
-def l4q_quantized_forward(desc: L4QDesc, X, packed, scale, zero, Y) -> None:
+def l4q_quantized_forward(desc: L4QDesc, X, packed, scale, zero, Y, workspace=None) -> None:
     _check(load_library().l4q_quantized_forward(ctypes.byref(desc), _ptr(X), _ptr(packed), _ptr(scale), _ptr(zero),
-                                                _ptr(Y), _stream()), "l4q_quantized_forward")
+                                                _ptr(Y), _ptr(workspace),
+                                                0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                                _stream()), "l4q_quantized_forward")
+
+
+def l4q_quantized_forward_workspace_bytes(desc: L4QDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().l4q_quantized_forward_workspace_bytes(ctypes.byref(desc), ctypes.byref(n)),
+           "l4q_quantized_forward_workspace_bytes")
+    return int(n.value)
 
 
 def l4q_adamw_step(desc: L4QDesc, hp: L4QAdamW, A32, B32, scale, zero, dA, dB, dscale, dzero, m, v,

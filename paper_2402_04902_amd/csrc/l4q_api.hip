@@ -427,7 +427,7 @@ int l4q_export_packed(const l4q_desc* desc, const void* W0, const void* A, const
 }
 
 int l4q_quantized_forward(const l4q_desc* desc, const void* X, const uint32_t* packed, const float* scale,
-                          const float* zero, void* Y, void* hip_stream) {
+                          const float* zero, void* Y, void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int st = check_desc(desc, true);
   if (st != L4Q_OK) return st;
   if (desc->dtype != L4Q_DTYPE_BF16) return L4Q_ERR_DTYPE;
@@ -437,9 +437,20 @@ int l4q_quantized_forward(const l4q_desc* desc, const void* X, const uint32_t* p
   const void* ptrs[] = {X, packed, scale, zero, Y};
   for (const void* p : ptrs)
     if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  if (workspace && !aligned(workspace, kWsAlign)) return L4Q_ERR_ALIGN;
   (void)hipGetLastError();
-  l4q::launch_qgemm(d, (const bf16_t*)X, packed, scale, zero, (bf16_t*)Y, static_cast<hipStream_t>(hip_stream));
+  l4q::launch_qgemm(d, (const bf16_t*)X, packed, scale, zero, (bf16_t*)Y, static_cast<float*>(workspace),
+                    workspace ? workspace_bytes : 0, static_cast<hipStream_t>(hip_stream));
   return launch_status();
+}
+
+int l4q_quantized_forward_workspace_bytes(const l4q_desc* desc, size_t* bytes) {
+  const int st = check_desc(desc, false);
+  if (st != L4Q_OK) return st;
+  if (!bytes) return L4Q_ERR_NULL;
+  const LayerDims d = dims_of(desc);
+  *bytes = desc->dtype == L4Q_DTYPE_BF16 && l4q::qgemm_supported(d) ? l4q::qgemm_workspace_bytes(d) : 0;
+  return L4Q_OK;
 }
 
 int l4q_qatlora_workspace_bytes(const l4q_desc* desc, size_t* forward_bytes, size_t* backward_bytes) {

@@ -650,6 +650,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
 // factor fetched before the loop, held in registers and staged through the LDS the rings have left.  The scales of the 64 rows sit in LDS too (odd row pitch), so the stage loop issues
 // DMA loads only and its partial waits are exact.
 constexpr int qt_ring_stages(int token_blocks) { return token_blocks == 1 ? 8 : token_blocks == 2 ? 5 : token_blocks == 3 ? 4 : 3; }
+constexpr int QT_SLICES_MAX = 8;  // k-slices of a row tile at most
 constexpr int QT_ROWQ = 6;  // 16-byte pieces of a 64-row scale / zero block per thread: groups per row <= 96
 
 template <int BITS, int TB>
@@ -657,7 +658,8 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
                                                          const uint32_t* __restrict__ packed,
                                                          const float* __restrict__ scale,
                                                          const float* __restrict__ zero, bf16_t* __restrict__ Y,
-                                                         int T, int t0, int o, int i, int g, int sx_pitch) {
+                                                         float* __restrict__ part, int T, int t0, int o, int i, int g,
+                                                         int sx_pitch) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char tlds[];
 #if defined(__HIP_DEVICE_COMPILE__)
   static_assert(BITS == 4 || BITS == 8, "bits");
@@ -681,8 +683,15 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   const int p0 = blockIdx.x * 64 + wave * 16;  // first row of this wave's tile
   const int p = p0 + ln;
   const int rb = i / 8 * BITS;
-  const int nst = rb / 128;
   const int G = i / g;
+  // k-slice of this workgroup: stages j0 .. j0 + nst - 1 of the row (the whole row when the grid has one slice)
+  const int nst_row = rb / 128, slices = gridDim.y, slice = blockIdx.y;
+  const int j0 = slice * (nst_row / slices) + (slice < nst_row % slices ? slice : nst_row % slices);
+  const int nst = nst_row / slices + (slice < nst_row % slices ? 1 : 0);
+  const int n_pass = T - t0 < 16 * TB ? T - t0 : 16 * TB;  // tokens of this pass
+  // the groups this slice meets: the tables in LDS hold these only, indexed from grp_first
+  const int grp_first = j0 * KS / g, groups = ((j0 + nst) * KS - 1) / g - grp_first + 1;
+  const int ppr = (groups + 3) / 4;  // 16-byte pieces of a table row
   const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
 
@@ -711,8 +720,8 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   }
   auto issue_dma = [&](int j) {  // stage j into ring slot j % QT_NS; past the end of k: zeros, no traffic
     const bool live = j < nst;
-    const unsigned kw = live ? (unsigned)j * 128u : gemm::PAST_END_OFFSET;
-    const unsigned kx = live ? (unsigned)j * (unsigned)XROW : gemm::PAST_END_OFFSET;
+    const unsigned kw = live ? (unsigned)(j0 + j) * 128u : gemm::PAST_END_OFFSET;
+    const unsigned kx = live ? (unsigned)(j0 + j) * (unsigned)XROW : gemm::PAST_END_OFFSET;
     unsigned char* wdst = wring + (j % QT_NS) * WSTAGE;
     unsigned char* xdst = xring + (j % QT_NS) * XSTAGE + wave * NXW * 1024;
 #pragma unroll
@@ -724,42 +733,37 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   };
   const float* srow = sl + (wave * 16 + ln) * sx_pitch;
 
-  // The scale / zero rows of the workgroup's 64 weight rows are one contiguous block of 64 G floats (rows past the
-  // matrix read as zero through the buffer range): each thread fetches up to QT_ROWQ pieces of 4 floats, all requested
-  // before the first is used, and scatters them into rows of odd pitch.
+  // The scale / zero values of the workgroup's 64 weight rows and the slice's groups: each thread fetches up to QT_ROWQ
+  // pieces of 4 floats (piece q4 of a row = groups grp_first + 4 q4 .. + 3; rows past the matrix read as zero through
+  // the buffer range, values past the slice's groups are fetched but not kept), all requested before the first is used,
+  // and puts them into rows of odd pitch.
   const __amdgpu_buffer_rsrc_t rsrcS = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(scale), 0, (int)((int64_t)o * G * 4), 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<float*>(zero), 0, (int)((int64_t)o * G * 4), 0x00020000);
+  int piece_row[QT_ROWQ], piece_q4[QT_ROWQ];
+#pragma unroll
+  for (int q = 0; q < QT_ROWQ; ++q) {
+    const int piece = q * 256 + (int)threadIdx.x;
+    piece_row[q] = piece / ppr;
+    piece_q4[q] = piece - piece_row[q] * ppr;
+  }
   auto load_rows = [&](const __amdgpu_buffer_rsrc_t& rsrc, float4 (&rows)[QT_ROWQ]) {
 #pragma unroll
     for (int q = 0; q < QT_ROWQ; ++q) {
-      const int idx = (q * 256 + (int)threadIdx.x) * 4;
-      const unsigned off = idx < 64 * G ? (unsigned)(((int64_t)blockIdx.x * 64 * G + idx) * 4) : gemm::OOB_OFFSET;
+      const int64_t at = ((int64_t)blockIdx.x * 64 + piece_row[q]) * G + grp_first + 4 * piece_q4[q];
+      const unsigned off = q * 256 + (int)threadIdx.x < 64 * ppr ? (unsigned)(at * 4) : gemm::OOB_OFFSET;
       rows[q] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
     }
   };
-  // table position (row * pitch + group) of the first float of each piece, and its group: one division per piece,
-  // done once; the other three floats follow by comparison (a piece crosses at most two row ends, as G >= 2)
-  int piece_at[QT_ROWQ], piece_grp[QT_ROWQ];
-#pragma unroll
-  for (int q = 0; q < QT_ROWQ; ++q) {
-    const int idx = (q * 256 + (int)threadIdx.x) * 4;
-    const int row = idx / G;
-    piece_grp[q] = idx - row * G;
-    piece_at[q] = row * sx_pitch + piece_grp[q];
-  }
   auto store_rows = [&](const float4 (&rows)[QT_ROWQ], float* table) {
 #pragma unroll
     for (int q = 0; q < QT_ROWQ; ++q) {
-      const int idx = (q * 256 + (int)threadIdx.x) * 4;
       const float v[4] = {rows[q].x, rows[q].y, rows[q].z, rows[q].w};
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int at_grp = piece_grp[q] + c;
-        const int wraps = (at_grp >= G ? 1 : 0) + (at_grp >= 2 * G ? 1 : 0);
-        if (idx + c < 64 * G) table[piece_at[q] + c + wraps * (sx_pitch - G)] = v[c];
-      }
+      for (int c = 0; c < 4; ++c)
+        if (q * 256 + (int)threadIdx.x < 64 * ppr && 4 * piece_q4[q] + c < groups)
+          table[piece_row[q] * sx_pitch + 4 * piece_q4[q] + c] = v[c];
     }
   };
 
@@ -780,7 +784,7 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   auto consume = [&](int j) {
     const unsigned char* wsrc = wring + (j % QT_NS) * WSTAGE + frag_row;
     const unsigned char* xsrc = xring + (j % QT_NS) * XSTAGE;
-    const int st = j < nst ? j : nst - 1;
+    const int st = j0 + (j < nst ? j : nst - 1);
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
       // every LDS read of the sub-step is issued before the first use: one exposed latency per sub-step
@@ -796,7 +800,7 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
         // read of that fragment instead of a branch on the wave index keeps the sub-step one straight block
         xo[f] = *reinterpret_cast<const bf16x8_t*>(xsrc + (own * 16 + ln) * XROW + cpos * 16);
       }
-      const int grp = (st * KS + h * SUB) / g;
+      const int grp = (st * KS + h * SUB) / g - grp_first;  // position in the tables
       const float sc = srow[grp];
       __builtin_amdgcn_sched_barrier(0);
       acc_t tw[TB];
@@ -880,7 +884,7 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   // zero-point term and store: register e of token block tb is token 16 tb + 4 kg + e of row p
   const float* bzrow = bzl + (wave * 16 + ln) * bz_pitch;
 #pragma unroll 4
-  for (int grp = 0; grp < G; ++grp) {
+  for (int grp = 0; grp < groups; ++grp) {
     const float bz = bzrow[grp];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb)
@@ -892,10 +896,33 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int t = t0 + tb * 16 + M::token(e, kg);
-      if (t < T && p < o) Y[(int64_t)t * o + p] = f32_to_bf16(acc[tb][e]);
+      const int tl = tb * 16 + M::token(e, kg), t = t0 + tl;
+      if (t < T && p < o) {
+        if (part == nullptr) Y[(int64_t)t * o + p] = f32_to_bf16(acc[tb][e]);
+        else part[((int64_t)slice * n_pass + tl) * o + p] = acc[tb][e];  // [slice][token of the pass][row]
+      }
     }
 #endif
+}
+
+// Y[t0 + tl][p] = sum over the k-slices, in slice order, of part[slice][tl][p]; four rows per thread.
+__global__ __launch_bounds__(256) void qgemm_slices_sum_kernel(const float* __restrict__ part, bf16_t* __restrict__ Y,
+                                                               int slices, int n_pass, int t0, int o) {
+  const int64_t quads = (int64_t)n_pass * o / 4;  // o is a multiple of 8
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= quads) return;
+  float4 v = reinterpret_cast<const float4*>(part)[q];
+  float4 w[QT_SLICES_MAX];  // every slice requested before the first is added
+#pragma unroll
+  for (int sl = 1; sl < QT_SLICES_MAX; ++sl)
+    if (sl < slices) w[sl] = reinterpret_cast<const float4*>(part)[(int64_t)sl * quads + q];
+#pragma unroll
+  for (int sl = 1; sl < QT_SLICES_MAX; ++sl)
+    if (sl < slices) { v.x += w[sl].x; v.y += w[sl].y; v.z += w[sl].z; v.w += w[sl].w; }
+  uint2 out;
+  out.x = pack_bf16x2(v.x, v.y);
+  out.y = pack_bf16x2(v.z, v.w);
+  reinterpret_cast<uint2*>(Y + (int64_t)t0 * o)[q] = out;
 }
 
 // rows per workgroup the streaming kernel can use for this layer (0: not at all)
@@ -909,6 +936,47 @@ int qgemm_stream_rows(const LayerDims& d, int tokens_in_pass) {
   return 0;
 }
 
+// How the 64-row tile kernel would run this layer: token blocks per pass (0: not at all), k-slices per row tile,
+// the pitch of its tables in LDS (groups a slice can meet, made odd) and the LDS of a pass of tb token blocks (rings,
+// sum table, scale table; the zero-point table reuses the rings; 0 where that does not fit).
+// One workgroup per compute unit at a time: with one slice it is worth it when the tiles keep most units busy over
+// the rounds they need.  Measured at [11008 x 4096] (172 tiles on 256 units) against the k-split streaming kernel:
+// 17 vs 23 us at 16 tokens, 23 vs 31 at 32, 33 vs 59 at 64; at [8192 x 8192] (128 tiles) 29 vs 29, 40 vs 30, 59 vs 59.
+// With fewer tiles, as many k-slices as fill the units, each at least four stages long.
+struct TilePlan {
+  int tb_max, slices, pitch;
+  int64_t lds[5];
+};
+TilePlan qgemm_tile_plan(const LayerDims& d) {
+  TilePlan plan = {0, 1, 1, {0, 0, 0, 0, 0}};
+  if (qgemm_stream_rows(d, 16) != 16) return plan;
+  const int64_t tiles = (d.o + 63) / 64, cus = device_compute_units();
+  const int64_t rounds = (tiles + cus - 1) / cus;
+  const int64_t nst = d.i / 8 * d.bits / 128, ks = 8 * (128 / d.bits), G = d.i / d.g;
+  if (8 * tiles < 5 * rounds * cus) {
+    int64_t want = cus / tiles;
+    if (want > nst / 4) want = nst / 4;
+    if (want > QT_SLICES_MAX) want = QT_SLICES_MAX;
+    if (want < 2) return plan;
+    plan.slices = (int)want;
+  }
+  const int64_t stages = (nst + plan.slices - 1) / plan.slices;  // of the longest slice
+  int64_t groups = (stages * ks - 1) / d.g + 2;                   // groups it can meet, wherever it starts
+  if (groups > G) groups = G;
+  plan.pitch = (int)(groups | 1);
+  if (groups > 4 * (QT_ROWQ * 256 / 64)) return plan;  // table rows longer than a thread's pieces cover
+  const int xrow = (int)ks * 2;
+  for (int tb = 1; tb <= 4; ++tb) {
+    const int64_t rings = (int64_t)qt_ring_stages(tb) * (4 * 2048 + (int64_t)tb * 16 * xrow);
+    const int64_t lds = rings + (int64_t)(tb * 16 + 64) * plan.pitch * 4;
+    if (lds <= QD_LDS_MAX && 64 * (int64_t)plan.pitch * 4 <= rings) {  // (the ring depth is not monotonic in tb)
+      plan.lds[tb] = lds;
+      plan.tb_max = tb;
+    }
+  }
+  return plan;
+}
+
 }  // namespace
 
 void launch_pack_codes(const int8_t* codes, int64_t o, int64_t i, int bits, uint32_t* packed, hipStream_t stream) {
@@ -919,8 +987,14 @@ void launch_pack_codes(const int8_t* codes, int64_t o, int64_t i, int bits, uint
 
 bool qgemm_supported(const LayerDims& d) { return (d.bits == 2 || d.bits == 3 || d.bits == 4 || d.bits == 8) && d.i % 64 == 0 && d.g >= 8; }
 
+size_t qgemm_workspace_bytes(const LayerDims& d) {
+  const TilePlan plan = qgemm_tile_plan(d);
+  if (plan.tb_max == 0 || plan.slices <= 1) return 0;
+  return (size_t)plan.slices * 16 * plan.tb_max * (size_t)d.o * sizeof(float);  // [slice][token of a pass][row]
+}
+
 void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, const float* scale, const float* zero,
-                  bf16_t* Y, hipStream_t stream) {
+                  bf16_t* Y, float* partial, size_t partial_bytes, hipStream_t stream) {
   dim3 grid((unsigned)((d.o + 31) / 32));
   // more than 32 tokens: the general kernel reads the weights once per 64 tokens, the streaming form once per 32
   // smallest batches: activations and the tile's scale / zero in LDS
@@ -952,38 +1026,29 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     }
   }
   // larger batches: 64-row tiles that share each activation stage through LDS, up to 64 tokens per pass
-  if (qgemm_stream_rows(d, 16) == 16) {
-    const int xrow = 8 * (128 / d.bits) * 2;
-    const int64_t G = d.i / d.g, pitch = G | 1;
-    // LDS of a pass of tb token blocks: rings, sum table, scale table; the zero-point table reuses the rings
-    const auto rings_of = [&](int tb) {
-      return (int64_t)qt_ring_stages(tb) * (4 * 2048 + (int64_t)tb * 16 * xrow);
-    };
-    const auto lds_of = [&](int tb) { return rings_of(tb) + (int64_t)(tb * 16 + 64) * pitch * 4; };
-    int tb_max = 0;
-    for (int tb = 1; tb <= 4; ++tb)
-      if (lds_of(tb) <= QD_LDS_MAX && 64 * pitch * 4 <= rings_of(tb) && 64 * G <= QT_ROWQ * 1024) tb_max = tb;
-    // One workgroup per compute unit at a time: worth it when the 64-row tiles keep most units busy over the rounds
-    // they need.  Measured at [11008 x 4096] (172 tiles on 256 units) against the k-split streaming kernel: 17 vs 23 us
-    // at 16 tokens, 23 vs 31 at 32, 33 vs 59 at 64; at [8192 x 8192] (128 tiles) 29 vs 29, 40 vs 30, 59 vs 59.
-    {
-      const int64_t tiles = (d.o + 63) / 64, cus = device_compute_units();
-      const int64_t rounds = (tiles + cus - 1) / cus;
-      if (8 * tiles < 5 * rounds * cus) tb_max = 0;
+  {
+    const TilePlan plan = qgemm_tile_plan(d);
+    int tb_max = plan.tb_max, slices = 1;
+    if (plan.slices > 1) {  // too few row tiles for one k-slice each: split, if the caller gave room for the partial sums
+      if (d.T > 16 && partial != nullptr && partial_bytes >= qgemm_workspace_bytes(d)) slices = plan.slices;
+      else tb_max = 0;
     }
     if (tb_max > 0) {
-      dim3 tgrid((unsigned)((d.o + 63) / 64));
+      const int pitch = plan.pitch;
+      dim3 tgrid((unsigned)((d.o + 63) / 64), (unsigned)slices);
+      float* part = slices > 1 ? partial : nullptr;
       for (int t0 = 0; t0 < d.T; t0 += 16 * tb_max) {
         const int n = (int)d.T - t0 < 16 * tb_max ? (int)d.T - t0 : 16 * tb_max;
-        const int tb = (n + 15) / 16;
-        const size_t lds_bytes = (size_t)lds_of(tb);
+        int tb = (n + 15) / 16;
+        while (plan.lds[tb] == 0) ++tb;  // a form that does not fit: the next larger one (tb_max fits) masks the tokens
+        const size_t lds_bytes = (size_t)plan.lds[tb];
 #define L4Q_QT(B, N)                                                                                                 \
   do {                                                                                                               \
     if (lds_bytes > 64 * 1024)                                                                                       \
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_tile_kernel<B, N>),                             \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                             \
     hipLaunchKernelGGL((qgemm_tile_kernel<B, N>), tgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y,    \
-                       (int)d.T, t0, (int)d.o, (int)d.i, d.g, (int)pitch);                                           \
+                       part, (int)d.T, t0, (int)d.o, (int)d.i, d.g, pitch);                                          \
   } while (0)
         if (d.bits == 4) {
           if (tb == 1) L4Q_QT(4, 1); else if (tb == 2) L4Q_QT(4, 2); else if (tb == 3) L4Q_QT(4, 3); else L4Q_QT(4, 4);
@@ -991,6 +1056,11 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
           if (tb == 1) L4Q_QT(8, 1); else if (tb == 2) L4Q_QT(8, 2); else if (tb == 3) L4Q_QT(8, 3); else L4Q_QT(8, 4);
         }
 #undef L4Q_QT
+        if (slices > 1) {  // the next pass reuses the partial sums' memory: stream order keeps the two apart
+          const int64_t quads = (int64_t)n * d.o / 4;
+          hipLaunchKernelGGL(qgemm_slices_sum_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
+                             partial, Y, slices, n, t0, (int)d.o);
+        }
       }
       return;
     }

@@ -105,8 +105,10 @@ void launch_adamw(const AdamwArgs& a, hipStream_t stream);
 // ---- fully quantized layer: bit-packing of int8 codes [o,i] (i % 32 == 0) and Y = X . dequant(packed)^T ----
 void launch_pack_codes(const int8_t* codes, int64_t o, int64_t i, int bits, uint32_t* packed, hipStream_t stream);
 bool qgemm_supported(const LayerDims& d);
+// partial: optional room for fp32 partial sums (qgemm_workspace_bytes(d); ignored when null or smaller)
+size_t qgemm_workspace_bytes(const LayerDims& d);
 void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, const float* scale, const float* zero,
-                  bf16_t* Y, hipStream_t stream);
+                  bf16_t* Y, float* partial, size_t partial_bytes, hipStream_t stream);
 
 // outa = scale * sum of nba partials of na elements, outb likewise, in one launch (na, nb multiples of 4)
 void launch_reduce_two_partials(const float* pa, int nba, int64_t na, float* outa, const float* pb, int nbb,

@@ -102,6 +102,27 @@ def test_descriptor_layout_matches_header():
     assert binding.L4QDesc.alpha.offset == 36 and binding.L4QDesc.flags.offset == 44
 
 
+def test_quantized_forward_workspace_query_and_argument_checks(lib):
+    """The optional workspace of the quantized forward: its size is a host computation (k-slices x tokens of a pass x
+    rows of fp32 for layers with few 64-row tiles and long rows, nothing otherwise); arguments are checked before
+    anything is launched."""
+    n = ctypes.c_size_t(7)
+    narrow = binding.make_desc(LayerSpec("down", 64, 11008, 4096, 16, 32.0, 4, 128, DTYPE_BF16))
+    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow), ctypes.byref(n)) == 0
+    assert n.value > 0 and n.value % (4096 * 4) == 0 and n.value <= 8 * 64 * 4096 * 4
+    wide = binding.make_desc(LayerSpec("up", 64, 4096, 11008 * 2, 16, 32.0, 4, 128, DTYPE_BF16))
+    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(wide), ctypes.byref(n)) == 0 and n.value == 0
+    f32 = binding.make_desc(LayerSpec("f", 64, 11008, 4096, 16, 32.0, 4, 128, DTYPE_F32))
+    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(f32), ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow), None) == -1
+    assert lib.l4q_quantized_forward_workspace_bytes(None, ctypes.byref(n)) == -1
+    r = ctypes.byref(narrow)
+    assert lib.l4q_quantized_forward(r, 16, 16, 16, 16, None, None, 0, None) == -1
+    assert lib.l4q_quantized_forward(r, 16, 16, 16, 16, 24, None, 0, None) == -5
+    assert lib.l4q_quantized_forward(r, 16, 16, 16, 16, 16, 128, 1 << 30, None) == -5   # workspace not 256-aligned
+    assert lib.l4q_quantized_forward(ctypes.byref(f32), 16, 16, 16, 16, 16, None, 0, None) == -4
+
+
 def test_header_is_plain_c_and_agrees_with_the_binding(tmp_path):
     """include/l4q.h compiles as C99 on its own, and a C program reports the struct layout and enum values the
     ctypes binding assumes."""

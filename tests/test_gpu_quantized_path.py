@@ -63,7 +63,7 @@ def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
 @pytest.mark.parametrize("T,i,o,bits,g", [
     (1, 256, 72, 4, 64), (7, 512, 264, 4, 128), (64, 1024, 520, 3, 64), (33, 256, 40, 2, 8), (100, 320 * 2, 96, 8, 32),
     (16, 4096, 11008, 4, 128),      # LLaMA-7B up projection at a decode batch
-    (64, 11008, 4096, 4, 128),      # down projection
+    (64, 4096, 1024, 3, 128),       # 3-bit, 64 tokens
     (1, 4096, 11008, 4, 128), (1, 11008, 4096, 4, 128),   # single-token decode, both projections
     (17, 11008, 1000, 4, 64),       # odd stage count (43), 17 tokens -> 32-row tiles, ragged rows
     (5, 640, 88, 8, 64), (40, 1280, 200, 8, 128),         # 8-bit streaming form, 16- and 32-row tiles
@@ -80,6 +80,10 @@ def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
     # form
     (64, 4096, 11008, 4, 128), (70, 1024, 10248, 4, 128), (40, 896, 10312, 8, 128), (48, 11008, 10240, 4, 128),
     (24, 2048, 10304, 4, 256), (13, 4096, 10240, 4, 64),
+    # few row tiles and long rows with a workspace: k-slices over the compute units (4, 2 and 3 slices; a slice
+    # boundary inside a group (g = 1024); 8-bit; two passes; stage counts that do not divide by the slices)
+    (64, 11008, 4096, 4, 128), (33, 8192, 8192, 4, 128), (48, 5120, 5000, 4, 1024), (80, 2304, 4104, 8, 128),
+    (17, 4096, 4096, 4, 128),
 ])
 def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g):
     import torch
@@ -93,12 +97,22 @@ def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
     packed = packed_on_gpu(spec, layer)
     Yq = torch.empty_like(layer.Y)
     binding.l4q_quantized_forward(layer.desc, layer.X, packed, layer.scale, layer.zero, Yq)
+    # the optional workspace (k-slices over the compute units for layers with few row tiles); a second result
+    Yw = None
+    ws_bytes = binding.l4q_quantized_forward_workspace_bytes(layer.desc)
+    if ws_bytes > 0:
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda:0")
+        Yw = torch.full_like(layer.Y, float("nan"))
+        binding.l4q_quantized_forward(layer.desc, layer.X, packed, layer.scale, layer.zero, Yw, ws)
     layer.forward()
     torch.cuda.synchronize()
     dec, _, _ = O.decide_f32(arrs["W0"], arrs["A"], arrs["B"], s, b, bits, g, spec.alpha)
     ref = O.quantized_forward(arrs["X"], O.pack_codes(dec.codes, bits), s, b, bits, g)
-    got = Yq.double().cpu().numpy()
-    assert np.isfinite(got).all()
-    assert rel_fro(got, ref) <= 2e-2
-    # single forward path: the quantized-only output equals the training-time forward up to summation order
-    assert rel_fro(got, layer.Y.double().cpu().numpy()) <= 5e-3
+    for Yg in (Yq, Yw):
+        if Yg is None:
+            continue
+        got = Yg.double().cpu().numpy()
+        assert np.isfinite(got).all()
+        assert rel_fro(got, ref) <= 2e-2
+        # single forward path: the quantized-only output equals the training-time forward up to summation order
+        assert rel_fro(got, layer.Y.double().cpu().numpy()) <= 5e-3
