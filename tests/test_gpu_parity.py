@@ -167,6 +167,13 @@ def test_config5_mistral_kv_and_gate():
     run_case(layers[6].with_(tokens=2048, name="mistral7b_down_T2048"), seed=3, shrink=1.0)
 
 
+def test_larger_model_shapes():
+    """Projections of larger models than the benchmark's (13B-class up projection, 70B-class down projection): operands of
+    0.14 and 0.47 GB, the largest the 32-bit byte offsets of the matrix-core kernels are asked to address here."""
+    run_case(LayerSpec("up_5120x13824_T256", 256, 5120, 13824, 16, 32.0, 4, 128, DTYPE_BF16), seed=13, shrink=0.8)
+    run_case(LayerSpec("down_28672x8192_T64", 64, 28672, 8192, 16, 32.0, 4, 128, DTYPE_BF16), seed=70, shrink=0.8)
+
+
 # ------------------------------------------------------------------ initialisation kernel
 
 @pytest.mark.parametrize("dtype", [DTYPE_F32, DTYPE_BF16])

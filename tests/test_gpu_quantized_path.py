@@ -84,6 +84,9 @@ def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
     # boundary inside a group (g = 1024); 8-bit; two passes; stage counts that do not divide by the slices)
     (64, 11008, 4096, 4, 128), (33, 8192, 8192, 4, 128), (48, 5120, 5000, 4, 1024), (80, 2304, 4104, 8, 128),
     (17, 4096, 4096, 4, 128),
+    # 70B-class projections: the widest layer at a small batch, the longest rows (too many groups for the tile kernel's
+    # tables: the streaming forms take it)
+    (4, 8192, 28672, 4, 128), (40, 28672, 8192, 4, 128),
 ])
 def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g):
     import torch
