@@ -119,3 +119,45 @@ def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
         assert rel_fro(got, ref) <= 2e-2
         # single forward path: the quantized-only output equals the training-time forward up to summation order
         assert rel_fro(got, layer.Y.double().cpu().numpy()) <= 5e-3
+
+
+@pytest.mark.parametrize("T,i,o,bits,g", [
+    (1, 4096, 11008, 4, 128),     # activations resident in LDS
+    (16, 4096, 10240, 4, 128),    # 64-row tiles
+    (48, 5120, 5000, 4, 1024),    # k-slices into the workspace + the sum over the slices
+    (20, 512, 264, 3, 64),        # general kernel
+])
+def test_quantized_forward_replayed_from_a_graph(T, i, o, bits, g):
+    """A serving loop replays the layer from a captured graph: the call allocates nothing, launches only kernels on the
+    caller's stream and keeps no state between calls, so every replay - with eager work and synchronisation in
+    between - must give exactly what the eager call gives on the same inputs."""
+    import torch
+    from paper_2402_04902_amd import binding
+    spec = LayerSpec(f"qgraph_{T}x{i}x{o}_{bits}b", T, i, o, 8, 16.0, bits, g, DTYPE_BF16)
+    print("case", spec.name, flush=True)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(T * 131 + bits)
+    packed = torch.randint(-2**31, 2**31 - 1, (o, bits * i // 32), dtype=torch.int32, device=dev, generator=gen)
+    s = torch.rand(o, i // g, device=dev, generator=gen) * 0.01 + 0.001
+    b = torch.randn(o, i // g, device=dev, generator=gen) * 0.01
+    X = torch.zeros(T, i, dtype=torch.bfloat16, device=dev)
+    Yg = torch.zeros(T, o, dtype=torch.bfloat16, device=dev)
+    Ye = torch.zeros(T, o, dtype=torch.bfloat16, device=dev)
+    d = binding.make_desc(spec)
+    ws = torch.empty(max(256, binding.l4q_quantized_forward_workspace_bytes(d)), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty_like(ws)
+    binding.l4q_quantized_forward(d, X, packed, s, b, Yg, ws)   # first call outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.l4q_quantized_forward(d, X, packed, s, b, Yg, ws)
+    for rep in range(4):
+        X.copy_(torch.randn(T, i, device=dev, generator=gen).to(torch.bfloat16))
+        Yg.fill_(float("nan"))
+        binding.l4q_quantized_forward(d, X, packed, s, b, Ye, ws2)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(Yg.float()).all()
+        assert torch.equal(Yg.view(torch.int16), Ye.view(torch.int16)), f"replay {rep}"
