@@ -635,26 +635,30 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
 }
 
 // Batches of up to 64 tokens per pass on wide layers (the smallest ones only when their activations do not fit the
-// kernel above).  One workgroup = 64 weight rows, one 16-row tile per wave, every wave
-// walking the whole row (no k-split), so the four waves consume the same k-stage at the same time and can share its
-// activations: a stage of X (TB x 16 tokens x 128 / BITS x 8 k-values) is put into LDS once per workgroup by DMA,
-// swizzled (chunk c of token t at position c ^ (t % 16)) so that the fragment reads of 16 tokens hit 16 different
-// bank groups.  The weights are streamed exactly as in the kernels above (private ring per wave).  The ring is as deep
-// as 160 KB of LDS allow for the stage size (8 stages for one token block, 3 for four): memory returns in order, so
-// the weight stream from HBM and the activations from the L2 share one prefetch distance.  One barrier per stage
-// makes the shared part visible and frees the slot that is refilled next.
-// The zero-point term needs sum_k X per (token, group), which does not depend on the weight row: wave w forms it for
-// token block w with one extra matrix op per fragment (against ones), chained over the sub-steps of a group, and
-// stores the running sum into a table in LDS (no read-modify-write: a wave alone on its SIMD pays every LDS round trip
-// in full); after the loop every lane adds sum_g (zero - K0 scale)[row, g] * table[token, g] to its outputs, the first
-// factor fetched before the loop, held in registers and staged through the LDS the rings have left.  The scales of the 64 rows sit in LDS too (odd row pitch), so the stage loop issues
-// DMA loads only and its partial waits are exact.
+// kernel above).  One workgroup = 64 weight rows in four 16-row tiles, every wave walking its tile's whole row (or the
+// workgroup's k-slice of it), so all waves consume the same k-stage at the same time and can share its activations: a
+// stage of X (TB x 16 tokens x 128 / BITS x 8 k-values) is put into LDS once per workgroup by DMA, swizzled (chunk c
+// of token t at position c ^ (t % 16)) so that the fragment reads of 16 tokens hit 16 different bank groups.  NWV = 4:
+// one wave per row tile with all TB token blocks.  NWV = 8 (even TB): two waves per row tile, each with half of the
+// token blocks; they share the tile's weight ring (each issues half of its loads) and both turn the codes into
+// operands, but a SIMD now holds two waves, and one's LDS round trips and integer work run under the other's matrix
+// ops (measured at [11008 x 4096]: 21 vs 23 us at 32 tokens, 28 vs 35 at 64).  The weights are streamed as in the
+// kernels above (a ring of 2 KB stages per row tile).  The ring is as deep as 160 KB of LDS allow for the stage size
+// (8 stages for one token block, 3 for four): memory returns in order, so the weight stream from HBM and the
+// activations from the L2 share one prefetch distance.  One barrier per stage makes the stage visible to every wave
+// and frees the slot that is refilled next.
+// The zero-point term needs sum_k X per (token, group), which does not depend on the weight row: wave w < TB forms it
+// for token block w with one extra matrix op per fragment (against ones), chained over the sub-steps of a group, and
+// stores the running sum into a table in LDS (no read-modify-write, whose LDS round trips a wave pays in full);
+// after the loop every lane adds sum_g (zero - K0 scale)[row, g] * table[token, g] to its outputs, the first factor
+// fetched before the loop, held in registers and staged through the LDS the rings have left.  The scales of the 64
+// rows sit in LDS too (odd row pitch), so the stage loop issues DMA loads only and its partial waits are exact.
 constexpr int qt_ring_stages(int token_blocks) { return token_blocks == 1 ? 8 : token_blocks == 2 ? 5 : token_blocks == 3 ? 4 : 3; }
 constexpr int QT_SLICES_MAX = 8;  // k-slices of a row tile at most
 constexpr int QT_ROWQ = 6;  // 16-byte pieces of a 64-row scale / zero block per thread: groups per row <= 96
 
-template <int BITS, int TB>
-__global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restrict__ X,
+template <int BITS, int TB, int NWV>
+__global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __restrict__ X,
                                                          const uint32_t* __restrict__ packed,
                                                          const float* __restrict__ scale,
                                                          const float* __restrict__ zero, bf16_t* __restrict__ Y,
@@ -664,15 +668,20 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
 #if defined(__HIP_DEVICE_COMPILE__)
   static_assert(BITS == 4 || BITS == 8, "bits");
   static_assert(TB >= 1 && TB <= 4, "token blocks of 16");
+  static_assert(NWV == 4 || (NWV == 8 && TB % 2 == 0), "4 waves, or 8 with the token blocks split in two halves");
   typedef QsMfma<16> M;
   typedef typename M::acc_t acc_t;
-  constexpr int KG = 4, NH = 2, NDMA = 2;
+  constexpr int TH = NWV / 4;        // waves per 16-row tile, each with TBW of the token blocks
+  constexpr int TBW = TB / TH;
+  constexpr int NT = NWV * 64;
+  constexpr int KG = 4, NH = 2, NDMA = 2 / TH;  // NDMA: this wave's loads of its row tile's weight stage
   constexpr int QT_NS = qt_ring_stages(TB);
   constexpr int CH = 128 / BITS, KS = 8 * CH, FR = CH / 8, SUB = KG * CH;
-  constexpr int WSTAGE = 16 * 128;            // bytes of a weight stage of one wave
+  constexpr int WSTAGE = 16 * 128;            // bytes of a weight stage of one row tile
   constexpr int XROW = KS * 2;                // bytes of a token's activations in a stage
   constexpr int XSTAGE = TB * 16 * XROW;      // bytes of the shared activation stage
-  constexpr int NXW = XSTAGE / 1024 / 4;      // wave-wide activation loads per wave and stage
+  constexpr int NXW = XSTAGE / 1024 / NWV;    // wave-wide activation loads per wave and stage
+  static_assert(NXW >= 1 && NXW * 1024 * NWV == XSTAGE, "the activation stage divides over the waves");
   constexpr int LOADS = NDMA + NXW;           // DMA loads per wave and stage
   constexpr float K0 = BITS == 8 ? 0.f : 128.f + (float)(1 << (BITS - 1));
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -680,7 +689,8 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ln = lane % 16, kg = lane / 16;
-  const int p0 = blockIdx.x * 64 + wave * 16;  // first row of this wave's tile
+  const int rt = wave & 3, th = wave >> 2;    // row tile and token half of this wave
+  const int p0 = blockIdx.x * 64 + rt * 16;   // first row of this wave's tile
   const int p = p0 + ln;
   const int rb = i / 8 * BITS;
   const int G = i / g;
@@ -695,7 +705,7 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
 
-  unsigned char* wring = tlds + wave * (QT_NS * WSTAGE);
+  unsigned char* wring = tlds + rt * (QT_NS * WSTAGE);  // shared by the waves of the row tile
   unsigned char* xring = tlds + 4 * QT_NS * WSTAGE;
   float* sx = reinterpret_cast<float*>(xring + QT_NS * XSTAGE);  // [TB * 16][sx_pitch] sums of X per token and group
   float* sl = sx + TB * 16 * sx_pitch;                           // [64][sx_pitch] scale of the workgroup's rows
@@ -706,8 +716,8 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
       const_cast<bf16_t*>(X), 0, (int)((int64_t)T * i * 2), 0x00020000);
   unsigned voffW[NDMA], voffX[NXW];
 #pragma unroll
-  for (int q = 0; q < NDMA; ++q) {
-    const int r = 8 * q + (lane >> 3);
+  for (int q = 0; q < NDMA; ++q) {  // wave-wide load th NDMA + q of the row tile's stage: rows 8 (th NDMA + q) .. + 7
+    const int r = 8 * (th * NDMA + q) + (lane >> 3);
     const int chunk = (lane & 7) ^ ((r >> 1) & 7);
     voffW[q] = p0 + r < o ? (unsigned)((p0 + r) * rb + chunk * 16) : gemm::OOB_OFFSET;
   }
@@ -726,12 +736,13 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
     unsigned char* xdst = xring + (j % QT_NS) * XSTAGE + wave * NXW * 1024;
 #pragma unroll
     for (int q = 0; q < NDMA; ++q)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcW, (lds_ptr_t)(wdst + q * 1024), 16, voffW[q] + kw, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcW, (lds_ptr_t)(wdst + (th * NDMA + q) * 1024), 16, voffW[q] + kw, 0,
+                                               0, 0);
 #pragma unroll
     for (int q = 0; q < NXW; ++q)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xdst + q * 1024), 16, voffX[q] + kx, 0, 0, 0);
   };
-  const float* srow = sl + (wave * 16 + ln) * sx_pitch;
+  const float* srow = sl + (rt * 16 + ln) * sx_pitch;
 
   // The scale / zero values of the workgroup's 64 weight rows and the slice's groups: each thread fetches up to QT_ROWQ
   // pieces of 4 floats (piece q4 of a row = groups grp_first + 4 q4 .. + 3; rows past the matrix read as zero through
@@ -744,7 +755,7 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   int piece_row[QT_ROWQ], piece_q4[QT_ROWQ];
 #pragma unroll
   for (int q = 0; q < QT_ROWQ; ++q) {
-    const int piece = q * 256 + (int)threadIdx.x;
+    const int piece = q * NT + (int)threadIdx.x;
     piece_row[q] = piece / ppr;
     piece_q4[q] = piece - piece_row[q] * ppr;
   }
@@ -752,7 +763,7 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
 #pragma unroll
     for (int q = 0; q < QT_ROWQ; ++q) {
       const int64_t at = ((int64_t)blockIdx.x * 64 + piece_row[q]) * G + grp_first + 4 * piece_q4[q];
-      const unsigned off = q * 256 + (int)threadIdx.x < 64 * ppr ? (unsigned)(at * 4) : gemm::OOB_OFFSET;
+      const unsigned off = q * NT + (int)threadIdx.x < 64 * ppr ? (unsigned)(at * 4) : gemm::OOB_OFFSET;
       rows[q] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0));
     }
   };
@@ -762,14 +773,14 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
       const float v[4] = {rows[q].x, rows[q].y, rows[q].z, rows[q].w};
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        if (q * 256 + (int)threadIdx.x < 64 * ppr && 4 * piece_q4[q] + c < groups)
+        if (q * NT + (int)threadIdx.x < 64 * ppr && 4 * piece_q4[q] + c < groups)
           table[piece_row[q] * sx_pitch + 4 * piece_q4[q] + c] = v[c];
     }
   };
 
-  acc_t acc[TB];
+  acc_t acc[TBW];  // token blocks th TBW .. th TBW + TBW - 1 of this wave's 16 rows
 #pragma unroll
-  for (int tb = 0; tb < TB; ++tb)
+  for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[tb][e] = 0.f;
 
@@ -789,46 +800,48 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
     for (int h = 0; h < NH; ++h) {
       // every LDS read of the sub-step is issued before the first use: one exposed latency per sub-step
       const u32x4 w = *reinterpret_cast<const u32x4*>(wsrc + (((KG * h + kg) ^ swz) << 4));
-      bf16x8_t xf[FR][TB], xo[FR];
+      bf16x8_t xf[FR][TBW], xo[FR];
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
         const int cpos = ((KG * h + kg) * FR + f) ^ ln;  // swizzled chunk position of this lane's token
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb)
-          xf[f][tb] = *reinterpret_cast<const bf16x8_t*>(xsrc + (tb * 16 + ln) * XROW + cpos * 16);
-        // this wave sums token block `own` (waves beyond the last block repeat it and discard the result); a second
-        // read of that fragment instead of a branch on the wave index keeps the sub-step one straight block
+        for (int tb = 0; tb < TBW; ++tb)
+          xf[f][tb] = *reinterpret_cast<const bf16x8_t*>(xsrc + ((th * TBW + tb) * 16 + ln) * XROW + cpos * 16);
+        // wave w < TB also sums token block w (read by every wave, so that the reads stay one straight block)
         xo[f] = *reinterpret_cast<const bf16x8_t*>(xsrc + (own * 16 + ln) * XROW + cpos * 16);
       }
       const int grp = (st * KS + h * SUB) / g - grp_first;  // position in the tables
       const float sc = srow[grp];
       __builtin_amdgcn_sched_barrier(0);
-      acc_t tw[TB];
+      acc_t tw[TBW];
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb)
+      for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) tw[tb][e] = 0.f;
-      if (grp != tx_grp) {  // a group starts (the groups are whole numbers of sub-steps)
-        tx_grp = grp;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) tx[e] = 0.f;
-      }
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
         const bf16x8_t wf = code_fragment<BITS>(w, f);
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) tw[tb] = M::mma(xf[f][tb], wf, tw[tb]);
-        tx = M::mma(xo[f], ones, tx);
+        for (int tb = 0; tb < TBW; ++tb) tw[tb] = M::mma(xf[f][tb], wf, tw[tb]);
       }
 #pragma unroll
-      for (int tb = 0; tb < TB; ++tb)
+      for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[tb][e] = fmaf(sc, tw[tb][e], acc[tb][e]);
-      // Every column of tx holds the same sums: one lane per token stores the running sum of the group (plain stores,
-      // the last one of a group leaves the whole sum; this wave is the only writer of the cell).
-      if (wave < TB && ln == 0 && j < nst) {
+      if (wave < TB) {  // (uniform over the wave)
+        if (grp != tx_grp) {  // a group starts (the groups are whole numbers of sub-steps)
+          tx_grp = grp;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) sx[(wave * 16 + M::token(e, kg)) * sx_pitch + grp] = tx[e];
+          for (int e = 0; e < 4; ++e) tx[e] = 0.f;
+        }
+#pragma unroll
+        for (int f = 0; f < FR; ++f) tx = M::mma(xo[f], ones, tx);
+        // Every column of tx holds the same sums: one lane per token stores the running sum of the group (plain
+        // stores, the last one of a group leaves the whole sum; this wave is the only writer of the cell).
+        if (ln == 0 && j < nst) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sx[(wave * 16 + M::token(e, kg)) * sx_pitch + grp] = tx[e];
+        }
       }
     }
   };
@@ -881,22 +894,22 @@ __global__ __launch_bounds__(256) void qgemm_tile_kernel(const bf16_t* __restric
   store_rows(bzrows, bzl);
   __syncthreads();
 
-  // zero-point term and store: register e of token block tb is token 16 tb + 4 kg + e of row p
-  const float* bzrow = bzl + (wave * 16 + ln) * bz_pitch;
+  // zero-point term and store: register e of this wave's token block tb is token 16 (th TBW + tb) + 4 kg + e of row p
+  const float* bzrow = bzl + (rt * 16 + ln) * bz_pitch;
 #pragma unroll 4
   for (int grp = 0; grp < groups; ++grp) {
     const float bz = bzrow[grp];
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
+    for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        acc[tb][e] = fmaf(bz, sx[(tb * 16 + M::token(e, kg)) * sx_pitch + grp], acc[tb][e]);
+        acc[tb][e] = fmaf(bz, sx[((th * TBW + tb) * 16 + M::token(e, kg)) * sx_pitch + grp], acc[tb][e]);
   }
 #pragma unroll
-  for (int tb = 0; tb < TB; ++tb)
+  for (int tb = 0; tb < TBW; ++tb)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int tl = tb * 16 + M::token(e, kg), t = t0 + tl;
+      const int tl = (th * TBW + tb) * 16 + M::token(e, kg), t = t0 + tl;
       if (t < T && p < o) {
         if (part == nullptr) Y[(int64_t)t * o + p] = f32_to_bf16(acc[tb][e]);
         else part[((int64_t)slice * n_pass + tl) * o + p] = acc[tb][e];  // [slice][token of the pass][row]
@@ -1042,18 +1055,18 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
         int tb = (n + 15) / 16;
         while (plan.lds[tb] == 0) ++tb;  // a form that does not fit: the next larger one (tb_max fits) masks the tokens
         const size_t lds_bytes = (size_t)plan.lds[tb];
-#define L4Q_QT(B, N)                                                                                                 \
+#define L4Q_QT(B, N, W)                                                                                               \
   do {                                                                                                               \
     if (lds_bytes > 64 * 1024)                                                                                       \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_tile_kernel<B, N>),                             \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_tile_kernel<B, N, W>),                          \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                             \
-    hipLaunchKernelGGL((qgemm_tile_kernel<B, N>), tgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y,    \
-                       part, (int)d.T, t0, (int)d.o, (int)d.i, d.g, pitch);                                          \
+    hipLaunchKernelGGL((qgemm_tile_kernel<B, N, W>), tgrid, dim3(W * 64), lds_bytes, stream, X, packed, scale, zero, \
+                       Y, part, (int)d.T, t0, (int)d.o, (int)d.i, d.g, pitch);                                       \
   } while (0)
         if (d.bits == 4) {
-          if (tb == 1) L4Q_QT(4, 1); else if (tb == 2) L4Q_QT(4, 2); else if (tb == 3) L4Q_QT(4, 3); else L4Q_QT(4, 4);
+          if (tb == 1) L4Q_QT(4, 1, 4); else if (tb == 2) L4Q_QT(4, 2, 8); else if (tb == 3) L4Q_QT(4, 3, 4); else L4Q_QT(4, 4, 8);
         } else {
-          if (tb == 1) L4Q_QT(8, 1); else if (tb == 2) L4Q_QT(8, 2); else if (tb == 3) L4Q_QT(8, 3); else L4Q_QT(8, 4);
+          if (tb == 1) L4Q_QT(8, 1, 4); else if (tb == 2) L4Q_QT(8, 2, 8); else if (tb == 3) L4Q_QT(8, 3, 4); else L4Q_QT(8, 4, 8);
         }
 #undef L4Q_QT
         if (slices > 1) {  // the next pass reuses the partial sums' memory: stream order keeps the two apart
