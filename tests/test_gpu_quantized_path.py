@@ -60,6 +60,34 @@ def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
     test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
 
 
+def _random_tile_cases(count=12, seed=2402):
+    """Seeded draw of problems for the 64-row tile kernel: wide layers (every compute unit gets a tile) and narrow
+    ones with long rows (k-slices through the workspace), 4 and 8 bits, groups of one to four sub-steps, 1 .. 100
+    tokens (every count of token blocks, several passes), ragged last row tiles."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        bits = int(rng.choice([4, 8]))
+        unit = 256 if bits == 4 else 128            # codes of a 128-byte stage
+        g = int(rng.choice([unit // 2, unit, 2 * unit]))
+        if k % 2 == 0:                              # wide
+            o = 10240 + 8 * int(rng.integers(0, 200))
+            i = unit * int(rng.integers(1, 9))
+        else:                                       # narrow, long rows
+            o = 2048 + 8 * int(rng.integers(0, 500))
+            i = unit * int(rng.integers(8, 24))
+        while i % g != 0:
+            i += unit
+        T = int(rng.choice([1, 7, 16, 17, 30, 32, 33, 47, 48, 49, 64, 65, 81, 100]))
+        cases.append((k, T, i, o, bits, g))
+    return cases
+
+
+@pytest.mark.parametrize("k,T,i,o,bits,g", _random_tile_cases())
+def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
+    test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
+
+
 @pytest.mark.parametrize("T,i,o,bits,g", [
     (1, 256, 72, 4, 64), (7, 512, 264, 4, 128), (64, 1024, 520, 3, 64), (33, 256, 40, 2, 8), (100, 320 * 2, 96, 8, 32),
     (16, 4096, 11008, 4, 128),      # LLaMA-7B up projection at a decode batch
@@ -79,7 +107,7 @@ def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
     # 8-bit g = 128), long rows that leave LDS for two token blocks only, a small batch too long for the LDS-resident
     # form
     (64, 4096, 11008, 4, 128), (70, 1024, 10248, 4, 128), (40, 896, 10312, 8, 128), (48, 11008, 10240, 4, 128),
-    (24, 2048, 10304, 4, 256), (13, 4096, 10240, 4, 64),
+    (24, 2048, 10304, 4, 256), (13, 4096, 10240, 4, 64), (30, 1024, 10240, 8, 64),
     # few row tiles and long rows with a workspace: k-slices over the compute units (4, 2 and 3 slices; a slice
     # boundary inside a group (g = 1024); 8-bit; two passes; stage counts that do not divide by the slices)
     (64, 11008, 4096, 4, 128), (33, 8192, 8192, 4, 128), (48, 5120, 5000, 4, 1024), (80, 2304, 4104, 8, 128),
