@@ -166,10 +166,11 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
         for (int e = 0; e < 4; ++e) {
           const float x = acc.v[a][b][4 * eg + e];
           const float f = (float)fh[e];
-          const bool clipped = fabsf(f) > 0.75f;
+          // one use of the comparison (a second one keeps 64 lane masks alive in scalar registers and spills them):
+          // x - xm is exactly x where the element is clipped and 0 elsewhere
+          xm[e] = fabsf(f) > 0.75f ? 0.f : x;
           ds_b[b] = fmaf(x, f, ds_b[b]);
-          db_b[b] += clipped ? x : 0.f;
-          xm[e] = clipped ? 0.f : x;
+          db_b[b] += x - xm[e];
         }
         pk[b][2 * eg] = pack_bf16x2(xm[0], xm[1]);
         pk[b][2 * eg + 1] = pack_bf16x2(xm[2], xm[3]);
@@ -247,14 +248,19 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
   }
 
   // ---- dB partials: register e of lane l is (row 8 (e/4) + 4 (l/32) + e%4 of the block, rank l % 32)
+  //      Stored through a buffer descriptor of this partial's [o, r] block: rows past o fall beyond its range and are
+  //      dropped by the hardware, lanes past the rank get an out-of-range offset, so the 64 stores carry no branches.
   {
     float* dst = p.dB_part + (int64_t)(tile_n * 2 + wn) * p.o * p.r;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(dst, 0, p.o * p.r * 4, 0x00020000);
+    const unsigned lane_off = l32 < p.r ? (unsigned)(((m0 + wm * 128 + 4 * lh) * p.r + l32) * 4) : gemm::OOB_OFFSET;
 #pragma unroll
     for (int a = 0; a < T::TM; ++a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * 128 + a * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
-        if (l32 < p.r && row < p.o) dst[(int64_t)row * p.r + l32] = accB[a][e];
+        const unsigned row_off = (unsigned)((a * 32 + 8 * (e >> 2) + (e & 3)) * p.r * 4);  // uniform
+        const float v = accB[a][e];
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rsrc, lane_off + row_off, 0, 0);
       }
     }
   }
@@ -301,15 +307,18 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
       ca[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, gfrag, ca[nb], 0, 0, 0);
     }
   }
-  {
+  {  // this tile row's [r, i] block through a buffer descriptor: rank indices past r fall beyond its range
     float* dst = p.dA_part + (int64_t)tile_m * p.r * p.i;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(dst, 0, p.r * p.i * 4, 0x00020000);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       const int j = n0 + wave * 64 + nb * 32 + l32;
+      const unsigned lane_off = j < p.i ? (unsigned)((4 * lh * p.i + j) * 4) : gemm::OOB_OFFSET;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int k = 8 * (e >> 2) + 4 * lh + (e & 3);
-        if (k < p.r && j < p.i) dst[(int64_t)k * p.i + j] = ca[nb][e];
+        const unsigned k_off = (unsigned)((8 * (e >> 2) + (e & 3)) * p.i * 4);  // uniform
+        const float v = ca[nb][e];
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rsrc, lane_off + k_off, 0, 0);
       }
     }
   }
