@@ -17,8 +17,8 @@
 //  * group sums over j are in-lane adds plus one exchange with lane ^ 32;
 //  * dB is a second MFMA straight from the registers: the masked gradient is the row operand and
 //    the 8 k-slots of a lane are loaded from A with the same column pattern;
-//  * dA contracts over p, the lane axis, so the masked tile goes through LDS once, transposed
-//    ([j][p], 2-byte writes, 16-byte fragment reads), and is multiplied with B^T.
+//  * dA contracts over p, the lane axis, so the masked tile goes through LDS once (row-major, 8-byte writes of what a
+//    lane holds; the transposing LDS read turns it into operand fragments) and is multiplied with B^T.
 // Partial results per tile row / tile column go to the workspace and are summed by a second,
 // tiny kernel in a fixed order, so the result does not depend on scheduling.
 #include "l4q_device.h"
@@ -32,7 +32,7 @@ namespace {
 typedef gemm::Tile<256, 256, 32, 5> T;
 static_assert(T::WTM == 128 && T::WTN == 128 && T::TM == 4 && T::TN == 4, "epilogue is written for 128 x 128 wave tiles");
 
-constexpr int EP_ROWB = 256 * 2 + 16;             // bytes per [j] row of the transposed tile: 256 p + pad
+constexpr int EP_ROWB = 256 * 2 + 16;             // bytes per row p of the masked tile in LDS: 256 columns + pad
 constexpr int EP_TILE = 256 * EP_ROWB;            // 135168
 constexpr int EP_SCRATCH = 2 * 128 * 2 * 4;       // per wave-row pair: 128 rows x (dscale, dzero)
 constexpr int EP_LDS = EP_TILE + EP_SCRATCH;
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
           const float f = (float)fh[e];
           // one use of the comparison (a second one keeps 64 lane masks alive in scalar registers and spills them):
           // x - xm is exactly x where the element is clipped and 0 elsewhere
-          xm[e] = fabsf(f) > 0.75f ? 0.f : x;
+          xm[e] = __builtin_fabsf16(fh[e]) > (_Float16)0.75f ? 0.f : x;  // decided on the stored binary16 value
           ds_b[b] = fmaf(x, f, ds_b[b]);
           db_b[b] += x - xm[e];
         }
@@ -234,15 +234,14 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     }
     accB[a] = cb;
 
-    // ---- masked gradient, transposed, to LDS: element (p, j) at [j][p]
+    // ---- masked gradient to LDS as it lies in the registers: row p, 4 consecutive columns per 8-byte write
 #pragma unroll
     for (int b = 0; b < T::TN; ++b) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int jl = wn * 128 + b * 32 + 8 * (e >> 2) + 4 * lh + (e & 3);
+      for (int eg = 0; eg < 4; ++eg) {
+        const int jl = wn * 128 + b * 32 + 8 * eg + 4 * lh;
         const int pl = wm * 128 + a * 32 + l32;
-        const uint32_t w = pk[b][e >> 1];
-        *reinterpret_cast<uint16_t*>(lds + jl * EP_ROWB + pl * 2) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
+        *reinterpret_cast<uint2*>(lds + pl * EP_ROWB + jl * 2) = make_uint2(pk[b][2 * eg], pk[b][2 * eg + 1]);
       }
     }
   }
@@ -297,14 +296,24 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
   for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
     for (int e = 0; e < 16; ++e) ca[nb][e] = 0.f;
+  // The operand wants, per lane, 8 consecutive rows p of one column: the transposing LDS read delivers that from the
+  // row-major tile.  Lane (g16, j16) of a read fetches 4 columns of row 8 (g16 / 2) + j16 / 4 (and of the row 4 below
+  // for the second half); the hardware exchanges them within each group of 16 lanes.
+  typedef short s16x4_t __attribute__((ext_vector_type(4)));
+  typedef short s16x8_t __attribute__((ext_vector_type(8)));
+  typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr_t;
+  const int j16 = lane & 15, g16 = lane >> 4;
+  const unsigned tr_off = (unsigned)((8 * (g16 >> 1) + (j16 >> 2)) * EP_ROWB + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2);
 #pragma unroll
   for (int ks = 0; ks < 16; ++ks) {
     const bf16x8_t bfrag = __builtin_bit_cast(bf16x8_t, bt_all[ks]);
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-      const int jl = wave * 64 + nb * 32 + l32;
-      const bf16x8_t gfrag = *reinterpret_cast<const bf16x8_t*>(lds + jl * EP_ROWB + ks * 32 + lh * 16);
-      ca[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, gfrag, ca[nb], 0, 0, 0);
+      const unsigned char* p0 = lds + tr_off + ks * 16 * EP_ROWB + (wave * 64 + nb * 32) * 2;
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)p0);
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(p0 + 4 * EP_ROWB));
+      const s16x8_t gv = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      ca[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, __builtin_bit_cast(bf16x8_t, gv), ca[nb], 0, 0, 0);
     }
   }
   {  // this tile row's [r, i] block through a buffer descriptor: rank indices past r fall beyond its range
