@@ -260,6 +260,18 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
   const float zero4[4] = {0.f, 0.f, 0.f, 0.f};
   constexpr bool want_wq = MODE != 2, want_t = MODE != 1, want_f = MODE != 1, want_misc = MODE == 0;
 
+  // bf16 operands are below 1 GiB (checked by the caller): rows are addressed through buffer descriptors, 32-bit lane
+  // offset plus a wave-uniform row offset in a scalar register, which takes the 64-bit address arithmetic off the
+  // vector unit (a fifth of this kernel's vector instructions before)
+  constexpr bool BUF = std::is_same<T, bf16_t>::value;
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  const __amdgpu_buffer_rsrc_t rsrcW0 = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<T*>(W0), 0, BUF ? (int)(d.o * d.i * 2) : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcS = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(scale), 0, BUF ? (int)(d.o * G * 4) : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(zero), 0, BUF ? (int)(d.o * G * 4) : 0, 0x00020000);
+
   // row data: every load is requested before the rank sums are consumed
   raw4_t w0raw[MQ_RPW];
   float sv[MQ_RPW], bv[MQ_RPW];
@@ -267,10 +279,17 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
 #pragma unroll
     for (int rr = 0; rr < MQ_RPW; ++rr) {
       const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
-      // wave-uniform row base first, lane offset second: the loads take a scalar base register
-      w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
-      sv[rr] = (scale + pc * G)[q];
-      bv[rr] = (zero + pc * G)[q];
+      if constexpr (BUF) {
+        const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrcW0, (int)(jc * 2), (int)(pc * d.i * 2), 0);
+        w0raw[rr] = make_uint2(w[0], w[1]);
+        sv[rr] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrcS, (int)(q * 4), (int)(pc * G * 4), 0));
+        bv[rr] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrcZ, (int)(q * 4), (int)(pc * G * 4), 0));
+      } else {
+        // wave-uniform row base first, lane offset second: the loads take a scalar base register
+        w0raw[rr] = *reinterpret_cast<const raw4_t*>((W0 + pc * d.i) + jc);
+        sv[rr] = (scale + pc * G)[q];
+        bv[rr] = (zero + pc * G)[q];
+      }
     }
   };
 
@@ -301,8 +320,16 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
     const int64_t rowoff = p * d.i;  // wave-uniform
     if (want_wq && (MODE == 1 || out.wq) && p < d.o) {
       // the dequantized weight is zero-padded up to its leading dimension (k-step of the GEMM)
-      if (col_ok) store4((out.wq + p * out.ld_wq) + j32, wqv);
-      else if (j0 < out.ld_wq) store4((out.wq + p * out.ld_wq) + j32, zero4);
+      if constexpr (BUF) {  // one store per lane: the values, zeros in the padding, dropped (offset out of range) past it
+        const __amdgpu_buffer_rsrc_t rsrcWq = __builtin_amdgcn_make_buffer_rsrc(
+            out.wq, 0, (int)(d.o * out.ld_wq * 2), 0x00020000);
+        const u32x2 v = {col_ok ? pack_bf16x2(wqv[0], wqv[1]) : 0u, col_ok ? pack_bf16x2(wqv[2], wqv[3]) : 0u};
+        const unsigned voff = j0 < out.ld_wq ? j32 * 2u : 0x80000000u;
+        __builtin_amdgcn_raw_buffer_store_b64(v, rsrcWq, (int)voff, (int)(p * out.ld_wq * 2), 0);
+      } else {
+        if (col_ok) store4((out.wq + p * out.ld_wq) + j32, wqv);
+        else if (j0 < out.ld_wq) store4((out.wq + p * out.ld_wq) + j32, zero4);
+      }
     }
     if (ok) {
       if (want_misc) {
@@ -310,10 +337,20 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
         if (out.mask) *reinterpret_cast<uint32_t*>((out.mask + rowoff) + j32) = mpack;
         if (out.wcomb) store4((out.wcomb + rowoff) + j32, wc);
       }
-      if (want_f && (MODE == 2 || out.fgrad)) {
+      if (!BUF && want_f && (MODE == 2 || out.fgrad)) {
         typedef _Float16 h4 __attribute__((ext_vector_type(4)));
         h4 h = {(_Float16)fg[0], (_Float16)fg[1], (_Float16)fg[2], (_Float16)fg[3]};
         *reinterpret_cast<h4*>((out.fgrad + rowoff) + j32) = h;
+      }
+    }
+    if constexpr (BUF) {
+      if (want_f && (MODE == 2 || out.fgrad) && p < d.o) {  // (uniform) lanes past the last column: offset out of range
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        const h4 h = {(_Float16)fg[0], (_Float16)fg[1], (_Float16)fg[2], (_Float16)fg[3]};
+        const __amdgpu_buffer_rsrc_t rsrcF = __builtin_amdgcn_make_buffer_rsrc(
+            out.fgrad, 0, (int)(d.o * d.i * 2), 0x00020000);
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, h), rsrcF, (int)(col_ok ? j32 * 2u : 0x80000000u),
+                                              (int)(rowoff * 2), 0);
       }
     }
   }
