@@ -506,7 +506,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_stream_kernel(const bf16_t* __re
 // per wave: 4 when several workgroups share a compute unit, 8 when there is at most one per unit and a wave has to
 // keep more of the stream in flight by itself.
 constexpr int QD_X_MAX = 96 * 1024;   // bytes of X held in LDS
-constexpr int QD_SB_MAX = 16 * 1024;  // bytes of scale + zero held in LDS
+constexpr int QD_SB_MAX = 17 * 1024;  // bytes of scale + zero held in LDS (up to 128 groups per row)
 constexpr int QD_LDS_MAX = 160 * 1024; // LDS of a compute unit
 
 template <int BITS, int NSW>
@@ -566,17 +566,30 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
   };
 
   // the first NSW - 1 weight stages, then X (1 KiB pieces round-robin over the waves; bytes past the end of X read
-  // as zero), then scale / zero of the tile's rows through registers into the padded LDS rows
+  // as zero), then scale / zero of the tile's rows, all by DMA into LDS
 #pragma unroll
   for (int j = 0; j < NSW - 1; ++j) issue_dma(j);
   for (int q = wave; q < x_bytes / 1024; q += 4)
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xl + q * 1024), 16, (unsigned)(q * 1024 + lane * 16), 0,
                                              0, 0);
-  for (int idx = threadIdx.x; idx < ROWS * G; idx += 256) {
-    const int row = idx / G, grp = idx - row * G;
-    const int64_t src = (int64_t)(p0 + row < o ? p0 + row : o - 1) * G + grp;
-    sl[row * sb_pitch + grp] = scale[src];
-    bl[row * sb_pitch + grp] = zero[src];
+  {
+    // Per table row ceil(G / 64) wave-wide loads of 4 bytes per lane, straight into the padded LDS row: nothing passes
+    // through registers and nothing waits before the common wait below (a loop of load - wait - store rounds cost a
+    // memory latency per round: same box, [4096 x 11008] at one token 8.9 against 10.0 us).  Lanes past the row's G
+    // values and rows past o get out-of-range offsets and write zeros, which the pitch (a multiple of 64, plus 1)
+    // keeps inside the row's own padding.
+    const __amdgpu_buffer_rsrc_t rsrcS = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(scale), 0, (int)((int64_t)o * G * 4), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(zero), 0, (int)((int64_t)o * G * 4), 0x00020000);
+    const int per_row = (G + 63) / 64;
+    for (int u = wave; u < ROWS * per_row; u += 4) {
+      const int row = u / per_row, c = u - row * per_row;
+      const int idx = c * 64 + lane;
+      const unsigned off = idx < G && p0 + row < o ? (unsigned)(((p0 + row) * G + idx) * 4) : gemm::OOB_OFFSET;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcS, (lds_ptr_t)(sl + row * sb_pitch + c * 64), 4, off, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcZ, (lds_ptr_t)(bl + row * sb_pitch + c * 64), 4, off, 0, 0, 0);
+    }
   }
   __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
   __syncthreads();
@@ -1013,7 +1026,7 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
   // smallest batches: activations and the tile's scale / zero in LDS
   if (d.T <= 16 && qgemm_stream_rows(d, (int)d.T) == 16) {
     const int64_t xb = (d.T * d.i * 2 + 1023) / 1024 * 1024;
-    const int64_t G = d.i / d.g, pitch = G | 1;
+    const int64_t G = d.i / d.g, pitch = 64 * ((G + 63) / 64) + 1;  // whole 64-lane loads per row, odd: no bank conflicts
     const int64_t sbb = 2 * 16 * pitch * 4;
     const int64_t tiles = (d.o + 15) / 16;
     int nsw = tiles <= device_compute_units() ? 8 : 4;
