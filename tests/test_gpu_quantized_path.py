@@ -189,3 +189,35 @@ def test_quantized_forward_replayed_from_a_graph(T, i, o, bits, g):
         torch.cuda.synchronize()
         assert torch.isfinite(Yg.float()).all()
         assert torch.equal(Yg.view(torch.int16), Ye.view(torch.int16)), f"replay {rep}"
+
+
+def test_quantized_forward_ignores_a_short_workspace():
+    """A workspace smaller than the layer can use is ignored: the result is the one computed without any, bit for bit,
+    and nothing is written past the bytes that were passed."""
+    import torch
+    from paper_2402_04902_amd import binding
+    T, i, o, bits, g = 40, 4096, 4096, 4, 128
+    spec = LayerSpec("qshort_ws", T, i, o, 8, 16.0, bits, g, DTYPE_BF16)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77)
+    packed = torch.randint(-2**31, 2**31 - 1, (o, bits * i // 32), dtype=torch.int32, device=dev, generator=gen)
+    s = torch.rand(o, i // g, device=dev, generator=gen) * 0.01 + 0.001
+    b = torch.randn(o, i // g, device=dev, generator=gen) * 0.01
+    X = torch.randn(T, i, device=dev, generator=gen).to(torch.bfloat16)
+    d = binding.make_desc(spec)
+    need = binding.l4q_quantized_forward_workspace_bytes(d)
+    assert need > 0
+    guard = torch.full((need,), 0x5A, dtype=torch.uint8, device=dev)
+    Y0 = torch.empty(T, o, dtype=torch.bfloat16, device=dev)
+    Y1 = torch.empty_like(Y0)
+    Y2 = torch.empty_like(Y0)
+    binding.l4q_quantized_forward(d, X, packed, s, b, Y0)
+    binding.l4q_quantized_forward(d, X, packed, s, b, Y1, guard[: need // 2])
+    torch.cuda.synchronize()
+    assert torch.equal(Y0.view(torch.int16), Y1.view(torch.int16))
+    assert bool((guard == 0x5A).all())
+    binding.l4q_quantized_forward(d, X, packed, s, b, Y2, guard)   # the full workspace is used
+    torch.cuda.synchronize()
+    assert not bool((guard == 0x5A).all())
+    assert float((Y2.float() - Y0.float()).abs().max()) <= 0.02 * float(Y0.float().abs().max())
