@@ -647,6 +647,177 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
 #endif
 }
 
+// The same kernel for 3-bit codes.  A 128-byte stage is not a whole number of 3-bit codes; three stages (384 bytes =
+// 1024 codes) are, so the unit a wave streams, rings and consumes is such a super-stage, in 8 sub-steps of 128 codes:
+// lane group kg of sub-step h owns codes 32 (4 h + kg) .. + 31 = the 12 bytes from (4 h + kg) 12 of the row's 384, read
+// as three dwords (a piece can straddle two 16-byte chunks, or two stages, of the swizzled layout).  Rows need not be
+// whole cache lines nor whole super-stages (i = 11008: 4128 bytes, 10.75 super-stages): the activations sit in LDS with
+// every token padded with zeros to the next multiple of 1024 k-values, so whatever packed bytes follow a row's end
+// (the next row's codes, or zeros past the matrix) meet activations that are zero, and the padded groups' scale and
+// zero are the zeros of the table's own padding.  Fragment f of a piece is a 24-bit window; code pairs become bf16
+// pairs as for 4 bits, with 6-bit fields and 0x2001 as the spreading factor (K0 = 128 + 4).
+template <int NSS>
+__global__ __launch_bounds__(256, 2) void qgemm_decode3_kernel(const bf16_t* __restrict__ X,
+                                                                const uint32_t* __restrict__ packed,
+                                                                const float* __restrict__ scale,
+                                                                const float* __restrict__ zero,
+                                                                bf16_t* __restrict__ Y, int T, int o, int i, int g,
+                                                                int ipad, int sb_pitch) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char d3lds[];
+#if defined(__HIP_DEVICE_COMPILE__)
+  constexpr int ROWS = 16;
+  constexpr int STAGE = ROWS * 128, SS = 3 * STAGE;  // bytes of a stage and of a super-stage of one wave
+  typedef QsMfma<ROWS> M;
+  typedef typename M::acc_t acc_t;
+  constexpr int NACC = M::NACC;
+  constexpr int KG = 4, NH = 8, NDMA = 6;             // lane groups, sub-steps and DMA loads of a super-stage
+  constexpr int CH = 32, KS = 1024, FR = 4, SUB = 128;  // codes of a piece, a super-stage, fragments of a piece, codes of a sub-step
+  constexpr float K0 = 128.f + 4.f;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef gemm::lds_ptr_t lds_ptr_t;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ln = lane % ROWS, kg = lane / ROWS;
+  const int p0 = blockIdx.x * ROWS;
+  const int p = p0 + ln;
+  const int rb = i / 8 * 3;        // bytes of a packed row
+  const int nss = ipad / KS;       // super-stages of a (padded) row
+  const int G = i / g, Gp = ipad / g;
+  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
+  const int x_bytes = T * ipad * 2;
+
+  unsigned char* ring = d3lds + wave * (NSS * SS);
+  unsigned char* xl = d3lds + 4 * NSS * SS;                    // [T][ipad] bf16, zeros past i
+  float* sl = reinterpret_cast<float*>(xl + x_bytes);          // [16][sb_pitch]
+  float* bl = sl + ROWS * sb_pitch;
+
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(packed), 0, (int)((int64_t)o * rb), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcX = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(X), 0, (int)((int64_t)T * i * 2), 0x00020000);
+  unsigned voff[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int r = 8 * q + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+    voff[q] = p0 + r < o ? (unsigned)((p0 + r) * rb + chunk * 16) : gemm::OOB_OFFSET;
+  }
+  const int nj = wave < nss ? (nss - wave + 3) / 4 : 0;  // super-stages of this wave: wave, wave + 4, ...
+  auto issue_dma = [&](int j) {
+    unsigned char* dst = ring + (j % NSS) * SS;
+#pragma unroll
+    for (int s3 = 0; s3 < 3; ++s3) {
+      const unsigned kb = j < nj ? (unsigned)(3 * (wave + 4 * j) + s3) * 128u : gemm::PAST_END_OFFSET;
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(dst + s3 * STAGE + q * 1024), 16, voff[q] + kb, 0,
+                                                 0, 0);
+    }
+  };
+
+#pragma unroll
+  for (int j = 0; j < NSS - 1; ++j) issue_dma(j);
+  {  // X: 1 KiB pieces (512 k-values of one token) round-robin over the waves; k-values past i read as zero
+    const int ppr = ipad / 512;  // pieces per token
+    for (int u = wave; u < T * ppr; u += 4) {
+      const int t = u / ppr, c = u - t * ppr;
+      const int k = c * 512 + lane * 8;
+      const unsigned off = k < i ? (unsigned)(((int64_t)t * i + k) * 2) : gemm::OOB_OFFSET;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xl + (size_t)t * ipad * 2 + c * 1024), 16, off, 0, 0,
+                                               0);
+    }
+  }
+  {  // scale / zero rows of the tile, padded groups included (they read as zero)
+    const __amdgpu_buffer_rsrc_t rsrcS = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(scale), 0, (int)((int64_t)o * G * 4), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(zero), 0, (int)((int64_t)o * G * 4), 0x00020000);
+    const int per_row = (Gp + 63) / 64;
+    for (int u = wave; u < ROWS * per_row; u += 4) {
+      const int row = u / per_row, c = u - row * per_row;
+      const int idx = c * 64 + lane;
+      const unsigned off = idx < G && p0 + row < o ? (unsigned)(((p0 + row) * G + idx) * 4) : gemm::OOB_OFFSET;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcS, (lds_ptr_t)(sl + row * sb_pitch + c * 64), 4, off, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcZ, (lds_ptr_t)(bl + row * sb_pitch + c * 64), 4, off, 0, 0, 0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
+  __syncthreads();
+
+  const int swz = (ln >> 1) & 7;
+  const int tok = ln < T ? ln : T - 1;
+  const unsigned char* xrow = xl + (size_t)tok * ipad * 2;
+  const float* srow = sl + ln * sb_pitch;
+  const float* brow = bl + ln * sb_pitch;
+  // LDS offsets of the three dwords of this lane's piece in every sub-step, relative to the row's place in the slot
+  unsigned piece_off[NH][3];
+#pragma unroll
+  for (int h = 0; h < NH; ++h)
+#pragma unroll
+    for (int dw = 0; dw < 3; ++dw) {
+      const int byte = (4 * h + kg) * 12 + 4 * dw;
+      const int st = byte >> 7, b = byte & 127;
+      piece_off[h][dw] = (unsigned)(st * STAGE + (((b >> 4) ^ swz) << 4) + (b & 15));
+    }
+
+  acc_t acc;
+#pragma unroll
+  for (int e = 0; e < NACC; ++e) acc[e] = 0.f;
+
+  for (int j = 0; j < nj; ++j) {
+    issue_dma(j + NSS - 1);
+    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm((NSS - 1) * NDMA));  // super-stage j has landed
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned char* src = ring + (j % NSS) * SS + ln * 128;
+    const int k0 = (wave + 4 * j) * KS;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      const uint32_t d0 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][0]);
+      const uint32_t d1 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][1]);
+      const uint32_t d2 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][2]);
+      // the four 24-bit windows of the 96-bit piece
+      const uint32_t win[FR] = {d0 & 0xFFFFFFu, ((d0 >> 24) | (d1 << 8)) & 0xFFFFFFu,
+                                ((d1 >> 16) | (d2 << 16)) & 0xFFFFFFu, d2 >> 8};
+      const int grp = (k0 + h * SUB) / g;
+      const float sc = srow[grp], bz = brow[grp] - K0 * sc;
+      acc_t tw, tx;
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) { tw[e] = 0.f; tx[e] = 0.f; }
+#pragma unroll
+      for (int f = 0; f < FR; ++f) {
+        u32x4 d;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {  // codes 2r (bits 0..2 of the 6-bit field) and 2r + 1 (bits 3..5 -> bits 16..18)
+          const uint32_t spread = __builtin_amdgcn_ubfe(win[f], 6 * r, 6) * 0x2001u;
+          d[r] = (spread & 0x00070007u) | 0x43004300u;
+        }
+        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+        const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xrow + (size_t)(k0 + (KG * h + kg) * CH + 8 * f) * 2);
+        tw = M::mma(xf, wf, tw);
+        tx = M::mma(xf, ones, tx);
+      }
+#pragma unroll
+      for (int e = 0; e < NACC; ++e) acc[e] = fmaf(bz, tx[e], fmaf(sc, tw[e], acc[e]));
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
+  __syncthreads();  // every wave is done with its ring: the LDS is reused for the sum over the waves
+
+  float* red = reinterpret_cast<float*>(d3lds);
+#pragma unroll
+  for (int e = 0; e < NACC; ++e) red[(wave * NACC + e) * 64 + lane] = acc[e];
+  __syncthreads();
+  {
+    const int e = wave;  // wave w finishes register w: token 4 kg + w
+    const float v = (red[(0 * NACC + e) * 64 + lane] + red[(1 * NACC + e) * 64 + lane]) +
+                    (red[(2 * NACC + e) * 64 + lane] + red[(3 * NACC + e) * 64 + lane]);
+    const int t = M::token(e, kg);
+    if (t < T && p < o) Y[(int64_t)t * o + p] = f32_to_bf16(v);
+  }
+#endif
+}
+
 // Batches of up to 64 tokens per pass on wide layers (the smallest ones only when their activations do not fit the
 // kernel above).  One workgroup = 64 weight rows in four 16-row tiles, every wave walking its tile's whole row (or the
 // workgroup's k-slice of it), so all waves consume the same k-stage at the same time and can share its activations: a
@@ -1048,6 +1219,32 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
       else if (nsw == 4) L4Q_QD(8, 4);
       else L4Q_QD(8, 8);
 #undef L4Q_QD
+      return;
+    }
+  }
+  // 3 bits, smallest batches: the LDS-resident form with three-stage units
+  if (d.bits == 3 && d.T <= 16 && d.i % 128 == 0 && d.g % 128 == 0 && d.o * (d.i / 8 * 3) < (1ll << 31)) {
+    const int64_t ipad = (d.i + 1023) / 1024 * 1024;
+    const int64_t xb = d.T * ipad * 2;
+    const int64_t Gp = ipad / d.g, pitch = 64 * ((Gp + 63) / 64) + 1;
+    const int64_t sbb = 2 * 16 * pitch * 4;
+    const int64_t tiles = (d.o + 15) / 16;
+    const auto fits = [&](int n) { return 4 * n * 3 * 2048 + xb + sbb <= QD_LDS_MAX; };
+    int nss = tiles <= device_compute_units() && fits(3) ? 3 : 2;  // a lone workgroup per unit keeps more in flight
+    if (xb <= QD_X_MAX && sbb <= QD_SB_MAX && fits(nss)) {
+      const size_t lds_bytes = (size_t)(4 * nss * 3 * 2048 + xb + sbb);
+      dim3 sgrid((unsigned)tiles);
+#define L4Q_QD3(N)                                                                                                 \
+  do {                                                                                                             \
+    if (lds_bytes > 64 * 1024)                                                                                     \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode3_kernel<N>),                           \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                           \
+    hipLaunchKernelGGL((qgemm_decode3_kernel<N>), sgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y,  \
+                       (int)d.T, (int)d.o, (int)d.i, d.g, (int)ipad, (int)pitch);                                  \
+  } while (0)
+      if (nss == 2) L4Q_QD3(2);
+      else L4Q_QD3(3);
+#undef L4Q_QD3
       return;
     }
   }

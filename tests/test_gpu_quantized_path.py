@@ -112,6 +112,11 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     # boundary inside a group (g = 1024); 8-bit; two passes; stage counts that do not divide by the slices)
     (64, 11008, 4096, 4, 128), (33, 8192, 8192, 4, 128), (48, 5120, 5000, 4, 1024), (80, 2304, 4104, 8, 128),
     (17, 4096, 4096, 4, 128),
+    # 3 bits at the smallest batches: the LDS-resident form on three-stage units; both projections (rows of 11008
+    # codes are neither whole cache lines nor whole units), ragged row tiles, row lengths of 1.125, 2 and 1/8 units,
+    # groups of two sub-steps, 16 tokens
+    (1, 4096, 11008, 3, 128), (1, 11008, 4096, 3, 128), (12, 4096, 1000, 3, 128), (5, 1152, 264, 3, 128),
+    (16, 2048, 72, 3, 256), (3, 128, 40, 3, 128), (4, 11008, 4096, 3, 128),
     # 70B-class projections: the widest layer at a small batch, the longest rows (too many groups for the tile kernel's
     # tables: the streaming forms take it)
     (4, 8192, 28672, 4, 128), (40, 28672, 8192, 4, 128),
