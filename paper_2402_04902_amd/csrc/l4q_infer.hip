@@ -311,6 +311,16 @@ __device__ __forceinline__ bf16x8_t code_fragment(const code_chunk_t& w, int f) 
       asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
       d[r] = pair;
     }
+  } else if (BITS == 3) {
+    // the chunk's first three dwords hold 32 codes; fragment f is the 24-bit window from bit 24 f, its code pairs are
+    // 6-bit fields: times 0x2001 puts a copy 13 bits up, the mask leaves code 2r in bits 0..2 and code 2r + 1 in bits
+    // 16..18 (the caller's K0 is 128 + 4)
+    const uint32_t win = f == 0 ? w[0] : f == 1 ? (w[0] >> 24) | (w[1] << 8) : f == 2 ? (w[1] >> 16) | (w[2] << 16) : w[2] >> 8;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t spread = __builtin_amdgcn_ubfe(win, 6 * r, 6) * 0x2001u;
+      d[r] = (spread & 0x00070007u) | 0x43004300u;
+    }
   } else {
     const uint32_t v0 = w[(2 * f) & 3], v1 = w[(2 * f + 1) & 3];  // 4 + 4 codes
     d[0] = pack_bf16x2((float)(v0 & 0xFFu) - 128.f, (float)((v0 >> 8) & 0xFFu) - 128.f);
@@ -776,9 +786,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode3_kernel(const bf16_t* __r
       const uint32_t d0 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][0]);
       const uint32_t d1 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][1]);
       const uint32_t d2 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][2]);
-      // the four 24-bit windows of the 96-bit piece
-      const uint32_t win[FR] = {d0 & 0xFFFFFFu, ((d0 >> 24) | (d1 << 8)) & 0xFFFFFFu,
-                                ((d1 >> 16) | (d2 << 16)) & 0xFFFFFFu, d2 >> 8};
+      const u32x4 w = {d0, d1, d2, 0u};
       const int grp = (k0 + h * SUB) / g;
       const float sc = srow[grp], bz = brow[grp] - K0 * sc;
       acc_t tw, tx;
@@ -786,13 +794,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode3_kernel(const bf16_t* __r
       for (int e = 0; e < NACC; ++e) { tw[e] = 0.f; tx[e] = 0.f; }
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
-        u32x4 d;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {  // codes 2r (bits 0..2 of the 6-bit field) and 2r + 1 (bits 3..5 -> bits 16..18)
-          const uint32_t spread = __builtin_amdgcn_ubfe(win[f], 6 * r, 6) * 0x2001u;
-          d[r] = (spread & 0x00070007u) | 0x43004300u;
-        }
-        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, d);
+        const bf16x8_t wf = code_fragment<3>(w, f);
         const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xrow + (size_t)(k0 + (KG * h + kg) * CH + 8 * f) * 2);
         tw = M::mma(xf, wf, tw);
         tx = M::mma(xf, ones, tx);
@@ -850,18 +852,22 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
                                                          int sx_pitch) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char tlds[];
 #if defined(__HIP_DEVICE_COMPILE__)
-  static_assert(BITS == 4 || BITS == 8, "bits");
+  static_assert(BITS == 3 || BITS == 4 || BITS == 8, "bits");
   static_assert(TB >= 1 && TB <= 4, "token blocks of 16");
   static_assert(NWV == 4 || (NWV == 8 && TB % 2 == 0), "4 waves, or 8 with the token blocks split in two halves");
+  constexpr bool W3 = BITS == 3;  // 3-bit codes: weights in units of three stages (see below), same activation stages as 4 bits
   typedef QsMfma<16> M;
   typedef typename M::acc_t acc_t;
   constexpr int TH = NWV / 4;        // waves per 16-row tile, each with TBW of the token blocks
   constexpr int TBW = TB / TH;
   constexpr int NT = NWV * 64;
   constexpr int KG = 4, NH = 2, NDMA = 2 / TH;  // NDMA: this wave's loads of its row tile's weight stage
-  constexpr int QT_NS = qt_ring_stages(TB);
-  constexpr int CH = 128 / BITS, KS = 8 * CH, FR = CH / 8, SUB = KG * CH;
+  constexpr int QT_NS = W3 ? 3 : qt_ring_stages(TB);
+  constexpr int CH = W3 ? 32 : 128 / BITS, KS = 8 * CH, FR = CH / 8, SUB = KG * CH;
   constexpr int WSTAGE = 16 * 128;            // bytes of a weight stage of one row tile
+  // ring of a row tile's weights: QT_NS stages, or (3 bits) two units of three stages
+  constexpr int WSLOT = W3 ? 3 * WSTAGE : WSTAGE;
+  constexpr int WRING = W3 ? 2 * WSLOT : QT_NS * WSTAGE;
   constexpr int XROW = KS * 2;                // bytes of a token's activations in a stage
   constexpr int XSTAGE = TB * 16 * XROW;      // bytes of the shared activation stage
   constexpr int NXW = XSTAGE / 1024 / NWV;    // wave-wide activation loads per wave and stage
@@ -879,9 +885,13 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
   const int rb = i / 8 * BITS;
   const int G = i / g;
   // k-slice of this workgroup: stages j0 .. j0 + nst - 1 of the row (the whole row when the grid has one slice)
-  const int nst_row = rb / 128, slices = gridDim.y, slice = blockIdx.y;
-  const int j0 = slice * (nst_row / slices) + (slice < nst_row % slices ? slice : nst_row % slices);
-  const int nst = nst_row / slices + (slice < nst_row % slices ? 1 : 0);
+  // (3 bits: a stage here is an activation stage of KS k-values, and slices are whole units of four of them)
+  const int nst_row = W3 ? i / KS : rb / 128, slices = gridDim.y, slice = blockIdx.y;
+  const int nun = W3 ? (nst_row + 3) / 4 : nst_row, unit = W3 ? 4 : 1;
+  const int u0 = slice * (nun / slices) + (slice < nun % slices ? slice : nun % slices);
+  const int ucnt = nun / slices + (slice < nun % slices ? 1 : 0);
+  const int j0 = u0 * unit;
+  const int nst = ((u0 + ucnt) * unit < nst_row ? (u0 + ucnt) * unit : nst_row) - j0;
   const int n_pass = T - t0 < 16 * TB ? T - t0 : 16 * TB;  // tokens of this pass
   // the groups this slice meets: the tables in LDS hold these only, indexed from grp_first
   const int grp_first = j0 * KS / g, groups = ((j0 + nst) * KS - 1) / g - grp_first + 1;
@@ -889,8 +899,8 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
   const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
 
-  unsigned char* wring = tlds + rt * (QT_NS * WSTAGE);  // shared by the waves of the row tile
-  unsigned char* xring = tlds + 4 * QT_NS * WSTAGE;
+  unsigned char* wring = tlds + rt * WRING;  // shared by the waves of the row tile
+  unsigned char* xring = tlds + 4 * WRING;
   float* sx = reinterpret_cast<float*>(xring + QT_NS * XSTAGE);  // [TB * 16][sx_pitch] sums of X per token and group
   float* sl = sx + TB * 16 * sx_pitch;                           // [64][sx_pitch] scale of the workgroup's rows
 
@@ -914,14 +924,32 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
   }
   auto issue_dma = [&](int j) {  // stage j into ring slot j % QT_NS; past the end of k: zeros, no traffic
     const bool live = j < nst;
-    const unsigned kw = live ? (unsigned)(j0 + j) * 128u : gemm::PAST_END_OFFSET;
     const unsigned kx = live ? (unsigned)(j0 + j) * (unsigned)XROW : gemm::PAST_END_OFFSET;
-    unsigned char* wdst = wring + (j % QT_NS) * WSTAGE;
     unsigned char* xdst = xring + (j % QT_NS) * XSTAGE + wave * NXW * 1024;
+    if constexpr (!W3) {
+      const unsigned kw = live ? (unsigned)(j0 + j) * 128u : gemm::PAST_END_OFFSET;
+      unsigned char* wdst = wring + (j % QT_NS) * WSTAGE;
 #pragma unroll
-    for (int q = 0; q < NDMA; ++q)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcW, (lds_ptr_t)(wdst + (th * NDMA + q) * 1024), 16, voffW[q] + kw, 0,
-                                               0, 0);
+      for (int q = 0; q < NDMA; ++q)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcW, (lds_ptr_t)(wdst + (th * NDMA + q) * 1024), 16, voffW[q] + kw,
+                                                 0, 0, 0);
+    } else if (j >= 1) {
+      // Three stages of weights (1024 codes) serve four activation stages.  Every group of loads carries one stage's
+      // worth, so that the count per group - and with it the partial waits - stays what it is for 4 bits: group j
+      // brings part (j - 1) % 4 of unit (j - 1) / 4 + 1 (parts 0 .. 2 = its three stages, part 3 = loads that fetch
+      // nothing and write zeros over stage 0 of the unit before, which its last two activation stages no longer read
+      // and which the next group refills).  The unit is complete with group 4 c, one group before activation stage
+      // 4 c, its first user, is waited for; part 0 overwrites stage 0 of the unit two back while that unit's last
+      // activation stage reads its stage 2 only.
+      const int part = (j - 1) & 3, un = (j - 1) / 4 + 1;
+      const bool real = part < 3 && 4 * un < nst;
+      const unsigned kb = real ? (unsigned)(3 * (u0 + un) + part) * 128u : gemm::PAST_END_OFFSET;
+      unsigned char* wdst = wring + (part < 3 ? (un & 1) * WSLOT + part * WSTAGE : ((un - 1) & 1) * WSLOT);
+#pragma unroll
+      for (int q = 0; q < NDMA; ++q)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcW, (lds_ptr_t)(wdst + (th * NDMA + q) * 1024), 16, voffW[q] + kb,
+                                                 0, 0, 0);
+    }
 #pragma unroll
     for (int q = 0; q < NXW; ++q)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xdst + q * 1024), 16, voffX[q] + kx, 0, 0, 0);
@@ -977,13 +1005,27 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
 #pragma unroll
   for (int e = 0; e < 4; ++e) tx[e] = 0.f;
   auto consume = [&](int j) {
-    const unsigned char* wsrc = wring + (j % QT_NS) * WSTAGE + frag_row;
+    const unsigned char* wsrc = wring + (W3 ? ((j >> 2) & 1) * WSLOT : (j % QT_NS) * WSTAGE) + frag_row;
     const unsigned char* xsrc = xring + (j % QT_NS) * XSTAGE;
     const int st = j0 + (j < nst ? j : nst - 1);
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
       // every LDS read of the sub-step is issued before the first use: one exposed latency per sub-step
-      const u32x4 w = *reinterpret_cast<const u32x4*>(wsrc + (((KG * h + kg) ^ swz) << 4));
+      u32x4 w;
+      if constexpr (!W3) {
+        w = *reinterpret_cast<const u32x4*>(wsrc + (((KG * h + kg) ^ swz) << 4));
+      } else {
+        // sub-step 2 (j % 4) + h of the unit: this lane group's 32 codes are the 12 bytes from (4 sub-step + kg) 12 of
+        // the row's 384, three dwords of the swizzled stages (a piece may straddle two chunks or two stages)
+        const int piece = (4 * (2 * (j & 3) + h) + kg) * 12;
+#pragma unroll
+        for (int dw = 0; dw < 3; ++dw) {
+          const int byte = piece + 4 * dw;
+          const int b = byte & 127;
+          w[dw] = *reinterpret_cast<const uint32_t*>(wsrc + (byte >> 7) * WSTAGE + (((b >> 4) ^ swz) << 4) + (b & 15));
+        }
+        w[3] = 0u;
+      }
       bf16x8_t xf[FR][TBW], xo[FR];
 #pragma unroll
       for (int f = 0; f < FR; ++f) {
@@ -1032,6 +1074,14 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
 
   // The first QT_NS - 1 stages are requested, then the scale / zero rows of the 64 weight rows are fetched: the scales
   // go into their table, (zero - K0 scale) stays in registers until the rings are free.
+  if constexpr (W3) {  // the first unit of weights whole; the groups below bring the following ones part by part
+#pragma unroll
+    for (int part = 0; part < 3; ++part)
+#pragma unroll
+      for (int q = 0; q < NDMA; ++q)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcW, (lds_ptr_t)(wring + part * WSTAGE + (th * NDMA + q) * 1024), 16,
+                                                 voffW[q] + (unsigned)(3 * u0 + part) * 128u, 0, 0, 0);
+  }
 #pragma unroll
   for (int j = 0; j < QT_NS - 1; ++j) issue_dma(j);
   float4 bzrows[QT_ROWQ];
@@ -1141,15 +1191,19 @@ int qgemm_stream_rows(const LayerDims& d, int tokens_in_pass) {
 // 17 vs 23 us at 16 tokens, 23 vs 31 at 32, 33 vs 59 at 64; at [8192 x 8192] (128 tiles) 29 vs 29, 40 vs 30, 59 vs 59.
 // With fewer tiles, as many k-slices as fill the units, each at least four stages long.
 struct TilePlan {
-  int tb_max, slices, pitch;
+  int tb_max, slices;
+  int pitch[5];
   int64_t lds[5];
 };
 TilePlan qgemm_tile_plan(const LayerDims& d) {
-  TilePlan plan = {0, 1, 1, {0, 0, 0, 0, 0}};
-  if (qgemm_stream_rows(d, 16) != 16) return plan;
+  TilePlan plan = {0, 1, {1, 1, 1, 1, 1}, {0, 0, 0, 0, 0}};
+  // 3 bits: activation stages of 256 k-values, weights in units of three 128-byte stages = four activation stages
+  const bool w3 = d.bits == 3 && d.i % 256 == 0 && d.g % 128 == 0 && d.o * (d.i / 8 * 3) < (1ll << 31);
+  if (!w3 && qgemm_stream_rows(d, 16) != 16) return plan;
   const int64_t tiles = (d.o + 63) / 64, cus = device_compute_units();
   const int64_t rounds = (tiles + cus - 1) / cus;
-  const int64_t nst = d.i / 8 * d.bits / 128, ks = 8 * (128 / d.bits), G = d.i / d.g;
+  const int64_t ks = w3 ? 256 : 8 * (128 / d.bits), G = d.i / d.g;
+  const int64_t nst = d.i / ks;  // activation stages of a row
   if (8 * tiles < 5 * rounds * cus) {
     int64_t want = cus / tiles;
     if (want > nst / 4) want = nst / 4;
@@ -1157,18 +1211,25 @@ TilePlan qgemm_tile_plan(const LayerDims& d) {
     if (want < 2) return plan;
     plan.slices = (int)want;
   }
-  const int64_t stages = (nst + plan.slices - 1) / plan.slices;  // of the longest slice
+  // stages of the longest slice (3 bits: slices are whole units of four stages)
+  const int64_t stages = w3 ? 4 * (((nst + 3) / 4 + plan.slices - 1) / plan.slices) : (nst + plan.slices - 1) / plan.slices;
   int64_t groups = (stages * ks - 1) / d.g + 2;                   // groups it can meet, wherever it starts
   if (groups > G) groups = G;
-  plan.pitch = (int)(groups | 1);
   if (groups > 4 * (QT_ROWQ * 256 / 64)) return plan;  // table rows longer than a thread's pieces cover
   const int xrow = (int)ks * 2;
   for (int tb = 1; tb <= 4; ++tb) {
-    const int64_t rings = (int64_t)qt_ring_stages(tb) * (4 * 2048 + (int64_t)tb * 16 * xrow);
-    const int64_t lds = rings + (int64_t)(tb * 16 + 64) * plan.pitch * 4;
-    if (lds <= QD_LDS_MAX && 64 * (int64_t)plan.pitch * 4 <= rings) {  // (the ring depth is not monotonic in tb)
-      plan.lds[tb] = lds;
-      plan.tb_max = tb;
+    const int64_t rings = w3 ? 4 * (2 * 3 * 2048) + 3 * (int64_t)tb * 16 * xrow
+                             : (int64_t)qt_ring_stages(tb) * (4 * 2048 + (int64_t)tb * 16 * xrow);
+    // table rows of odd pitch (the 16 rows of a tile read one group together: no bank conflicts); where only the
+    // even pitch fits (3 bits, four token blocks, 32 groups: by 512 bytes) that read is serialised instead
+    for (int64_t pitch = groups | 1; pitch >= groups; --pitch) {
+      const int64_t lds = rings + (int64_t)(tb * 16 + 64) * pitch * 4;
+      if (lds <= QD_LDS_MAX && 64 * pitch * 4 <= rings) {  // (the ring depth is not monotonic in tb)
+        plan.lds[tb] = lds;
+        plan.pitch[tb] = (int)pitch;
+        plan.tb_max = tb;
+        break;
+      }
     }
   }
   return plan;
@@ -1257,7 +1318,6 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
       else tb_max = 0;
     }
     if (tb_max > 0) {
-      const int pitch = plan.pitch;
       dim3 tgrid((unsigned)((d.o + 63) / 64), (unsigned)slices);
       float* part = slices > 1 ? partial : nullptr;
       for (int t0 = 0; t0 < d.T; t0 += 16 * tb_max) {
@@ -1265,6 +1325,7 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
         int tb = (n + 15) / 16;
         while (plan.lds[tb] == 0) ++tb;  // a form that does not fit: the next larger one (tb_max fits) masks the tokens
         const size_t lds_bytes = (size_t)plan.lds[tb];
+        const int pitch = plan.pitch[tb];
 #define L4Q_QT(B, N, W)                                                                                               \
   do {                                                                                                               \
     if (lds_bytes > 64 * 1024)                                                                                       \
@@ -1273,7 +1334,9 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     hipLaunchKernelGGL((qgemm_tile_kernel<B, N, W>), tgrid, dim3(W * 64), lds_bytes, stream, X, packed, scale, zero, \
                        Y, part, (int)d.T, t0, (int)d.o, (int)d.i, d.g, pitch);                                       \
   } while (0)
-        if (d.bits == 4) {
+        if (d.bits == 3) {
+          if (tb == 1) L4Q_QT(3, 1, 4); else if (tb == 2) L4Q_QT(3, 2, 8); else if (tb == 3) L4Q_QT(3, 3, 4); else L4Q_QT(3, 4, 8);
+        } else if (d.bits == 4) {
           if (tb == 1) L4Q_QT(4, 1, 4); else if (tb == 2) L4Q_QT(4, 2, 8); else if (tb == 3) L4Q_QT(4, 3, 4); else L4Q_QT(4, 4, 8);
         } else {
           if (tb == 1) L4Q_QT(8, 1, 4); else if (tb == 2) L4Q_QT(8, 2, 8); else if (tb == 3) L4Q_QT(8, 3, 4); else L4Q_QT(8, 4, 8);

@@ -117,6 +117,11 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     # groups of two sub-steps, 16 tokens
     (1, 4096, 11008, 3, 128), (1, 11008, 4096, 3, 128), (12, 4096, 1000, 3, 128), (5, 1152, 264, 3, 128),
     (16, 2048, 72, 3, 256), (3, 128, 40, 3, 128), (4, 11008, 4096, 3, 128),
+    # 3 bits beyond the LDS-resident form: 64-row tiles with weights in units of three stages; both projections (the
+    # narrow one in k-slices of whole units, the last one short), one to three token blocks per pass, two passes, a
+    # row of less than one unit, ragged last row tile, groups of two sub-steps
+    (64, 4096, 11008, 3, 128), (40, 11008, 4096, 3, 128), (16, 4096, 10240, 3, 128), (33, 1024, 10312, 3, 256),
+    (24, 2048, 10304, 3, 128), (70, 768, 10248, 3, 128),
     # 70B-class projections: the widest layer at a small batch, the longest rows (too many groups for the tile kernel's
     # tables: the streaming forms take it)
     (4, 8192, 28672, 4, 128), (40, 28672, 8192, 4, 128),
