@@ -839,6 +839,10 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode3_kernel(const bf16_t* __r
 // after the loop every lane adds sum_g (zero - K0 scale)[row, g] * table[token, g] to its outputs, the first factor
 // fetched before the loop, held in registers and staged through the LDS the rings have left.  The scales of the 64
 // rows sit in LDS too (odd row pitch), so the stage loop issues DMA loads only and its partial waits are exact.
+// BITS = 3: the activation side is that of 4 bits (256 k-values per stage, 32 codes per lane group and sub-step); the
+// weights of a row tile are streamed in units of three 128-byte stages = 1024 codes = four activation stages, held in
+// a ring of two units, and read as 12-byte pieces (see the 3-bit decode kernel above).  The activation ring has three
+// stages for every token-block count.
 constexpr int qt_ring_stages(int token_blocks) { return token_blocks == 1 ? 8 : token_blocks == 2 ? 5 : token_blocks == 3 ? 4 : 3; }
 constexpr int QT_SLICES_MAX = 8;  // k-slices of a row tile at most
 constexpr int QT_ROWQ = 6;  // 16-byte pieces of a 64-row scale / zero block per thread: groups per row <= 96
