@@ -60,15 +60,15 @@ def test_quantized_forward_random_shapes(k, T, i, o, bits, g):
     test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
 
 
-def _random_tile_cases(count=12, seed=2402):
+def _random_tile_cases(count=18, seed=2402):
     """Seeded draw of problems for the 64-row tile kernel: wide layers (every compute unit gets a tile) and narrow
-    ones with long rows (k-slices through the workspace), 4 and 8 bits, groups of one to four sub-steps, 1 .. 100
+    ones with long rows (k-slices through the workspace), 3, 4 and 8 bits, groups of one to four sub-steps, 1 .. 100
     tokens (every count of token blocks, several passes), ragged last row tiles."""
     rng = np.random.default_rng(seed)
     cases = []
     for k in range(count):
-        bits = int(rng.choice([4, 8]))
-        unit = 256 if bits == 4 else 128            # codes of a 128-byte stage
+        bits = int(rng.choice([3, 4, 8]))
+        unit = 128 if bits == 8 else 256            # codes of an activation stage
         g = int(rng.choice([unit // 2, unit, 2 * unit]))
         if k % 2 == 0:                              # wide
             o = 10240 + 8 * int(rng.integers(0, 200))
