@@ -1318,7 +1318,8 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     const TilePlan plan = qgemm_tile_plan(d);
     int tb_max = plan.tb_max, slices = 1;
     if (plan.slices > 1) {  // too few row tiles for one k-slice each: split, if the caller gave room for the partial sums
-      if (d.T > 16 && partial != nullptr && partial_bytes >= qgemm_workspace_bytes(d)) slices = plan.slices;
+      // (at 16 tokens or fewer the k-split inside a workgroup wins where it exists: 4 and 8 bits)
+      if ((d.T > 16 || d.bits == 3) && partial != nullptr && partial_bytes >= qgemm_workspace_bytes(d)) slices = plan.slices;
       else tb_max = 0;
     }
     if (tb_max > 0) {

@@ -122,6 +122,8 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     # row of less than one unit, ragged last row tile, groups of two sub-steps
     (64, 4096, 11008, 3, 128), (40, 11008, 4096, 3, 128), (16, 4096, 10240, 3, 128), (33, 1024, 10312, 3, 256),
     (24, 2048, 10304, 3, 128), (70, 768, 10248, 3, 128),
+    # ... and few tokens on narrow layers whose activations do not fit the LDS-resident form: k-slices at any batch size
+    (16, 4096, 4096, 3, 128), (7, 11008, 4096, 3, 128),
     # 70B-class projections: the widest layer at a small batch, the longest rows (too many groups for the tile kernel's
     # tables: the streaming forms take it)
     (4, 8192, 28672, 4, 128), (40, 28672, 8192, 4, 128),
