@@ -228,6 +228,38 @@ def main() -> int:
         decode["T%d" % tok] = {"us_both_layers": us, "GB_per_s": nbytes / (us * 1e-6) / 1e9,
                                "frac_hbm_8TBs": nbytes / (us * 1e-6) / 8e12}
 
+    # the same leg at 3 bits (the paper's other code width) on the same two shapes: seeded random packed words, the
+    # layers' scale / zero
+    decode3 = {}
+    gen3 = torch.Generator(device="cuda:0")
+    gen3.manual_seed(3)
+    packs3 = [torch.randint(-2**31, 2**31 - 1, (l.spec.out_features, 3 * l.spec.in_features // 32), dtype=torch.int32,
+                            device="cuda:0", generator=gen3) for l in layers]
+    for tok in (1, 16, 64):
+        descs3 = [binding.make_desc(l.spec.with_(tokens=tok, bits=3)) for l in layers]
+        qfws3 = [torch.empty(max(256, binding.l4q_quantized_forward_workspace_bytes(d_)), dtype=torch.uint8,
+                             device="cuda:0") for d_ in descs3]
+        xs = [l.X[:tok] for l in layers]
+        ys = [l.Y[:tok] for l in layers]
+
+        def qstep3():
+            for d_, x_, p_, l_, y_, w_ in zip(descs3, xs, packs3, layers, ys, qfws3):
+                binding.l4q_quantized_forward(d_, x_, p_, l_.scale, l_.zero, y_, w_)
+        for _ in range(5):
+            qstep3()
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(50):
+            qstep3()
+        ev1.record()
+        torch.cuda.synchronize()
+        us = ev0.elapsed_time(ev1) * 1e3 / 50
+        nbytes = sum(p_.numel() * 4 + 2 * l_.scale.numel() * 4 + tok * (l_.spec.in_features + l_.spec.out_features) * 2
+                     for p_, l_ in zip(packs3, layers))
+        decode3["T%d" % tok] = {"us_both_layers": us, "GB_per_s": nbytes / (us * 1e-6) / 1e9,
+                                "frac_hbm_8TBs": nbytes / (us * 1e-6) / 8e12}
+    del packs3
+
     # the QAT-LoRA layer (Sec. 3.1) on the same workload: separate LoRA path, stored weight gradient
     qws_f, qws_b = zip(*[binding.l4q_qatlora_workspace_bytes(l.desc) for l in layers])
     qws = torch.empty(max(max(qws_f), max(qws_b)), dtype=torch.uint8, device="cuda:0")
@@ -295,6 +327,7 @@ def main() -> int:
                      "measured_mfma_only_tflops": mfma_only_tflops},
     }
     out["quantized_forward"] = decode
+    out["quantized_forward_3bit"] = decode3
     out["qat_lora_same_workload"] = {"ms_per_step": qat_ms, "workspace_bytes_fwd": max(qws_f),
                                      "workspace_bytes_bwd": max(qws_b),
                                      "l4q_speedup": qat_ms / ms_per_step}
