@@ -112,6 +112,11 @@ def test_quantized_forward_workspace_query_and_argument_checks(lib):
     assert n.value > 0 and n.value % (4096 * 4) == 0 and n.value <= 8 * 64 * 4096 * 4
     wide = binding.make_desc(LayerSpec("up", 64, 4096, 11008 * 2, 16, 32.0, 4, 128, DTYPE_BF16))
     assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(wide), ctypes.byref(n)) == 0 and n.value == 0
+    narrow3 = binding.make_desc(LayerSpec("down3", 64, 11008, 4096, 16, 32.0, 3, 128, DTYPE_BF16))
+    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow3), ctypes.byref(n)) == 0
+    assert n.value > 0 and n.value % (4096 * 4) == 0          # 3 bits: k-slices of whole three-stage units
+    narrow2 = binding.make_desc(LayerSpec("down2", 64, 11008, 4096, 16, 32.0, 2, 128, DTYPE_BF16))
+    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow2), ctypes.byref(n)) == 0 and n.value == 0
     f32 = binding.make_desc(LayerSpec("f", 64, 11008, 4096, 16, 32.0, 4, 128, DTYPE_F32))
     assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(f32), ctypes.byref(n)) == 0 and n.value == 0
     assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow), None) == -1
