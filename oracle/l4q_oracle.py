@@ -29,7 +29,10 @@ initialisation gives zero clipping error (Table 5, E_clip = 0.0 at init);
 mask == 1 reduces dA, dB to the plain LoRA gradients (Eq. lora_backward);
 closed forms of d(scale), d(zero), dA, dB against hand-rolled forward-mode
 dual numbers (App. A.1, A.2); finite differences on clipped groups and on X;
-brute-force triple loops on tiny shapes.
+brute-force triple loops on tiny shapes; the error sums E_quant / E_clip on a
+hand-worked row and through their split into a clipping and a rounding part;
+LSQ+ initialisation on a group whose mean and population deviation are written
+out; the binary32 initialisation re-evaluated with scalar binary32 operations.
 """
 from __future__ import annotations
 

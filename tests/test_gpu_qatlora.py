@@ -5,7 +5,7 @@ import pytest
 from paper_2402_04902_amd import inputs
 from paper_2402_04902_amd.inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
 
-from parity_util import TOL, rel_fro
+from parity_util import BOUNDS, compare_tensor
 
 pytestmark = pytest.mark.gpu
 
@@ -38,15 +38,13 @@ def _run(spec, seed, shrink=0.8, accumulate=False):
         binding.l4q_qatlora_backward(layer.desc, *args)
         times = 2
     torch.cuda.synchronize()
-    tol = TOL[spec.dtype]
     assert (~dec.mask).sum() > 0
     for name, got, ref in [("Y", layer.Y, Y), ("dX", layer.dX, gr.dX), ("dA", layer.dA, times * gr.dA),
                            ("dB", layer.dB, times * gr.dB), ("dscale", layer.dscale, times * gr.dscale),
                            ("dzero", layer.dzero, times * gr.dzero)]:
-        g = got.double().cpu().numpy()
-        assert np.isfinite(g).all(), name
-        err = rel_fro(g, ref)
-        assert err <= tol, (spec.name, name, err, tol)
+        # Y and dX are rounded twice in bfloat16 mode (main product, then the LoRA term): the L4Q bounds hold
+        fro_tol, elem_tol = BOUNDS[spec.dtype][name]
+        compare_tensor(spec.name + " " + name, got.double().cpu().numpy(), ref, fro_tol, elem_tol)
     return fb, bb
 
 

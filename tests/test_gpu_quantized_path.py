@@ -6,7 +6,7 @@ import pytest
 from paper_2402_04902_amd import inputs
 from paper_2402_04902_amd.inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
 
-from parity_util import host_qparams, rel_fro
+from parity_util import compare_tensor, host_qparams, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -155,8 +155,7 @@ def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
         if Yg is None:
             continue
         got = Yg.double().cpu().numpy()
-        assert np.isfinite(got).all()
-        assert rel_fro(got, ref) <= 2e-2
+        compare_tensor(spec.name, got, ref, 2e-2, 2e-2)   # whole tensor, rows, columns, elements
         # single forward path: the quantized-only output equals the training-time forward up to summation order
         assert rel_fro(got, layer.Y.double().cpu().numpy()) <= 5e-3
 

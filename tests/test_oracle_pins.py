@@ -423,3 +423,97 @@ def test_packed_forward_is_the_layer_forward():
     c = O.unpack_codes(packed, 4, 64)
     Wq = np.array([[c[q, j] * p["s"][q, j // 32] + p["b"][q, j // 32] for j in range(64)] for q in range(7)])
     assert np.allclose(Yq, p["X"] @ Wq.T, rtol=1e-13)
+
+
+# ---------------------------------------------------------------- error sums (App. B, initialisation table)
+
+def test_error_sums_on_a_hand_worked_row():
+    """Two groups of four weights with scales and biases that are exact in binary, so every figure below is exact:
+    group 0 (s = 1/4, b = 1/2, 3 bits: Q_N = -4, Q_P = 3): w = 1.25, 3.75 (clipped above), 0.5 (a rounding tie), -5
+    (clipped below); group 1 (s = 1/2, b = -1): w = 2.5 (tie), -4 (on the lower grid end, in range), 3.5 (clipped), 0."""
+    s = np.array([[0.25, 0.5]])
+    b = np.array([[0.5, -1.0]])
+    w = np.array([[1.25, 3.75, 0.5, -5.0, 2.5, -4.0, 3.5, 0.0]])
+    Wc = np.array([[0.8125, 1.4375, 0.625, -0.75, 0.25, -3.0, 0.75, -1.0]])      # b + s w, written out
+    assert np.array_equal(O.prequant(Wc, s, b, 4), w)
+    # |Wc - Wq| = s |w - round(clamp(w))|:  .25 (.25 + .75 + .5 + 1) + .5 (.5 + 0 + .5 + 0)
+    assert O.quantization_error(Wc, s, b, 3, 4) == 0.625 + 0.5
+    # |Wc - (clamp(w) s + b)| = s |w - clamp(w)|:  .25 (0 + .75 + 0 + 1) + .5 (0 + 0 + .5 + 0)
+    assert O.clipping_error(Wc, s, b, 3, 4) == 0.4375 + 0.25
+    # one more bit: nothing clips any more, the rounding error remains: .25 (.25 + .25 + .5 + 0) + .5 (.5 + 0 + .5 + 0)
+    assert O.clipping_error(Wc, s, b, 4, 4) == 0.0
+    assert O.quantization_error(Wc, s, b, 4, 4) == 0.25 + 0.5
+
+
+def test_quantization_error_splits_into_clipping_and_rounding_parts():
+    """|Wc - Wq| = s |w - c|: outside the grid c = clamp(w) and the whole difference is clipping; inside it
+    clamp(w) = w and the whole difference is rounding.  So E_quant = E_clip + sum s |clamp(w) - round(clamp(w))|,
+    evaluated here without any oracle function on the right-hand side."""
+    rng = np.random.default_rng(41)
+    o, i, g, bits = 24, 256, 32, 3
+    Wc = rng.standard_normal((o, i)) * 0.02
+    Wc[rng.random(Wc.shape) < 5e-3] *= 20
+    s = (Wc.reshape(o, i // g, g).max(axis=2) - Wc.reshape(o, i // g, g).min(axis=2)) / 7 * 0.7   # clips
+    b = rng.standard_normal(s.shape) * 0.01
+    se, be = np.repeat(s, g, axis=1), np.repeat(b, g, axis=1)
+    w = (Wc - be) / se
+    cl = np.clip(w, -4, 3)
+    rounding = float((se * np.abs(cl - np.round(cl))).sum())
+    clipping = float((se * np.abs(w - cl)).sum())
+    assert clipping > 0
+    assert math.isclose(O.clipping_error(Wc, s, b, bits, g), clipping, rel_tol=1e-11)
+    assert math.isclose(O.quantization_error(Wc, s, b, bits, g), clipping + rounding, rel_tol=1e-11)
+    # the two sums respond differently to a mistake: dropping the clamp from E_quant, or the rounding from it
+    assert not math.isclose(clipping + rounding, rounding, rel_tol=1e-3)
+
+
+# ---------------------------------------------------------------- LSQ+ initialisation (App. B, Eq. quant_inits)
+
+def test_lsqplus_init_uses_mean_and_population_deviation():
+    """Group {1, 2, 3, 6}: mean 3, squared deviations 4 + 1 + 0 + 9 = 14, population variance 14 / 4 = 3.5.
+    s = max(|3 - 3 sqrt(3.5)|, |3 + 3 sqrt(3.5)|) / 2^(n-1).  (The sample deviation sqrt(14 / 3) would give 1.185 at
+    4 bits instead of 1.0766, a factor 2 sigma 0.843, a denominator Q_P 1.2304.)"""
+    W = np.array([[1.0, 2.0, 3.0, 6.0, -1.0, -2.0, -3.0, -6.0]])
+    s, b = O.init_qparams(W, 4, 4, "lsq+")
+    assert s.shape == (1, 2) and not b.any()
+    assert abs(s[0, 0] - 1.076560760020114) < 1e-15            # (3 + 3 * 1.8708286933869707) / 8
+    assert abs(s[0, 1] - 1.076560760020114) < 1e-15            # mirrored group: |mu - 3 sigma| is the larger one
+    s3, _ = O.init_qparams(W, 3, 4, "lsq+")
+    assert abs(s3[0, 0] - 2.153121520040228) < 1e-15           # / 4 at 3 bits
+
+
+# ---------------------------------------------------------------- binary32 initialisation: operation order
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_f32_init_operation_order(bits):
+    """init_qparams(dtype=float32) is the bit-exact referee of the GPU initialisation kernel: re-evaluate every scheme
+    with scalar binary32 operations, one rounding per written operation, on a few groups."""
+    f = np.float32
+    rng = np.random.default_rng(43)
+    g = 8
+    W = (rng.standard_normal((3, 4 * g)) * 0.03).astype(f)
+    qn, qp = f(-(1 << (bits - 1))), f((1 << (bits - 1)) - 1)
+    got = {m: O.init_qparams(W, bits, g, m, dtype=f) for m in ("asymm", "symm", "l4q", "lsq+")}
+    for m in got:
+        assert got[m][0].dtype == f and got[m][1].dtype == f
+    for p in range(3):
+        for q in range(4):
+            grp = W[p, q * g:(q + 1) * g]
+            lo, hi = f(min(grp)), f(max(grp))
+            s = f(f(hi - lo) / f(qp - qn))
+            assert got["asymm"][0][p, q] == s
+            assert got["asymm"][1][p, q] == f(lo - f(s * qn))
+            assert got["symm"][0][p, q] == f(f(max(abs(lo), abs(hi))) / f(1 << (bits - 1)))
+            assert got["symm"][1][p, q] == 0
+            assert got["l4q"][0][p, q] == f(max(abs(f(lo / qn)), abs(f(hi / qp))))
+            assert got["l4q"][1][p, q] == 0
+            # LSQ+ sums in an unspecified binary32 order: within a few units of the last place of the float64 value
+            g64 = grp.astype(np.float64)
+            mu = g64.sum() / g
+            sd = math.sqrt(((g64 - mu) ** 2).sum() / g)
+            want = max(abs(mu - 3 * sd), abs(mu + 3 * sd)) / (1 << (bits - 1))
+            assert abs(float(got["lsq+"][0][p, q]) - want) <= 4e-7 * want
+    # the fused form lo - s qn in one rounding would differ somewhere on data like this; so would s = (hi - lo) * (1 / 15)
+    lo = W.reshape(3, 4, g).min(axis=2)
+    hi = W.reshape(3, 4, g).max(axis=2)
+    assert got["asymm"][0].tobytes() == ((hi - lo) / f(qp - qn)).astype(f).tobytes()
