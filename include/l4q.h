@@ -19,7 +19,8 @@
  *   scale, zero, dscale, dzero [o,G] : float always.  "zero" is the real-valued additive
  *       bias b of Eq. (quant): w = (W - b) / s, Wq = w~ s + b.  It is not an integer zero point.
  *   dA [r,i], dB [o,r] : float always.
- * Outputs are overwritten, never accumulated into.
+ * Outputs are overwritten; the one exception is L4Q_FLAG_ACCUMULATE_GRADS (below), under which l4q_backward and
+ * l4q_qatlora_backward add the four parameter gradients to what their arrays hold.
  *
  * Ownership.  The caller owns every buffer, workspace included.  The library allocates
  * nothing, keeps no pointer after a call returns and has no global state (the opt-in
@@ -32,7 +33,8 @@
  *
  * Errors.  Every entry point validates its arguments before it launches anything and
  * returns L4Q_OK (0) or a negative l4q_status.  Nothing is printed and nothing aborts.
- * scale <= 0, NaN or Inf inputs are not detected: results are then undefined.
+ * scale <= 0, NaN or Inf inputs are not detected: results are then undefined (a non-finite value in X or dY
+ * stays within the rows of Y / dX that the product's definition gives it).
  *
  * Arithmetic contract for the discrete part (codes and straight-through mask).  All kernels
  * evaluate, in IEEE binary32 with one rounding per written operation and no fused
@@ -88,7 +90,8 @@ enum {
 /* Shape rules: tokens, in_features, out_features, rank >= 1; group_size a power of two >= 4,
  * in_features % group_size == 0; 2 <= bits <= 8; rank <= 256.
  * BF16 additionally: group_size % 8 == 0 and out_features % 8 == 0 (16-byte rows), and each of
- * tokens*in_features, tokens*out_features, out_features*in_features below 2^29 - 2^20 elements. */
+ * tokens*in_features, tokens*out_features, out_features*ceil32(in_features), in_features*ceil32(out_features)
+ * below 2^29 - 2^20 elements (ceil32: rounded up to a multiple of 32). */
 typedef struct l4q_desc {
   int64_t tokens;       /* T */
   int64_t in_features;  /* i */

@@ -34,7 +34,10 @@ int check_desc(const l4q_desc* d, bool need_tokens) {
     // the matrix-core kernels address each operand with 32-bit byte offsets below 1 GiB
     const int64_t lim = (1ll << 29) - (1ll << 20);  // elements
     const int64_t t = need_tokens ? d->tokens : 1;
-    if (t * d->in_features >= lim || t * d->out_features >= lim || d->out_features * d->in_features >= lim)
+    // the workspace copies are padded: Wq is [o, i rounded up to 32], Wq^T is [i, o rounded up to 32]
+    const int64_t ipad = (d->in_features + 31) / 32 * 32, opad = (d->out_features + 31) / 32 * 32;
+    if (t * d->in_features >= lim || t * d->out_features >= lim || d->out_features * ipad >= lim ||
+        d->in_features * opad >= lim)
       return L4Q_ERR_SHAPE;
   }
   if (!(d->alpha == d->alpha)) return L4Q_ERR_SHAPE;
@@ -150,7 +153,7 @@ void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t
     }
   }
   if (timed) (void)hipEventRecord(e0, stream);
-  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, C, ldc, stream);
+  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, K_algorithmic, C, ldc, stream);
   if (timed) {
     (void)hipEventRecord(e1, stream);
     std::lock_guard<std::mutex> lk(g_prof.mu);

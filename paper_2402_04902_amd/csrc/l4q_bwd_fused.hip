@@ -81,7 +81,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
   // The d(Wq)/d(scale) factors of the tile (128 KiB of a weight-sized array streamed once from HBM) are needed right
-  // after the main loop.  Three quarters of them ride on the loads the loop issues for the three stages past the
+  // after the main loop.  They ride on the loads the loop issues for the four stages past the
   // end of K: tail stage q brings the factor rows of row block a = q (32 rows of the upper and of the lower wave
   // row) into the ring slot that stage would have used, 512 bytes per row, the 16-byte chunk c of row l at position
   // c ^ l so that the 32 rows a wave reads together spread over the banks.  Rows past the matrix lie beyond the
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
   }
   gemm::mainloop<T, true, true, FTail>(p.dY, p.o, p.X, p.i, p.o, p.i, p.K, m0, n0, lds, acc, ftail);
   // the operand stages are consumed (mainloop ends with a barrier after the last fragment read); slots
-  // (nk + q) % 4, q = 0 .. 2, hold the factor rows
+  // (nk + q) % NS, q = 0 .. 3, hold the factor rows
 
   // ---- fragments of the LoRA factor A for the dB product: lane = rank index, 8 k-slots = the same
   //      column pattern the accumulator registers 8h .. 8h+7 of a lane group have
@@ -123,9 +123,8 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
   }
 
   // The factors this lane needs: 64 pieces of 4 consecutive columns, one per (row block, column tile, register
-  // group).  Row block 3 comes from memory (requested first; it is used last); blocks 0 .. 2 are read out of the
-  // ring slots, after which the LDS is free for the epilogue.  Rows and columns past the matrix: the memory loads are
-  // clamped to a valid address and the LDS pieces are zeros; their accumulators are exactly zero either way.
+  // group), all four row blocks read out of the ring slots (nk + a) % NS, after which the LDS is free for the
+  // epilogue.  Rows and columns past the matrix: the LDS pieces are zeros, and so are their accumulators.
   typedef _Float16 h4 __attribute__((ext_vector_type(4)));
   h4 fpre[T::TM][T::TN][4];
   {

@@ -4,8 +4,8 @@
 //   dX        dX [T,i] = dY [T,o] . WqT [i,opad]^T      both operands K-contiguous
 //   dWq       dWq[o,i] = dY [T,o]^T . X [T,i]           both operands K-major (unfused backward only;
 //                                                       the fused form lives in l4q_bwd_fused.hip)
-// The workspace operand (Wq, WqT) is zero-padded along k to the 32-wide k-step; the caller's operand
-// may then read past its row end, which multiplies with those zeros.
+// The workspace operand (Wq, WqT) is zero-padded along k to the 32-wide k-step; the caller's operand is
+// not: its 16-byte chunks past the row end are masked (read as zeros) in the last stage.
 #include "l4q_device.h"
 #include "l4q_gemm_core.h"
 #include "l4q_kernels.h"
@@ -18,10 +18,10 @@ namespace {
 // Direct-to-LDS ring pipeline (l4q_gemm_core.h) + plain store epilogue.  Operands below 1 GiB.
 // ---------------------------------------------------------------------------------------------
 // One macro tile: main loop, then the store epilogue.
-template <class T, bool OUT_BF16, bool A_KM, bool B_KM>
+template <class T, bool OUT_BF16, bool A_KM, bool B_KM, bool MASK_A_K>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                                          int64_t ldb, int M, int N, int K, void* __restrict__ Cout, int64_t ldc,
-                                          int m0, int n0, unsigned char* lds) {
+                                          int64_t ldb, int M, int N, int K, int K_a, void* __restrict__ Cout,
+                                          int64_t ldc, int m0, int n0, unsigned char* lds) {
   gemm::Accum<T> acc;
 #pragma unroll
   for (int a = 0; a < T::TM; ++a)
@@ -29,7 +29,8 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
     for (int b = 0; b < T::TN; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
-  gemm::mainloop<T, A_KM, B_KM>(A, lda, B, ldb, M, N, K, m0, n0, lds, acc);
+  gemm::mainloop<T, A_KM, B_KM, gemm::NoTailLoads, MASK_A_K>(A, lda, B, ldb, M, N, K, m0, n0, lds, acc,
+                                                            gemm::NoTailLoads(), K_a);
   // bf16 output through LDS (free after the main loop): a lane holds 4 consecutive columns of 64 different
   // rows, which as direct stores are 16-byte pieces of 32 cache lines per instruction.  Each wave instead
   // parks its 128 x 128 block in its own LDS region (rows padded to 272 bytes) and writes it out as 16 bytes
@@ -84,15 +85,16 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
   }
 }
 
-template <class T, bool OUT_BF16, bool A_KM = false, bool B_KM = false>
+template <class T, bool OUT_BF16, bool A_KM = false, bool B_KM = false, bool MASK_A_K = false>
 __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                    const bf16_t* __restrict__ B, int64_t ldb, int M,
-                                                                   int N, int K, void* __restrict__ Cout,
+                                                                   int N, int K, int K_a, void* __restrict__ Cout,
                                                                    int64_t ldc, int tiles_m, int tiles_n) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
   int tile_m, tile_n;
   gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-  gemm_tile<T, OUT_BF16, A_KM, B_KM>(A, lda, B, ldb, M, N, K, Cout, ldc, tile_m * T::BM, tile_n * T::BN, lds);
+  gemm_tile<T, OUT_BF16, A_KM, B_KM, MASK_A_K>(A, lda, B, ldb, M, N, K, K_a, Cout, ldc, tile_m * T::BM,
+                                               tile_n * T::BN, lds);
 }
 
 // Matrix-core-only loop with the GEMM's register shape (4 x 4 accumulator tiles, 8 fragments per wave) and
@@ -153,13 +155,21 @@ int device_compute_units() {
 }
 
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
-                         int64_t K, bf16_t* C, int64_t ldc, hipStream_t stream) {
+                         int64_t K, int64_t K_a, bf16_t* C, int64_t ldc, hipStream_t stream) {
   // K-contiguous operands: stages loaded in cache-line pairs; 8 waves (2 x 4, two per SIMD, 128 x 64 each): a second
   // wave on the SIMD keeps the matrix pipe busy while the first waits for a barrier or for operands (1.5 % over 2 x 2)
   typedef gemm::Tile<256, 256, 32, 5, true, 4> F;
   const int tiles_m = (int)((M + F::BM - 1) / F::BM), tiles_n = (int)((N + F::BN - 1) / F::BN);
-  hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false>), dim3((unsigned)(tiles_m * tiles_n)),
-                     dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (void*)C, ldc, tiles_m, tiles_n);
+  // rows of A end at K_a: where that is short of the k-step, the chunks past it are masked (a second instance, so
+  // that the usual shapes do not pay for the selection)
+  if (K_a == K)
+    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false, false>), dim3((unsigned)(tiles_m * tiles_n)),
+                       dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (int)K_a, (void*)C, ldc, tiles_m,
+                       tiles_n);
+  else
+    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false, true>), dim3((unsigned)(tiles_m * tiles_n)),
+                       dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (int)K_a, (void*)C, ldc, tiles_m,
+                       tiles_n);
 }
 
 void launch_gemm_bf16_kmajor_f32(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
@@ -167,7 +177,8 @@ void launch_gemm_bf16_kmajor_f32(const bf16_t* A, int64_t lda, const bf16_t* B, 
   typedef gemm::Tile<256, 256, 32, 4> F;
   const int tiles_m = (int)((M + F::BM - 1) / F::BM), tiles_n = (int)((N + F::BN - 1) / F::BN);
   hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, false, true, true>), dim3((unsigned)(tiles_m * tiles_n)),
-                     dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (void*)C, ldc, tiles_m, tiles_n);
+                     dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (int)K, (void*)C, ldc, tiles_m,
+                     tiles_n);
 }
 
 }  // namespace l4q

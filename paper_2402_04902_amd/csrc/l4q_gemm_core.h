@@ -1,7 +1,8 @@
 // Main loop of the bf16 MFMA GEMM for gfx950:  acc[M,N] += A[M,K] . B[N,K]^T  (binary32 accumulate).
 //
-// One workgroup = 4 wavefronts (2 x 2) computes a BM x BN macro tile; each wavefront owns a
-// (BM/2) x (BN/2) block of 32 x 32 accumulator tiles fed by v_mfma_f32_32x32x16_bf16.
+// One workgroup = 2 x WAVES_N wavefronts (2 x 2 for the weight gradient, 2 x 4 = two per SIMD for the forward and
+// dX products) computes a BM x BN macro tile; each wavefront owns a (BM/2) x (BN/WAVES_N) block of 32 x 32
+// accumulator tiles fed by v_mfma_f32_32x32x16_bf16.
 //
 // Operand path.  Both operands are K-contiguous in memory.  Tiles of BK k-values travel
 // HBM/L2 -> LDS with buffer_load_dwordx4 ... lds (no VGPR staging): one wave instruction fills
@@ -138,10 +139,14 @@ struct TailLoads {
   unsigned stage_bytes;             // added once per tail stage
 };
 
-template <class T, bool A_KM = false, bool B_KM = false, class Tail = NoTailLoads>
+// MASK_A_K (paired loop only): operand A is valid for k < K_a only (K_a a multiple of 8, K - 32 < K_a <= K) and what
+// follows a row in memory is the next row, not padding: the 16-byte chunks of the last stage that start at k >= K_a
+// get an out-of-range offset and read as zero, so that a NaN or Inf in row m + 1 cannot reach row m of the product
+// through 0 x Inf.
+template <class T, bool A_KM = false, bool B_KM = false, class Tail = NoTailLoads, bool MASK_A_K = false>
 __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
                                          int64_t ldb, int M, int N, int K, int m0, int n0, unsigned char* lds,
-                                         Accum<T>& acc, const Tail& tail = Tail()) {
+                                         Accum<T>& acc, const Tail& tail = Tail(), int K_a = 0) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the declaration
   static_assert((!A_KM || T::BM == 256) && (!B_KM || T::BN == 256), "K-major staging is written for 256-wide tiles");
   typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -288,6 +293,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
   constexpr int EXTRA = NDA + NDB + LPK > NMF ? NDA + NDB + LPK - NMF : 0;  // reads that share a matrix op
   static_assert(2 * EXTRA <= NDA + NDB, "too many LDS reads per matrix op");
   static_assert(!Tail::ENABLED || !T::PAIR, "tail loads are wired into the non-paired loop");
+  static_assert(!MASK_A_K || T::PAIR, "k-masking of operand A is wired into the paired loop");
   if constexpr (T::PAIR) {
     // Paired loading for K-contiguous operands.  A stage takes 64 bytes of every operand row, half a 128-byte
     // cache line; when the second half is requested a stage later the line has already left the 32 KiB vector
@@ -299,6 +305,15 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
     // Each pair is therefore issued two and a half stages before its first use.  An odd stage count is rounded up:
     // the extra stage is loaded as zeros.
     static_assert(!T::PAIR || (!A_KM && !B_KM && T::KK == 2), "paired loading is for K-contiguous operands");
+    unsigned voffA_last[MASK_A_K ? T::A_INSTR : 1];  // offsets of operand A in the last stage: chunks past K_a masked
+    if constexpr (MASK_A_K) {
+#pragma unroll
+      for (int c = 0; c < T::A_INSTR; ++c) {
+        const int row = (wave * T::A_INSTR + c) * T::RPI + lane / T::CPR;
+        const int ch = (lane % T::CPR) ^ ((row / T::RW) % T::CPR);
+        voffA_last[c] = (nk - 1) * T::BK + ch * 8 < K_a ? voffA[c] : OOB_OFFSET;
+      }
+    }
     auto issue_pair = [&](int stage0, int slot0, int slot1, int part) {
       const unsigned k0 = stage0 < nk ? (unsigned)stage0 * stage_bytes_a : PAST_END_OFFSET;
       const unsigned k1 = stage0 + 1 < nk ? (unsigned)(stage0 + 1) * stage_bytes_a : PAST_END_OFFSET;
@@ -308,8 +323,13 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
 #pragma unroll
         for (int c = 0; c < T::A_INSTR; ++c) {
           const int o = (wave * T::A_INSTR + c) * 1024;
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base0 + o), 16, voffA[c] + k0, 0, 0, 0);
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base1 + o), 16, voffA[c] + k1, 0, 0, 0);
+          unsigned v0 = voffA[c], v1 = voffA[c];
+          if constexpr (MASK_A_K) {
+            v0 = stage0 == nk - 1 ? voffA_last[c] : v0;
+            v1 = stage0 + 1 == nk - 1 ? voffA_last[c] : v1;
+          }
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base0 + o), 16, v0 + k0, 0, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lds_ptr_t)(base1 + o), 16, v1 + k1, 0, 0, 0);
         }
       } else {
 #pragma unroll

@@ -4,9 +4,11 @@
 // Packed layout: the unsigned field u = w~ - Q_N of column j occupies bits [n j, n j + n) of the
 // row's little-endian bit string; rows are n * i / 32 words.
 //
-// Two kernels compute the product.  qgemm_stream_kernel (further down) covers 4- and 8-bit layers whose packed
-// rows are whole cache lines, up to 32 tokens per pass; qgemm_kernel covers every other layout and up to 64
-// tokens per pass:
+// Five kernels compute the product, chosen by launch_qgemm from the code width, the token count and the layer's
+// shape (each is described where it is defined): qgemm_decode_kernel (4 / 8 bits, activations resident in LDS),
+// qgemm_decode3_kernel (3 bits, likewise), qgemm_stream_kernel (4 / 8 bits, up to 32 tokens per pass),
+// qgemm_tile_kernel (3 / 4 / 8 bits, 64-row tiles, up to 64 tokens per pass, optionally in k-slices whose partial
+// sums qgemm_slices_sum_kernel adds), and qgemm_kernel, which covers every other layout:
 // qgemm_kernel: one workgroup = 32 weight rows, 8 waves splitting k in interleaved 64-wide chunks.
 // A lane owns one weight row: per chunk it loads the n words holding its 32 consecutive codes
 // (lane group 0: k 0..31 of the chunk, group 1: k 32..63), turns them into bf16 operands (integer codes with the

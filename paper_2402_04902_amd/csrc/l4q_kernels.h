@@ -54,11 +54,11 @@ void launch_quant_errors(const LayerDims& d, const T* W0, const T* A, const T* B
 int device_compute_units();
 
 // ---- bf16 MFMA GEMM  C[M,N] = A[M,K] . B[N,K]^T, fp32 accumulate, bf16 output ----
-// A, B row-major and K-contiguous with leading dimensions lda, ldb (elements, multiples of 8).  B must hold
-// zeros for k in [K_true, K) where K is rounded up to 32; A may be read past its row end there.
-// Every operand below 1 GiB, N % 4 == 0, ldc % 4 == 0.
+// A, B row-major and K-contiguous with leading dimensions lda, ldb (elements, multiples of 8).  K is rounded up to
+// 32; B must hold zeros for k in [K_a, K); rows of A end at K_a (a multiple of 8, K - 32 < K_a <= K) and are not
+// read past it.  Every operand below 1 GiB, N % 4 == 0, ldc % 4 == 0.
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
-                         int64_t K, bf16_t* C, int64_t ldc, hipStream_t stream);
+                         int64_t K, int64_t K_a, bf16_t* C, int64_t ldc, hipStream_t stream);
 
 // ---- matrix-core-only probe: `workgroups` x 4 waves x `iterations` x 16 MFMA 32x32x16 on fragments taken from the
 // first 64 KiB of `data`; sink [workgroups * 256] floats.  Returns the FLOPs the launch performs. ----

@@ -307,3 +307,32 @@ def test_bf16_largest_operands(name, T, i, o):
         inputs.LayerSpec(name, T, i + 32, o, 2, 4.0, 4, 32, DTYPE_BF16)
     with pytest.raises(RuntimeError):
         binding.l4q_workspace_bytes(binding.make_desc(big))   # one step further is rejected, not mis-addressed
+
+
+# ------------------------------------------------------------------ a non-finite row stays in its own row
+
+def test_bf16_non_finite_row_does_not_reach_its_neighbours():
+    """In-features 264 and out-features 136 are multiples of 8 but not of the 32-wide k-step of the matrix-core
+    kernels.  An Inf planted in one row of X (or dY) must poison that row of Y (dX) only: all other rows stay bit for
+    bit what they were."""
+    import torch
+    from paper_2402_04902_amd import binding
+    spec = LayerSpec("bf16_k_tail", 70, 264, 136, 4, 8.0, 4, 8, DTYPE_BF16)
+    print("case", spec.name, flush=True)
+    arrs = inputs.make_layer_inputs(spec, seed=9)
+    s, b = host_qparams(spec, arrs, "asymm", 0.8)
+    layer = binding.upload(spec, arrs, s, b)
+    layer.forward()
+    layer.backward()
+    torch.cuda.synchronize()
+    Y0, dX0 = layer.Y.clone(), layer.dX.clone()
+    layer.X[5, :] = float("inf")
+    layer.dY[9, :] = float("inf")
+    layer.forward()
+    layer.backward()
+    torch.cuda.synchronize()
+    keep_y = [t for t in range(spec.tokens) if t != 5]
+    keep_dx = [t for t in range(spec.tokens) if t != 9]
+    assert torch.equal(layer.Y[keep_y].view(torch.int16), Y0[keep_y].view(torch.int16))
+    assert torch.equal(layer.dX[keep_dx].view(torch.int16), dX0[keep_dx].view(torch.int16))
+    assert not torch.isfinite(layer.Y[5].float()).all() and not torch.isfinite(layer.dX[9].float()).all()
