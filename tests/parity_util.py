@@ -52,9 +52,10 @@ def compare_tensor(name, got, ref, fro_tol, elem_tol):
 
     fro:   ||got - ref||_F <= fro_tol ||ref||_F
     elem:  |got - ref| <= elem_tol (|ref| + rms(ref))                        for every element
-    rows:  ||got[r] - ref[r]|| <= fro_tol (||ref[r]|| + rms(ref) sqrt(ncols)) for every row (and likewise columns):
+    rows:  ||got[r] - ref[r]|| <= elem_tol (||ref[r]|| + rms(ref) sqrt(ncols)) for every row (and likewise columns):
            a row that is wrong as a whole (dropped, shifted, stale) has an error of the size of its own norm and
-           fails this whatever the size of the tensor, where the whole-tensor norm would dilute it.
+           fails this whatever the size of the tensor, where the whole-tensor norm would dilute it.  (The element
+           tolerance, because a row or column may be as short as one element: rank 1, one group per row.)
     Returns the four measured figures (each relative to its bound's right-hand side without the tolerance)."""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
@@ -70,8 +71,8 @@ def compare_tensor(name, got, ref, fro_tol, elem_tol):
                  (np.linalg.norm(ref, axis=0) + rms * np.sqrt(ref.shape[0]) + 1e-300)).max())
     assert fro <= fro_tol, (name, "frobenius", fro, fro_tol)
     assert elem <= elem_tol, (name, "element", elem, elem_tol)
-    assert row <= fro_tol, (name, "row", row, fro_tol)
-    assert col <= fro_tol, (name, "column", col, fro_tol)
+    assert row <= elem_tol, (name, "row", row, elem_tol)
+    assert col <= elem_tol, (name, "column", col, elem_tol)
     return {"fro": fro, "elem": elem, "row": row, "col": col}
 
 

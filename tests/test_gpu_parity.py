@@ -294,17 +294,17 @@ def test_backward_accumulates_parameter_gradients(dtype, flags):
 
 @pytest.mark.parametrize("name,T,i,o", [
     ("max_tokens_x_out", 32768, 64, 16344),    # Y and dY just below the 2^29 - 2^20 element limit (1 GiB of bf16)
-    ("max_out_x_in", 8, 32768, 16344),         # W0, Wq, the fp16 factor just below it
+    ("max_out_x_in", 8, 32768, 16320),         # W0, Wq, Wq^T (rows padded to a multiple of 32), the fp16 factor just below it
 ])
 def test_bf16_largest_operands(name, T, i, o):
     """Byte offsets of the matrix-core kernels are 32-bit: operands of the largest accepted size must still be
     addressed correctly at their far end.  Whole-tensor comparison against the oracle."""
-    assert T * o < (1 << 29) - (1 << 20) and o * i < (1 << 29) - (1 << 20)
+    assert T * o < (1 << 29) - (1 << 20) and (o + 31) // 32 * 32 * i < (1 << 29) - (1 << 20)
     spec = LayerSpec(name, T, i, o, 2, 4.0, 4, 32, DTYPE_BF16, outliers=False)
     run_case(spec, seed=5, shrink=0.8, discrete=False)
     from paper_2402_04902_amd import binding
     big = inputs.LayerSpec(name, T, i, o + 8, 2, 4.0, 4, 32, DTYPE_BF16) if name == "max_tokens_x_out" else \
-        inputs.LayerSpec(name, T, i + 32, o, 2, 4.0, 4, 32, DTYPE_BF16)
+        inputs.LayerSpec(name, T, i, o + 32, 2, 4.0, 4, 32, DTYPE_BF16)
     with pytest.raises(RuntimeError):
         binding.l4q_workspace_bytes(binding.make_desc(big))   # one step further is rejected, not mis-addressed
 
