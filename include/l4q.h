@@ -24,7 +24,7 @@
  *
  * Ownership.  The caller owns every buffer, workspace included.  The library allocates
  * nothing, keeps no pointer after a call returns and has no global state (the opt-in
- * benchmark switch l4q_profile_gemm aside), so calls on
+ * benchmark switch l4q_profile_gemm and the fixed scratch array of l4q_quant_errors_static aside), so calls on
  * different streams may run concurrently as long as their output and workspace buffers are
  * distinct.
  *
@@ -67,7 +67,8 @@ typedef enum l4q_status {
   L4Q_ERR_ALIGN = -5,     /* a pointer is not 16-byte aligned */
   L4Q_ERR_WORKSPACE = -6, /* workspace NULL or smaller than l4q_workspace_bytes reports */
   L4Q_ERR_LAUNCH = -7,    /* a kernel launch failed (hipGetLastError was not hipSuccess) */
-  L4Q_ERR_METHOD = -8     /* unknown initialisation method */
+  L4Q_ERR_METHOD = -8,    /* unknown initialisation method */
+  L4Q_ERR_TOO_LARGE = -9  /* l4q_quant_errors_static: the problem needs more than L4Q_STATIC_SCRATCH_BYTES */
 } l4q_status;
 
 enum { L4Q_DTYPE_F32 = 0, L4Q_DTYPE_BF16 = 1 };
@@ -206,6 +207,17 @@ int l4q_init_qparams(const l4q_desc* desc, const void* W0, const void* A, const 
 int l4q_quant_errors(const l4q_desc* desc, const void* W0, const void* A, const void* B,
                      const float* scale, const float* zero, float* errors,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* l4q_quant_errors for callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same kernels, with the partial sums in a device array that is
+ * part of the library image (L4Q_STATIC_SCRATCH_BYTES per GPU, resident until the process ends).  Calls no
+ * allocator.  Arguments, result and errors as l4q_quant_errors, without the workspace; additionally
+ * L4Q_ERR_TOO_LARGE when out_features * ceil(in_features / 256) * 8 exceeds L4Q_STATIC_SCRATCH_BYTES (nothing is
+ * launched then).  All calls on one GPU share the one array: calls that may overlap there (different streams,
+ * concurrent graph launches) race and must be ordered by the caller.  Nothing of an earlier call's content is read. */
+#define L4Q_STATIC_SCRATCH_BYTES (8u << 20)
+int l4q_quant_errors_static(const l4q_desc* desc, const void* W0, const void* A, const void* B,
+                            const float* scale, const float* zero, float* errors, void* hip_stream);
 
 /* One AdamW step (decoupled weight decay; App. C: weight decay 0.01) on the layer's four trainable tensors.
  *   m <- beta1 m + (1 - beta1) g;   v <- beta2 v + (1 - beta2) g^2

@@ -20,7 +20,7 @@ INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
             "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward", "l4q_quantized_forward_workspace_bytes", "l4q_adamw_step", "l4q_cosine_lr",
-            "l4q_qatlora_workspace_bytes", "l4q_qatlora_forward", "l4q_qatlora_backward"]
+            "l4q_qatlora_workspace_bytes", "l4q_qatlora_forward", "l4q_qatlora_backward", "l4q_quant_errors_static"]
 
 
 class L4QDesc(ctypes.Structure):
@@ -79,6 +79,8 @@ def load_library() -> ctypes.CDLL:
                                           ctypes.POINTER(ctypes.c_double)]
     lib.l4q_quant_errors.restype = ctypes.c_int
     lib.l4q_quant_errors.argtypes = [dp, vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+    lib.l4q_quant_errors_static.restype = ctypes.c_int
+    lib.l4q_quant_errors_static.argtypes = [dp, vp, vp, vp, fp, fp, fp, vp]
     lib.l4q_export_packed.restype = ctypes.c_int
     lib.l4q_export_packed.argtypes = [dp, vp, vp, vp, fp, fp, vp, vp, ctypes.c_size_t, vp]
     lib.l4q_quantized_forward.restype = ctypes.c_int
@@ -177,6 +179,14 @@ def l4q_quant_errors(desc: L4QDesc, W0, A, B, scale, zero, errors, workspace) ->
                                            _ptr(errors), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream()),
            "l4q_quant_errors")
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def l4q_quant_errors_static(desc: L4QDesc, W0, A, B, scale, zero, errors) -> None:
+    _check(load_library().l4q_quant_errors_static(ctypes.byref(desc), _ptr(W0), _ptr(A), _ptr(B), _ptr(scale),
+                                                  _ptr(zero), _ptr(errors), _stream()), "l4q_quant_errors_static")
 
 
 def l4q_export_packed(desc: L4QDesc, W0, A, B, scale, zero, packed, workspace) -> None:

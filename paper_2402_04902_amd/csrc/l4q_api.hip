@@ -132,6 +132,33 @@ BwdWs carve_bwd(const l4q_desc* d, void* ws) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? L4Q_OK : L4Q_ERR_LAUNCH; }
 
+// ---- device-resident scratch of l4q_quant_errors_static ----
+// One array per GPU the library runs on, held until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: the device address is asked for once per device and kept in g_static_scratch.
+constexpr size_t kStaticScratchBytes = L4Q_STATIC_SCRATCH_BYTES;
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  std::mutex mu;
+  void* ptr[kMaxDevices] = {};
+} g_static_scratch;
+
+// Device address of `scratch` on the current device (null on failure).
+void* static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lk(g_static_scratch.mu);
+  if (!g_static_scratch.ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_static_scratch.ptr[dev] = p;
+  }
+  return g_static_scratch.ptr[dev];
+}
+
 // ---- opt-in timing of the GEMM launches (l4q_profile_gemm) ----
 struct GemmProfile {
   std::mutex mu;
@@ -244,6 +271,7 @@ const char* l4q_status_string(int status) {
     case L4Q_ERR_WORKSPACE: return "workspace missing or too small";
     case L4Q_ERR_LAUNCH: return "kernel launch failed";
     case L4Q_ERR_METHOD: return "unknown initialisation method";
+    case L4Q_ERR_TOO_LARGE: return "problem needs more scratch than this entry point's fixed device array holds";
     default: return "unknown status";
   }
 }
@@ -575,6 +603,31 @@ int l4q_quant_errors(const l4q_desc* desc, const void* W0, const void* A, const 
   else
     l4q::launch_quant_errors<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero,
                                     (float*)workspace, errors, stream);
+  return launch_status();
+}
+
+int l4q_quant_errors_static(const l4q_desc* desc, const void* W0, const void* A, const void* B, const float* scale,
+                            const float* zero, float* errors, void* hip_stream) {
+  const int st = check_desc(desc, false);
+  if (st != L4Q_OK) return st;
+  if (!W0 || !A || !B || !scale || !zero || !errors) return L4Q_ERR_NULL;
+  const void* ptrs[] = {W0, A, B, scale, zero, errors};
+  for (const void* p : ptrs)
+    if (!aligned(p, 16)) return L4Q_ERR_ALIGN;
+  const size_t need = (size_t)desc->out_features * (size_t)((desc->in_features + 255) / 256) * 2 * sizeof(float);
+  if (need > kStaticScratchBytes) return L4Q_ERR_TOO_LARGE;
+  float* partial = static_cast<float*>(static_scratch_ptr());
+  if (!partial) return L4Q_ERR_LAUNCH;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const LayerDims d = dims_of(desc);
+  (void)hipGetLastError();
+  // every pair the sum kernel reads is written by the error kernel of this same call: nothing needs clearing
+  if (desc->dtype == L4Q_DTYPE_BF16)
+    l4q::launch_quant_errors<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, partial,
+                                     errors, stream);
+  else
+    l4q::launch_quant_errors<float>(d, (const float*)W0, (const float*)A, (const float*)B, scale, zero, partial,
+                                    errors, stream);
   return launch_status();
 }
 
