@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 # HBM-side bytes per GEMM launch (mean over the 4 plain + 2 fused launches of a step) from the
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/l4q_layer__llama7b_mlp_T4096.md
 GEMM_TRAFFIC_BYTES_PER_LAUNCH = (2 * (588e6 + 90e6) + 2 * (546e6 + 34e6) + 2 * (718e6 + 39e6)) / 6
@@ -130,6 +131,8 @@ def main() -> int:
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short timings of the other published configurations (C2, C4, C5)")
     ap.add_argument("--tokens", type=int, default=4096, help=argparse.SUPPRESS)
+    ap.add_argument("--profile-steps", type=int, default=10,
+                    help="steps of the separate loop that times the GEMM and merge+quantize launches one by one")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -171,7 +174,7 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    binding.l4q_profile_gemm(True)
+    # the headline: exactly `steps` steps, nothing else enqueued or recorded inside the library
     step_events = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     step_events[0].record()
@@ -181,7 +184,21 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     per_step = sorted(step_events[k].elapsed_time(step_events[k + 1]) for k in range(args.steps))
-    gemm_ms, gemm_launches, gemm_flops = binding.l4q_profile_gemm_read()
+
+    # per-kernel attribution in a loop of its own: the library brackets its GEMM and merge + quantize launches with
+    # HIP events on the stream they are launched on
+    binding.l4q_profile_gemm(True)
+    for _ in range(args.profile_steps):
+        step()
+    torch.cuda.synchronize()
+    gemm_ms, gemm_launches, gemm_flops = binding.l4q_profile_read(binding.PROFILE_GEMM)
+    mq = {}
+    for name, kind in (("forward", binding.PROFILE_MERGE_FORWARD), ("backward", binding.PROFILE_MERGE_BACKWARD)):
+        ms_k, n_k, bytes_k = binding.l4q_profile_read(kind)
+        us = ms_k * 1e3 / max(n_k, 1)
+        gbs = bytes_k / max(ms_k * 1e-3, 1e-12) / 1e9
+        mq[name] = {"us": us, "launches": n_k, "algorithmic_bytes_per_launch": bytes_k / max(n_k, 1),
+                    "GB_per_s": gbs, "frac_hbm": gbs / HBM_PEAK_GBS}
     binding.l4q_profile_gemm(False)
 
     # matrix-core-only ceiling on this chip for the benchmark's own operand values (random bf16 from X)
@@ -323,9 +340,14 @@ def main() -> int:
                      "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH, "launches": gemm_launches,
                      "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
-                     "gemm_share_of_step": gemm_ms / args.steps / ms_per_step,
+                     "gemm_share_of_step": gemm_ms / args.profile_steps / ms_per_step,
                      "measured_mfma_only_tflops": mfma_only_tflops},
     }
+    # merge + quantize pass (Sec. 3.2, Eqs. l4q_Wcombine .. l4q_Wdequant), HBM-bound: forward form (W0 -> Wq) and the
+    # recompute of the backward pass (W0 -> Wq^T + gradient factor), mean over the two layers
+    out["merge_quantize"] = dict(mq, bound="hbm", peak_GB_per_s=HBM_PEAK_GBS,
+                                 share_of_step=sum(v["us"] * v["launches"] for v in mq.values()) * 1e-3
+                                 / args.profile_steps / ms_per_step)
     out["quantized_forward"] = decode
     out["quantized_forward_3bit"] = decode3
     out["qat_lora_same_workload"] = {"ms_per_step": qat_ms, "workspace_bytes_fwd": max(qws_f),

@@ -41,7 +41,7 @@
  * multiply-add,
  *     acc = 0;  for k = 0..r-1: acc = acc + B[p,k] * A[k,j]
  *     Wc  = W0[p,j] + gamma * acc           gamma = (float)alpha / (float)r
- *     w   = (Wc - zero[p,q]) / scale[p,q]   correctly rounded divide
+ *     w   = (Wc - zero[p,q]) / scale[p,q]   correctly rounded divide (or any sequence proved to give its result)
  *     w~  = rint(min(max(w, Q_N), Q_P))     ties to even
  *     m   = (Q_N <= w) && (w <= Q_P)
  * so codes and masks are reproducible bit for bit on any IEEE machine.
@@ -241,15 +241,31 @@ int l4q_adamw_step(const l4q_desc* desc, const l4q_adamw* hp,
  * (App. C: cosine decay with linear warm-up through 10 % of the steps; the end value is this file's reading). */
 float l4q_cosine_lr(int64_t step, int64_t total_steps, double lr_max, double warmup_fraction);
 
-/* Opt-in timing of the bf16 GEMM launches, for benchmarks (not for use under graph capture:
- * it creates HIP events).  While enabled, every GEMM the library enqueues is bracketed by two
- * events recorded on the caller's stream.  This switch and its event list are the library's only
- * process-wide state.  l4q_profile_gemm(1) clears earlier records and starts recording,
- * l4q_profile_gemm(0) stops and clears.  l4q_profile_gemm_read waits for the recorded events
- * (host-blocking) and returns the summed kernel time in milliseconds, the number of launches and
- * their algorithmic FLOPs (2 M N K each, with the unpadded K); any pointer may be NULL. */
+/* Opt-in timing of the library's bf16 GEMM and merge + quantize launches, for benchmarks (not for use under graph
+ * capture: it creates HIP events).  While enabled, every such launch of l4q_forward / l4q_backward (and the GEMMs of
+ * the QAT-LoRA entry points) is bracketed by two events recorded on the caller's stream.  This switch and its event
+ * list are process-wide state.  l4q_profile_gemm(1) clears earlier records and starts recording, l4q_profile_gemm(0)
+ * stops and clears.  l4q_profile_read waits for the recorded events of one kind (host-blocking) and returns their
+ * summed kernel time in milliseconds, the number of launches and their algorithmic work; any pointer may be NULL.
+ *   L4Q_PROFILE_GEMM            work = FLOPs, 2 M N K per launch with the unpadded K
+ *   L4Q_PROFILE_MERGE_FORWARD   the merge + quantize pass of l4q_forward (Eqs. l4q_Wcombine .. l4q_Wdequant);
+ *                               work = bytes: W0 read (2 o i) + scale and zero (8 o G) + Wq written (2 o i)
+ *   L4Q_PROFILE_MERGE_BACKWARD  the recompute pass of l4q_backward; work = bytes: the same reads + Wq^T (2 o i) and,
+ *                               for the fused weight-gradient kernel, the binary16 d(Wq)/d(scale) factor (2 o i)
+ * l4q_profile_gemm_read is l4q_profile_read(L4Q_PROFILE_GEMM, ...). */
+enum { L4Q_PROFILE_GEMM = 0, L4Q_PROFILE_MERGE_FORWARD = 1, L4Q_PROFILE_MERGE_BACKWARD = 2 };
 int l4q_profile_gemm(int enable);
+int l4q_profile_read(int kind, double* total_ms, int64_t* launches, double* total_work);
 int l4q_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops);
+
+/* Diagnostic for the merge + quantize pass, whose bf16 kernels replace the division w = (Wc - zero) / scale of the
+ * arithmetic contract above by a multiplication with the correctly rounded reciprocal of the scale and one
+ * exact-remainder correction.  For `count` (<= 2^23) significands of the scale starting at `first_significand`, at
+ * three exponents each, the device compares (a) that reciprocal with the IEEE 1 / s and (b) the kernels' quotient
+ * with the IEEE x / s for every x = s t moved by -5 .. +5 units in the last place, t running over every rounding tie
+ * k + 1/2 (-128 <= k < 128) and every grid end Q_N, Q_P of 2 .. 8 bits.  counts: 3 x uint64 on the device, zeroed by
+ * the caller; the call adds the number of wrong reciprocals, of wrong quotients, and of quotients compared. */
+int l4q_check_fast_divide(uint32_t first_significand, uint32_t count, uint64_t* counts, void* hip_stream);
 
 /* Matrix-core-only microbenchmark (for benchmarks): `workgroups` workgroups of 4 waves each run
  * `iterations` x 16 v_mfma_f32_32x32x16_bf16 on operand fragments taken from the first 64 KiB of

@@ -20,7 +20,7 @@ INIT_ASYMM, INIT_SYMM, INIT_L4Q, INIT_LSQPLUS = 0, 1, 2, 3
 
 EXPORTED = ["l4q_version", "l4q_status_string", "l4q_workspace_bytes", "l4q_forward", "l4q_backward",
             "l4q_export_codes", "l4q_init_qparams", "l4q_profile_gemm", "l4q_profile_gemm_read", "l4q_mfma_probe", "l4q_quant_errors", "l4q_export_packed", "l4q_quantized_forward", "l4q_quantized_forward_workspace_bytes", "l4q_adamw_step", "l4q_cosine_lr",
-            "l4q_qatlora_workspace_bytes", "l4q_qatlora_forward", "l4q_qatlora_backward", "l4q_quant_errors_static"]
+            "l4q_qatlora_workspace_bytes", "l4q_qatlora_forward", "l4q_qatlora_backward", "l4q_quant_errors_static", "l4q_profile_read", "l4q_check_fast_divide"]
 
 
 class L4QDesc(ctypes.Structure):
@@ -77,6 +77,11 @@ def load_library() -> ctypes.CDLL:
     lib.l4q_profile_gemm_read.restype = ctypes.c_int
     lib.l4q_profile_gemm_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
                                           ctypes.POINTER(ctypes.c_double)]
+    lib.l4q_profile_read.restype = ctypes.c_int
+    lib.l4q_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
+                                     ctypes.POINTER(ctypes.c_double)]
+    lib.l4q_check_fast_divide.restype = ctypes.c_int
+    lib.l4q_check_fast_divide.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp]
     lib.l4q_quant_errors.restype = ctypes.c_int
     lib.l4q_quant_errors.argtypes = [dp, vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, vp]
     lib.l4q_quant_errors_static.restype = ctypes.c_int
@@ -231,6 +236,23 @@ def l4q_profile_gemm_read() -> Tuple[float, int, float]:
     _check(load_library().l4q_profile_gemm_read(ctypes.byref(ms), ctypes.byref(n), ctypes.byref(fl)),
            "l4q_profile_gemm_read")
     return ms.value, n.value, fl.value
+
+
+PROFILE_GEMM, PROFILE_MERGE_FORWARD, PROFILE_MERGE_BACKWARD = 0, 1, 2
+
+
+def l4q_profile_read(kind: int) -> Tuple[float, int, float]:
+    """(summed kernel milliseconds, launches, algorithmic work) of one kind of launch since profiling was enabled."""
+    ms, n, wk = ctypes.c_double(0), ctypes.c_int64(0), ctypes.c_double(0)
+    _check(load_library().l4q_profile_read(int(kind), ctypes.byref(ms), ctypes.byref(n), ctypes.byref(wk)),
+           "l4q_profile_read")
+    return ms.value, n.value, wk.value
+
+
+def l4q_check_fast_divide(first_significand: int, count: int, counts) -> None:
+    """counts: int64 device tensor of 3 elements, zeroed by the caller."""
+    _check(load_library().l4q_check_fast_divide(int(first_significand), int(count), _ptr(counts), _stream()),
+           "l4q_check_fast_divide")
 
 
 def l4q_mfma_probe(data, iterations: int, workgroups: int, sink) -> float:

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libl4q.so")
 
-SOURCES = ["l4q_api.hip", "l4q_quant.hip", "l4q_ref.hip", "l4q_gemm.hip", "l4q_bwd_fused.hip", "l4q_infer.hip", "l4q_lora.hip"]
+SOURCES = ["l4q_api.hip", "l4q_quant.hip", "l4q_merge_stream.hip", "l4q_ref.hip", "l4q_gemm.hip", "l4q_bwd_fused.hip", "l4q_infer.hip", "l4q_lora.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -159,56 +159,65 @@ void* static_scratch_ptr() {
   return g_static_scratch.ptr[dev];
 }
 
-// ---- opt-in timing of the GEMM launches (l4q_profile_gemm) ----
-struct GemmProfile {
+// ---- opt-in timing of the GEMM and merge + quantize launches (l4q_profile_gemm) ----
+enum { kKindGemm = 0, kKindMergeFwd = 1, kKindMergeBwd = 2, kKinds = 3 };
+struct Profile {
   std::mutex mu;
   bool on = false;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
-  double flops = 0.0;
+  struct Rec { hipEvent_t e0, e1; int kind; };
+  std::vector<Rec> events;
+  double work[kKinds] = {0.0, 0.0, 0.0};  // FLOPs (GEMM) or algorithmic bytes (merge + quantize)
 } g_prof;
 
-// Enqueue one bf16 GEMM; when profiling is on, bracket it with events on the same stream.
-void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
-             int64_t K_algorithmic, bf16_t* C, int64_t ldc, hipStream_t stream) {
+// Brackets what is enqueued between construction and destruction with two events on `stream` while profiling is on.
+struct Timed {
+  hipStream_t stream;
+  int kind;
+  double work;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   bool timed = false;
-  {
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    if (g_prof.on && hipEventCreate(&e0) == hipSuccess) {
-      if (hipEventCreate(&e1) == hipSuccess) timed = true;
-      else (void)hipEventDestroy(e0);
+  Timed(hipStream_t s, int k, double w) : stream(s), kind(k), work(w) {
+    {
+      std::lock_guard<std::mutex> lk(g_prof.mu);
+      if (g_prof.on && hipEventCreate(&e0) == hipSuccess) {
+        if (hipEventCreate(&e1) == hipSuccess) timed = true;
+        else (void)hipEventDestroy(e0);
+      }
     }
+    if (timed) (void)hipEventRecord(e0, stream);
   }
-  if (timed) (void)hipEventRecord(e0, stream);
-  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, K_algorithmic, C, ldc, stream);
-  if (timed) {
+  ~Timed() {
+    if (!timed) return;
     (void)hipEventRecord(e1, stream);
     std::lock_guard<std::mutex> lk(g_prof.mu);
-    g_prof.events.emplace_back(e0, e1);
-    g_prof.flops += 2.0 * (double)M * (double)N * (double)K_algorithmic;
+    g_prof.events.push_back({e0, e1, kind});
+    g_prof.work[kind] += work;
   }
+};
+
+// Enqueue one bf16 GEMM (rows of A end at K_algorithmic, the padded operand B at K).
+void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+             int64_t K_algorithmic, bf16_t* C, int64_t ldc, hipStream_t stream) {
+  Timed t(stream, kKindGemm, 2.0 * (double)M * (double)N * (double)K_algorithmic);
+  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, K_algorithmic, C, ldc, stream);
 }
 
 // The fused weight-gradient kernel is a GEMM launch too: time it the same way.
 void dw_fused(const LayerDims& d, const BwdWs& w, const bf16_t* dY, const bf16_t* X, const bf16_t* A, float* dscale,
               float* dzero, hipStream_t stream) {
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  bool timed = false;
-  {
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    if (g_prof.on && hipEventCreate(&e0) == hipSuccess) {
-      if (hipEventCreate(&e1) == hipSuccess) timed = true;
-      else (void)hipEventDestroy(e0);
-    }
-  }
-  if (timed) (void)hipEventRecord(e0, stream);
+  Timed t(stream, kKindGemm, 2.0 * (double)d.o * (double)d.i * (double)d.T);
   l4q::launch_dw_fused(d, dY, X, w.fgrad, A, w.bT, w.opad, dscale, dzero, w.dA_part, w.dB_part, stream);
-  if (timed) {
-    (void)hipEventRecord(e1, stream);
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    g_prof.events.emplace_back(e0, e1);
-    g_prof.flops += 2.0 * (double)d.o * (double)d.i * (double)d.T;
-  }
+}
+
+// The merge + quantize pass of the bf16 layer.  Algorithmic bytes: the frozen weight read once, scale and zero, and
+// what the pass must hand on: Wq (forward), or Wq^T and the gradient factor (fused backward).
+void merge_quant_bf16(const LayerDims& d, const bf16_t* W0, const bf16_t* A, const bf16_t* B, const float* scale,
+                      const float* zero, const l4q::MergeQuantOut<bf16_t>& mq, hipStream_t stream) {
+  const double oi = (double)d.o * (double)d.i;
+  const double bytes = 2.0 * oi + 8.0 * (double)d.o * (double)d.G() + (mq.wq ? 2.0 * oi : 0.0) +
+                       (mq.wqT ? 2.0 * oi : 0.0) + (mq.fgrad ? 2.0 * oi : 0.0);
+  Timed t(stream, mq.wq ? kKindMergeFwd : kKindMergeBwd, bytes);
+  l4q::launch_merge_quant<bf16_t>(d, W0, A, B, scale, zero, mq, stream);
 }
 
 struct QlFwdWs {
@@ -304,7 +313,7 @@ int l4q_forward(const l4q_desc* desc, const void* X, const void* W0, const void*
     l4q::MergeQuantOut<bf16_t> mq;
     mq.wq = wq;
     mq.ld_wq = w.ipad;
-    l4q::launch_merge_quant<bf16_t>(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
+    merge_quant_bf16(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
     gemm_nt((const bf16_t*)X, d.i, wq, w.ipad, d.T, d.o, w.ipad, d.i, (bf16_t*)Y, d.o, stream);
   } else {
     float* wq = static_cast<float*>(w.wq);
@@ -344,7 +353,7 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     mq.ld_wqT = w.opad;
     mq.fgrad = w.fgrad;  // null when unfused
     mq.bT = w.fused ? w.bT : nullptr;
-    l4q::launch_merge_quant<bf16_t>(d, W0b, Ab, Bb, scale, zero, mq, stream);
+    merge_quant_bf16(d, W0b, Ab, Bb, scale, zero, mq, stream);
     // dWq = dY^T . X, both operands read as they lie in memory.  The fused kernel goes first: the factor array the
     // merge pass has just written is then still in the memory-side cache when the epilogues ask for it.
     if (w.fused) {
@@ -680,28 +689,46 @@ int l4q_mfma_probe(const void* data, int iterations, int workgroups, float* sink
 int l4q_profile_gemm(int enable) {
   std::lock_guard<std::mutex> lk(g_prof.mu);
   for (auto& ev : g_prof.events) {
-    (void)hipEventDestroy(ev.first);
-    (void)hipEventDestroy(ev.second);
+    (void)hipEventDestroy(ev.e0);
+    (void)hipEventDestroy(ev.e1);
   }
   g_prof.events.clear();
-  g_prof.flops = 0.0;
+  for (double& w : g_prof.work) w = 0.0;
   g_prof.on = enable != 0;
   return L4Q_OK;
 }
 
-int l4q_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops) {
+int l4q_profile_read(int kind, double* total_ms, int64_t* launches, double* total_work) {
+  if (kind < 0 || kind >= kKinds) return L4Q_ERR_SHAPE;
   std::lock_guard<std::mutex> lk(g_prof.mu);
   double ms = 0.0;
+  int64_t n = 0;
   for (auto& ev : g_prof.events) {
-    if (hipEventSynchronize(ev.second) != hipSuccess) return L4Q_ERR_LAUNCH;
+    if (ev.kind != kind) continue;
+    if (hipEventSynchronize(ev.e1) != hipSuccess) return L4Q_ERR_LAUNCH;
     float t = 0.f;
-    if (hipEventElapsedTime(&t, ev.first, ev.second) != hipSuccess) return L4Q_ERR_LAUNCH;
+    if (hipEventElapsedTime(&t, ev.e0, ev.e1) != hipSuccess) return L4Q_ERR_LAUNCH;
     ms += t;
+    ++n;
   }
   if (total_ms) *total_ms = ms;
-  if (launches) *launches = (int64_t)g_prof.events.size();
-  if (total_flops) *total_flops = g_prof.flops;
+  if (launches) *launches = n;
+  if (total_work) *total_work = g_prof.work[kind];
   return L4Q_OK;
+}
+
+int l4q_profile_gemm_read(double* total_ms, int64_t* launches, double* total_flops) {
+  return l4q_profile_read(kKindGemm, total_ms, launches, total_flops);
+}
+
+int l4q_check_fast_divide(uint32_t first_significand, uint32_t count, uint64_t* counts, void* hip_stream) {
+  if (!counts) return L4Q_ERR_NULL;
+  if (!aligned(counts, 16)) return L4Q_ERR_ALIGN;
+  if (count == 0 || count > (1u << 23)) return L4Q_ERR_SHAPE;
+  (void)hipGetLastError();
+  l4q::launch_check_fast_divide(first_significand, count, reinterpret_cast<unsigned long long*>(counts),
+                                static_cast<hipStream_t>(hip_stream));
+  return launch_status();
 }
 
 }  // extern "C"

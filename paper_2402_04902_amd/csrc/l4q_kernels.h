@@ -39,6 +39,17 @@ void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B,
                         const float* zero, const MergeQuantOut<T>& out, hipStream_t stream);
 
 
+// Streaming form of the pass for bfloat16 storage (l4q_merge_stream.hip): the forward output set (wq alone) or the
+// fused-backward set (wqT + fgrad [+ bT]), rank a multiple of 8, group size >= 32.  launch_merge_quant uses it where
+// it applies.
+bool merge_quant_stream_supported(const LayerDims& d, const MergeQuantOut<bf16_t>& out);
+void launch_merge_quant_stream(const LayerDims& d, const bf16_t* W0, const bf16_t* A, const bf16_t* B,
+                               const float* scale, const float* zero, const MergeQuantOut<bf16_t>& out,
+                               hipStream_t stream);
+// Check of the streaming form's reciprocal-based quotient against the IEEE divide for `count` significands of the
+// scale starting at `first`; counts (device, zeroed by the caller): wrong reciprocals, wrong quotients, quotients compared.
+void launch_check_fast_divide(uint32_t first, uint32_t count, unsigned long long* counts, hipStream_t stream);
+
 // ---- per-group min/max initialisation (App. B, Eq. quant_inits) ----
 template <class T>
 void launch_init_qparams(const LayerDims& d, const T* W0, const T* A, const T* B, int method, float* scale,

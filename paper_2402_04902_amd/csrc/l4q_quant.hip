@@ -580,6 +580,12 @@ __global__ __launch_bounds__(kThreads) void init_qparams_kernel(LayerDims d, con
 template <class T>
 void launch_merge_quant(const LayerDims& d, const T* W0, const T* A, const T* B, const float* scale,
                         const float* zero, const MergeQuantOut<T>& out, hipStream_t stream) {
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    if (merge_quant_stream_supported(d, out)) {
+      launch_merge_quant_stream(d, W0, A, B, scale, zero, out, stream);
+      return;
+    }
+  }
   const int64_t rows = out.wqT && out.ld_wqT > d.o ? out.ld_wqT : d.o;
   dim3 grid((unsigned)((d.i + MQ_COLS - 1) / MQ_COLS), (unsigned)((rows + MQ_ROWS - 1) / MQ_ROWS));
   const bool misc = out.codes || out.wcomb || out.mask;

@@ -139,3 +139,40 @@ def check_discrete(spec, layer, arrs, s, b, dec, Wc32):
     assert not (md & ~bnd).any(), "mask differs from the float64 chain away from the grid ends"
     return {"near_ties": int(tie.sum()), "near_boundaries": int(bnd.sum()), "codes_vs_f64": int(cd.sum()),
             "mask_vs_f64": int(md.sum())}
+
+
+def check_workspace_state(spec, layer, dec, w32, s, b, fused):
+    """bfloat16 layers: what the merge + quantize pass of the forward and of the backward call left in the workspace,
+    bit for bit against the oracle's binary32 chain.  The training path takes its discrete decisions in kernels of its
+    own (not the export kernel check_discrete looks at), and they reach the outputs only through floating-point sums;
+    here they are looked at directly.  Workspace layout (documented with the library's design): forward Wq [o, ipad]
+    bfloat16 first; backward Wq^T [i, opad] bfloat16 first, then (fused weight-gradient kernel only) the binary16
+    factor d(Wq)/d(scale) [o, i], each 256-byte aligned; ipad / opad = i / o rounded up to 32.
+    Call after layer.forward() and layer.backward() in this order, synchronised."""
+    import torch
+    o, i = spec.out_features, spec.in_features
+    ipad, opad = (i + 31) // 32 * 32, (o + 31) // 32 * 32
+    g = spec.group_size
+    s32 = np.repeat(np.asarray(s, np.float32), g, axis=1)
+    b32 = np.repeat(np.asarray(b, np.float32), g, axis=1)
+    codes = dec.codes.astype(np.float32)
+    # Wq = fma(code, s, b) rounded once to binary32 (exact product, one binary64 addition: 53 bits hold it in all but
+    # astronomically rare cases), then to bfloat16
+    wq32 = (codes.astype(np.float64) * s32.astype(np.float64) + b32.astype(np.float64)).astype(np.float32)
+    wq_bits = inputs.bf16_bits(inputs.round_to_bf16(wq32))
+    # backward workspace (the last call): Wq^T and the factor
+    ws = layer.ws
+    wqT = ws[: i * opad * 2].view(torch.int16).reshape(i, opad).cpu().numpy().view(np.uint16)
+    assert np.array_equal(wqT[:, :o], wq_bits.T), f"{(wqT[:, :o] != wq_bits.T).sum()} elements of Wq^T differ"
+    assert not wqT[:, o:].any(), "padding of Wq^T is not zero"
+    if fused:
+        off = (i * opad * 2 + 255) // 256 * 256
+        f = ws[off: off + o * i * 2].view(torch.int16).reshape(o, i).cpu().numpy().view(np.uint16)
+        want = np.where(dec.mask, codes - w32.astype(np.float32), codes).astype(np.float16).view(np.uint16)
+        assert np.array_equal(f, want), f"{(f != want).sum()} gradient factors differ"
+    # forward workspace: run the forward pass once more (it overwrites the workspace)
+    layer.forward()
+    torch.cuda.synchronize()
+    wq = ws[: o * ipad * 2].view(torch.int16).reshape(o, ipad).cpu().numpy().view(np.uint16)
+    assert np.array_equal(wq[:, :i], wq_bits), f"{(wq[:, :i] != wq_bits).sum()} elements of Wq differ"
+    assert not wq[:, i:].any(), "padding of Wq is not zero"

@@ -10,9 +10,12 @@ import pytest
 from paper_2402_04902_amd import inputs
 from paper_2402_04902_amd.inputs import DTYPE_BF16, DTYPE_F32, LayerSpec
 
-from parity_util import BOUNDS, check_discrete, check_float_outputs, compare_tensor, host_qparams, oracle_all
+from parity_util import (BOUNDS, check_discrete, check_float_outputs, check_workspace_state, compare_tensor,
+                         host_qparams, oracle_all)
 
 pytestmark = pytest.mark.gpu
+
+FUSED_MAX_RANK = 32   # ranks the fused weight-gradient epilogue covers
 
 # optional: a file that collects one JSON line of measured errors per case
 REPORT = os.environ.get("L4Q_PARITY_REPORT", "")
@@ -38,6 +41,10 @@ def run_case(spec, seed=0, method="asymm", shrink=1.0, flags=0, mutate=None, dis
     layer.backward()
     torch.cuda.synchronize()
     check_float_outputs(spec, layer, Y, gr, rep)
+    if spec.dtype == DTYPE_BF16:
+        fused = (flags & binding.FLAG_UNFUSED_BACKWARD) == 0 and spec.rank <= FUSED_MAX_RANK and \
+            spec.group_size in (32, 64, 128, 256)
+        check_workspace_state(spec, layer, dec, w32, s, b, fused)
     if REPORT:
         try:
             with open(REPORT, "a") as f:
