@@ -77,6 +77,10 @@ struct FwdWs {
 };
 struct BwdWs {
   bool fused;        // bf16: weight-gradient GEMM with the fused quantizer epilogue
+  bool masked;       // bf16, ranks above 32: its second form (masked gradient stored as bf16, thin dA / dB products);
+                     // the masked gradient takes the place of the factor array, tile by tile
+  float* rawA;       // [r,i]                      (bf16 masked)
+  float* rawB;       // [o,r]                      (bf16 masked)
   float* wq32;       // [o,i]                      (binary32 mode)
   bf16_t* wqT;       // [i,opad]                   (bf16)
   uint16_t* fgrad;   // [o,i] binary16             (bf16 fused)
@@ -110,8 +114,13 @@ BwdWs carve_bwd(const l4q_desc* d, void* ws) {
   const size_t nrb = (o + l4q::kDaRowBlock - 1) / l4q::kDaRowBlock;
   if (d->dtype == L4Q_DTYPE_BF16) {
     w.fused = !(d->flags & L4Q_FLAG_UNFUSED_BACKWARD) && l4q::dw_fused_supported(L);
+    w.masked = !(d->flags & L4Q_FLAG_UNFUSED_BACKWARD) && l4q::dw_masked_supported(L);
     w.wqT = c.take<bf16_t>(i * (size_t)w.opad);
-    if (w.fused) {
+    if (w.masked) {
+      w.fgrad = c.take<uint16_t>(n);
+      w.rawA = c.take<float>(r * i);
+      w.rawB = c.take<float>(o * r);
+    } else if (w.fused) {
       l4q::dw_fused_tiles(L, &w.tiles_m, &w.tiles_n);
       w.fgrad = c.take<uint16_t>(n);
       w.bT = c.take<bf16_t>(r * (size_t)w.opad);
@@ -352,7 +361,7 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
     mq.wqT = w.wqT;
     mq.ld_wqT = w.opad;
     mq.fgrad = w.fgrad;  // null when unfused
-    mq.bT = w.fused ? w.bT : nullptr;
+    mq.bT = w.fused ? w.bT : nullptr;  // (the masked form reads B as it lies)
     merge_quant_bf16(d, W0b, Ab, Bb, scale, zero, mq, stream);
     // dWq = dY^T . X, both operands read as they lie in memory.  The fused kernel goes first: the factor array the
     // merge pass has just written is then still in the memory-side cache when the epilogues ask for it.
@@ -361,8 +370,19 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
       l4q::launch_reduce_two_partials(w.dA_part, w.tiles_m, (int64_t)d.r * d.i, dA, w.dB_part, 2 * w.tiles_n,
                                       d.o * d.r, dB, d.gamma, d.accumulate, stream);
     }
+    if (w.masked) {
+      {
+        Timed t(stream, kKindGemm, 2.0 * (double)d.o * (double)d.i * (double)d.T);
+        // in place: a workgroup has its tile of the factors in LDS before it writes the tile's masked gradient, and no
+        // other workgroup touches that tile
+        l4q::launch_dw_masked(d, (const bf16_t*)dY, (const bf16_t*)X, w.fgrad, dscale, dzero, (bf16_t*)w.fgrad, stream);
+      }
+      l4q::launch_dw_masked_products(d, (const bf16_t*)w.fgrad, Ab, Bb, w.rawA, w.rawB, stream);
+      l4q::launch_reduce_two_partials(w.rawA, 1, (int64_t)d.r * d.i, dA, w.rawB, 1, d.o * d.r, dB, d.gamma,
+                                      d.accumulate, stream);
+    }
     gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream);
-    if (!w.fused) {
+    if (!w.fused && !w.masked) {
       l4q::launch_gemm_bf16_kmajor_f32((const bf16_t*)dY, d.o, (const bf16_t*)X, d.i, d.o, d.i, d.T, w.dwq, d.i, stream);
       l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);
       l4q::launch_dA<bf16_t>(d, Bb, w.dwq, w.dA_part, dA, stream);

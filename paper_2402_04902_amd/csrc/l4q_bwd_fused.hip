@@ -21,6 +21,12 @@
 //    lane holds; the transposing LDS read turns it into operand fragments) and is multiplied with B^T.
 // Partial results per tile row / tile column go to the workspace and are summed by a second,
 // tiny kernel in a fixed order, so the result does not depend on scheduling.
+//
+// Ranks above 32.  The volume of those partial sums grows with the rank (o i r / 32 bytes: at r = 64 as much as the
+// masked gradient itself in bfloat16, at r = 128 as much as dWq in binary32), so from rank 33 on the kernel runs in a
+// second form: group sums as above, and the masked tile m * dWq, which the epilogue has in LDS anyway, leaves as
+// bfloat16 [o, i] (half of what a stored binary32 dWq would take); dA and dB are then two thin products on the matrix
+// core (launch_dw_masked_products).
 #include "l4q_device.h"
 #include "l4q_gemm_core.h"
 #include "l4q_kernels.h"
@@ -52,6 +58,7 @@ struct FusedArgs {
   float* dscale; float* dzero;        // [o, i/g]
   float* dA_part;                     // [tiles_m, r, i]
   float* dB_part;                     // [2 * tiles_n, o, r]
+  bf16_t* dWm;                        // [o, i]: the masked gradient (second form only); may be the fgrad array itself
   int tiles_m, tiles_n;
   int accumulate;                     // add dscale / dzero to what the outputs hold
 };
@@ -62,6 +69,8 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(uint32_t a, uint32_t b, uint32_t c
   return __builtin_bit_cast(bf16x8_t, v);
 }
 
+// STORE_MASKED = false: dA / dB partial sums in the epilogue (rank <= 32).  true: the masked tile is written out.
+template <bool STORE_MASKED>
 __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[FUSED_LDS];
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -114,7 +123,7 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     for (int h = 0; h < 2; ++h) {
       const int j = n0 + wn * 128 + b * 32 + 16 * h + 4 * lh;
       uint2 lo = make_uint2(0, 0), hi = make_uint2(0, 0);
-      if (l32 < p.r && j < p.i) {  // i is a multiple of 32 here (g >= 32), so a 32-column tile is inside or outside as a whole
+      if (!STORE_MASKED && l32 < p.r && j < p.i) {  // i is a multiple of 32 here (g >= 32), so a 32-column tile is inside or outside as a whole
         lo = *reinterpret_cast<const uint2*>(p.A + (int64_t)l32 * p.i + j);
         hi = *reinterpret_cast<const uint2*>(p.A + (int64_t)l32 * p.i + j + 8);
       }
@@ -220,18 +229,20 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
     }
 
     // ---- dB: (masked gradient) x A^T on the matrix core, 2 k-steps of 16 columns per 32-column tile
-    f32x16_t cb;
+    if constexpr (!STORE_MASKED) {
+      f32x16_t cb;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) cb[e] = 0.f;
+      for (int e = 0; e < 16; ++e) cb[e] = 0.f;
 #pragma unroll
-    for (int b = 0; b < T::TN; ++b) {
+      for (int b = 0; b < T::TN; ++b) {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const bf16x8_t gfrag = as_bf16x8(pk[b][4 * h], pk[b][4 * h + 1], pk[b][4 * h + 2], pk[b][4 * h + 3]);
-        cb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gfrag, afrag[b][h], cb, 0, 0, 0);
+        for (int h = 0; h < 2; ++h) {
+          const bf16x8_t gfrag = as_bf16x8(pk[b][4 * h], pk[b][4 * h + 1], pk[b][4 * h + 2], pk[b][4 * h + 3]);
+          cb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gfrag, afrag[b][h], cb, 0, 0, 0);
+        }
       }
+      accB[a] = cb;
     }
-    accB[a] = cb;
 
     // ---- masked gradient to LDS as it lies in the registers: row p, 4 consecutive columns per 8-byte write
 #pragma unroll
@@ -243,6 +254,37 @@ __global__ __launch_bounds__(T::NT) void dw_fused_kernel(FusedArgs p) {
         *reinterpret_cast<uint2*>(lds + pl * EP_ROWB + jl * 2) = make_uint2(pk[b][2 * eg], pk[b][2 * eg + 1]);
       }
     }
+  }
+
+  if constexpr (STORE_MASKED) {
+    __syncthreads();
+    if (p.g == 256 && wn == 0 && lh == 0) {
+      const int q = n0 / 256;
+#pragma unroll
+      for (int a = 0; a < T::TM; ++a) {
+        const int row = m0 + wm * 128 + a * 32 + l32;
+        const float* sc = reinterpret_cast<const float*>(lds + EP_TILE) + (wm * 128 + a * 32 + l32) * 2;
+        if (row < p.o && q < G) {
+          put(p.dscale + (int64_t)row * G + q, keep_ds[a] + sc[0]);
+          put(p.dzero + (int64_t)row * G + q, keep_db[a] + sc[1]);
+        }
+      }
+    }
+    // ---- the masked tile leaves as it lies in LDS: 16 bytes per lane, a 512-byte row per 32 lanes; rows past o and
+    //      columns past i (whole 16-byte pieces: i % 8 == 0) get an out-of-range offset
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(p.dWm, 0, (int)((int64_t)p.o * p.i * 2),
+                                                                         0x00020000);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int ch = threadIdx.x & 31;
+#pragma unroll 4
+    for (int it = 0; it < 256 / 8; ++it) {
+      const int row = it * 8 + (threadIdx.x >> 5);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * EP_ROWB + ch * 16);
+      const bool ok = m0 + row < p.o && n0 + ch * 8 < p.i;
+      const unsigned vo = ok ? (unsigned)(((int64_t)(m0 + row) * p.i + n0 + ch * 8) * 2) : gemm::OOB_OFFSET;
+      __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)vo, 0, 0);
+    }
+    return;
   }
 
   // ---- dB partials: register e of lane l is (row 8 (e/4) + 4 (l/32) + e%4 of the block, rank l % 32)
@@ -340,6 +382,13 @@ bool dw_fused_supported(const LayerDims& d) {
   return g_ok && d.r <= 32 && d.i < (1 << 22);  // 32-bit offsets of factor rows up to 255 past the last one
 }
 
+// The second form (masked gradient stored as bfloat16, dA / dB as thin products): ranks 33 .. 256 that are multiples
+// of 8 (16-byte rows of B and of the binary32 results), in-features a multiple of the 32-wide k-step of the dB product.
+bool dw_masked_supported(const LayerDims& d) {
+  const bool g_ok = d.g == 32 || d.g == 64 || d.g == 128 || d.g == 256;
+  return g_ok && d.r > 32 && d.r <= 256 && d.r % 8 == 0 && d.i % 32 == 0 && d.i < (1 << 22);
+}
+
 void dw_fused_tiles(const LayerDims& d, int* tiles_m, int* tiles_n) {
   *tiles_m = (int)((d.o + T::BM - 1) / T::BM);
   *tiles_n = (int)((d.i + T::BN - 1) / T::BN);
@@ -355,9 +404,25 @@ void launch_dw_fused(const LayerDims& d, const bf16_t* dY, const bf16_t* X, cons
   p.o = (int)d.o; p.i = (int)d.i; p.r = d.r; p.g = d.g;
   p.fgrad = fgrad; p.A = A; p.BT = BT; p.ld_bt = ld_bt;
   p.dscale = dscale; p.dzero = dzero; p.dA_part = dA_part; p.dB_part = dB_part;
+  p.dWm = nullptr;
   dw_fused_tiles(d, &p.tiles_m, &p.tiles_n);
   p.accumulate = d.accumulate ? 1 : 0;
-  hipLaunchKernelGGL(dw_fused_kernel, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(T::NT), 0, stream, p);
+  hipLaunchKernelGGL(dw_fused_kernel<false>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(T::NT), 0, stream, p);
+}
+
+void launch_dw_masked(const LayerDims& d, const bf16_t* dY, const bf16_t* X, const uint16_t* fgrad, float* dscale,
+                      float* dzero, bf16_t* dWm, hipStream_t stream) {
+  FusedArgs p = {};
+  p.dY = dY;
+  p.X = X;
+  p.K = (int)d.T;
+  p.o = (int)d.o; p.i = (int)d.i; p.r = d.r; p.g = d.g;
+  p.fgrad = fgrad;
+  p.dscale = dscale; p.dzero = dzero;
+  p.dWm = dWm;
+  dw_fused_tiles(d, &p.tiles_m, &p.tiles_n);
+  p.accumulate = d.accumulate ? 1 : 0;
+  hipLaunchKernelGGL(dw_fused_kernel<true>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(T::NT), 0, stream, p);
 }
 
 }  // namespace l4q

@@ -181,4 +181,18 @@ void launch_gemm_bf16_kmajor_f32(const bf16_t* A, int64_t lda, const bf16_t* B, 
                      tiles_n);
 }
 
+void launch_dw_masked_products(const LayerDims& d, const bf16_t* dWm, const bf16_t* A, const bf16_t* B, float* rawA,
+                               float* rawB, hipStream_t stream) {
+  // rawB [o, r] = dWm [o, i] . A [r, i]^T: both K-contiguous, k = i (a multiple of 32: nothing to pad or mask)
+  {
+    typedef gemm::Tile<256, 256, 32, 5, true, 4> F;
+    const int tiles_m = (int)((d.o + F::BM - 1) / F::BM), tiles_n = (d.r + F::BN - 1) / F::BN;
+    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, false, false, false, false>), dim3((unsigned)(tiles_m * tiles_n)),
+                       dim3(F::NT), 0, stream, dWm, d.i, A, d.i, (int)d.o, d.r, (int)d.i, (int)d.i, (void*)rawB,
+                       (int64_t)d.r, tiles_m, tiles_n);
+  }
+  // rawA [r, i] = B [o, r]^T . dWm [o, i]: both K-major, k = o
+  launch_gemm_bf16_kmajor_f32(B, d.r, dWm, d.i, d.r, d.i, d.o, rawA, d.i, stream);
+}
+
 }  // namespace l4q

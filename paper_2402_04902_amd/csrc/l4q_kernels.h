@@ -136,6 +136,16 @@ void launch_dw_fused(const LayerDims& d, const bf16_t* dY, const bf16_t* X, cons
                      hipStream_t stream);
 
 
+// Second form for ranks 33 .. 256 (see l4q_bwd_fused.hip): dscale, dzero as above, and the masked gradient m * dWq
+// written as bfloat16 dWm [o, i]; then launch_dw_masked_products forms
+//   rawA [r, i] = B^T . dWm  and  rawB [o, r] = dWm . A^T   (binary32, no gamma yet)
+// with the library's GEMM kernels.
+bool dw_masked_supported(const LayerDims& d);
+void launch_dw_masked(const LayerDims& d, const bf16_t* dY, const bf16_t* X, const uint16_t* fgrad, float* dscale,
+                      float* dzero, bf16_t* dWm, hipStream_t stream);
+void launch_dw_masked_products(const LayerDims& d, const bf16_t* dWm, const bf16_t* A, const bf16_t* B, float* rawA,
+                               float* rawB, hipStream_t stream);
+
 // ---- rank-r side products of the QAT-LoRA layer (Sec. 3.1): U binary32 [T, r]; the small matrix M is read as
 // [r, n] (A) or, with m_is_n_by_r, as [n, r] (B) ----
 template <class S>

@@ -42,6 +42,7 @@ def run_case(spec, seed=0, method="asymm", shrink=1.0, flags=0, mutate=None, dis
     torch.cuda.synchronize()
     check_float_outputs(spec, layer, Y, gr, rep)
     if spec.dtype == DTYPE_BF16:
+        # the factor array survives the call only where the epilogue forms dA / dB itself (rank <= 32)
         fused = (flags & binding.FLAG_UNFUSED_BACKWARD) == 0 and spec.rank <= FUSED_MAX_RANK and \
             spec.group_size in (32, 64, 128, 256)
         check_workspace_state(spec, layer, dec, w32, s, b, fused)
@@ -123,10 +124,22 @@ def test_bf16_unfused_backward_flag(T, i, o, r, bits, g):
     run_case(spec, seed=T + 1, shrink=0.8, flags=binding.FLAG_UNFUSED_BACKWARD, discrete=False)
 
 
-def test_bf16_rank_above_fused_limit():
-    """Rank 40 is beyond the fused epilogue's 32: the library takes the unfused kernels by itself."""
-    spec = LayerSpec("bf16_rank40", 200, 512, 264, 40, 80.0, 4, 128, DTYPE_BF16)
-    run_case(spec, seed=40, shrink=0.8)
+@pytest.mark.parametrize("r,T,i,o,g", [(40, 200, 512, 264, 128), (64, 300, 1024, 520, 64), (128, 513, 768, 1032, 256),
+                                       (256, 70, 256, 136, 32), (48, 45, 200, 136, 8), (36, 64, 512, 264, 128)])
+def test_bf16_ranks_above_32(r, T, i, o, g):
+    """Ranks of the paper's rank sweep beyond 32 (App. D): the weight-gradient kernel keeps d(scale) / d(zero) in its
+    epilogue and hands the masked gradient on as bfloat16 for the two thin dA / dB products; no binary32 weight
+    gradient is stored (the backward workspace stays below what the unfused path asks for by more than o i 2 bytes).
+    In-features 200 (not a multiple of 32), group 8 and rank 36 (not a multiple of 8) take the unfused kernels."""
+    from paper_2402_04902_amd import binding
+    spec = LayerSpec(f"bf16_rank{r}", T, i, o, r, 2.0 * r, 4, g, DTYPE_BF16)
+    run_case(spec, seed=r, shrink=0.8)
+    _, bwd = binding.l4q_workspace_bytes(binding.make_desc(spec))
+    _, bwd_unfused = binding.l4q_workspace_bytes(binding.make_desc(spec, binding.FLAG_UNFUSED_BACKWARD))
+    if i % 32 == 0 and g >= 32 and r % 8 == 0:
+        assert bwd < bwd_unfused - o * i * 2 + 4 * r * (i + o) + 4096
+    else:
+        assert bwd == bwd_unfused
 
 
 def test_bf16_zero_B_is_plain_qat_and_kills_dA():
