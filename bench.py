@@ -223,27 +223,40 @@ def main() -> int:
         packs.append(pk)
     qfws = [torch.empty(max(256, binding.l4q_quantized_forward_workspace_bytes(l.desc)), dtype=torch.uint8,
                        device="cuda:0") for l in layers]
+    def time_decode(descs_, xs_, packs_, ys_, wss_, tok):
+        """Both layers back to back (the pair figure), then each layer's launch on its own: the packed weights, scale
+        and zero, and the activations in and out are the algorithmic bytes; 8 TB/s is the roofline."""
+        def one(k):
+            binding.l4q_quantized_forward(descs_[k], xs_[k], packs_[k], layers[k].scale, layers[k].zero, ys_[k], wss_[k])
+
+        def nbytes(k):
+            sp = layers[k].spec
+            return packs_[k].numel() * 4 + 2 * layers[k].scale.numel() * 4 + tok * (sp.in_features + sp.out_features) * 2
+        res = {}
+        for name, ks in (("both_layers", (0, 1)), ("up_11008x4096", (0,)), ("down_4096x11008", (1,))):
+            for _ in range(5):
+                for k in ks:
+                    one(k)
+            torch.cuda.synchronize()
+            ev0.record()
+            for _ in range(50):
+                for k in ks:
+                    one(k)
+            ev1.record()
+            torch.cuda.synchronize()
+            us = ev0.elapsed_time(ev1) * 1e3 / 50
+            nb = sum(nbytes(k) for k in ks)
+            res[name] = {"us": us, "GB_per_s": nb / (us * 1e-6) / 1e9, "frac_hbm_8TBs": nb / (us * 1e-6) / 8e12}
+        out_ = dict(res["both_layers"])
+        out_["us_both_layers"] = out_.pop("us")
+        out_["per_layer"] = {k: v for k, v in res.items() if k != "both_layers"}
+        return out_
+
     for tok in (1, 16, 64):
         descs = [binding.make_desc(l.spec.with_(tokens=tok)) for l in layers]
         xs = [l.X[:tok] for l in layers]
         ys = [l.Y[:tok] for l in layers]
-
-        def qstep():
-            for d_, x_, p_, l_, y_, w_ in zip(descs, xs, packs, layers, ys, qfws):
-                binding.l4q_quantized_forward(d_, x_, p_, l_.scale, l_.zero, y_, w_)
-        for _ in range(5):
-            qstep()
-        torch.cuda.synchronize()
-        ev0.record()
-        for _ in range(50):
-            qstep()
-        ev1.record()
-        torch.cuda.synchronize()
-        us = ev0.elapsed_time(ev1) * 1e3 / 50
-        nbytes = sum(p_.numel() * 4 + 2 * l_.scale.numel() * 4 + tok * (l_.spec.in_features + l_.spec.out_features) * 2
-                     for p_, l_ in zip(packs, layers))
-        decode["T%d" % tok] = {"us_both_layers": us, "GB_per_s": nbytes / (us * 1e-6) / 1e9,
-                               "frac_hbm_8TBs": nbytes / (us * 1e-6) / 8e12}
+        decode["T%d" % tok] = time_decode(descs, xs, packs, ys, qfws, tok)
 
     # the same leg at 3 bits (the paper's other code width) on the same two shapes: seeded random packed words, the
     # layers' scale / zero
@@ -259,22 +272,7 @@ def main() -> int:
         xs = [l.X[:tok] for l in layers]
         ys = [l.Y[:tok] for l in layers]
 
-        def qstep3():
-            for d_, x_, p_, l_, y_, w_ in zip(descs3, xs, packs3, layers, ys, qfws3):
-                binding.l4q_quantized_forward(d_, x_, p_, l_.scale, l_.zero, y_, w_)
-        for _ in range(5):
-            qstep3()
-        torch.cuda.synchronize()
-        ev0.record()
-        for _ in range(50):
-            qstep3()
-        ev1.record()
-        torch.cuda.synchronize()
-        us = ev0.elapsed_time(ev1) * 1e3 / 50
-        nbytes = sum(p_.numel() * 4 + 2 * l_.scale.numel() * 4 + tok * (l_.spec.in_features + l_.spec.out_features) * 2
-                     for p_, l_ in zip(packs3, layers))
-        decode3["T%d" % tok] = {"us_both_layers": us, "GB_per_s": nbytes / (us * 1e-6) / 1e9,
-                                "frac_hbm_8TBs": nbytes / (us * 1e-6) / 8e12}
+        decode3["T%d" % tok] = time_decode(descs3, xs, packs3, ys, qfws3, tok)
     del packs3
 
     # the QAT-LoRA layer (Sec. 3.1) on the same workload: separate LoRA path, stored weight gradient
