@@ -19,8 +19,7 @@ constexpr int kThreads = 256;
 // Block tile: MQ_ROWS weight rows x 256 columns, 8 waves.  A thread owns 4 consecutive columns (one
 // 8- or 16-byte load of W0 per row, 512 B / 1 KiB contiguous per wave) and its wave walks MQ_RPW
 // rows.  The rank loop runs k-outer: A[k, 4 columns] is unpacked once and used for all rows, B[p, k]
-// is wave-uniform and comes through scalar loads (or, for rows of B that do not start on a 4-byte
-// boundary, is fetched by lane k and read back with v_readlane), and the running sums of all rows stay
+// is wave-uniform and comes through scalar loads, and the running sums of all rows stay
 // in registers, which keeps the k-ascending summation order for any rank.
 // Every load is unconditional (clamped address, value discarded where out of range) so that the
 // W0 / scale / zero loads of all rows are in flight while the rank loop runs.
@@ -41,10 +40,9 @@ __device__ __forceinline__ void unpack4(const uint2& r, float (&v)[4]) {
 }
 
 // acc[rr][c] = sum_k B[pw + rr, k] * A[k, jc + c], k ascending, for the MQ_RPW rows of a wave and the 4 columns
-// of a lane.  Rows past o are clamped (their sums are never used).  A row of B is wave-uniform: where rows
-// start on a 4-byte boundary it is fetched with scalar loads and each B[p, k] reaches the multiply-add as a
-// scalar operand; otherwise lane k fetches it and it is read back with v_readlane (no lane may then skip this
-// call).  Steps past the rank multiply by zero, which leaves the running sum unchanged bit for bit.
+// of a lane (binary32 storage; bfloat16 storage takes lora_rows_mfma).  Rows past o are clamped (their sums are
+// never used).  A row of B is wave-uniform: it is fetched with scalar loads and each B[p, k] reaches the
+// multiply-add as a scalar operand.
 template <class T> struct BWord;
 template <> struct BWord<float> { static constexpr int PER = 1; };   // B values per 32-bit word
 template <> struct BWord<bf16_t> { static constexpr int PER = 2; };
@@ -62,7 +60,7 @@ __device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restric
   for (int rr = 0; rr < MQ_RPW; ++rr)
 #pragma unroll
     for (int c = 0; c < 4; ++c) acc[rr][c] = 0.f;
-  if ((d.r % PER) == 0) {  // rows of B are whole 32-bit words: scalar path, any rank
+  {  // rows of B are whole 32-bit words (binary32 storage; bfloat16 rows with an even rank): scalar path, any rank
     const int nw = d.r / PER;
     const uint32_t* Bw = reinterpret_cast<const uint32_t*>(B);
     const uint32_t* brow[MQ_RPW];
@@ -85,34 +83,6 @@ __device__ __forceinline__ void lora_rows(const LayerDims& d, const T* __restric
 #pragma unroll
           for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[c]);
         }
-      }
-    }
-    return;
-  }
-  for (int k0 = 0; k0 < d.r; k0 += MQ_KC) {
-    raw4_t araw[MQ_KC];
-#pragma unroll
-    for (int k = 0; k < MQ_KC; ++k) {
-      const int kc = k0 + k < d.r ? k0 + k : d.r - 1;
-      araw[k] = *reinterpret_cast<const raw4_t*>((A + (int64_t)kc * d.i) + jc);
-    }
-    float brow[MQ_RPW];
-#pragma unroll
-    for (int rr = 0; rr < MQ_RPW; ++rr) {
-      const int64_t pc = pw + rr < d.o ? pw + rr : d.o - 1;
-      const int kl = k0 + (lane & (MQ_KC - 1));
-      const float v = load1((B + pc * d.r) + (kl < d.r ? kl : d.r - 1));
-      brow[rr] = kl < d.r ? v : 0.f;
-    }
-#pragma unroll
-    for (int k = 0; k < MQ_KC; ++k) {
-      float a[4];
-      unpack4(araw[k], a);
-#pragma unroll
-      for (int rr = 0; rr < MQ_RPW; ++rr) {
-        const float bk = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(brow[rr]), k));
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[rr][c] = lora_mac<T>(acc[rr][c], bk, a[c]);
       }
     }
   }
