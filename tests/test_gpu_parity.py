@@ -90,6 +90,42 @@ def test_bf16_small_shapes(T, i, o, r, bits, g, shrink):
         assert rep["clipped"] > 0
 
 
+@pytest.mark.parametrize("T,i,o,r,bits,g", [
+    (33, 96, 40, 8, 4, 32),        # one and a half 64-column strips, two groups per strip, a partial row block
+    (70, 160, 72, 24, 3, 32),      # rank = one and a half chunks of 16; in-features not a multiple of 64
+    (129, 320, 200, 72, 4, 64),    # five rank chunks (the last half full), 6.25 row blocks
+    (40, 1088, 24, 16, 8, 64),     # 4.25 column tiles of 256, fewer rows than one row block
+    (64, 2048, 1000, 16, 2, 2048), # one group per row, 31.25 row blocks: uneven runs per wavefront
+    (17, 64, 8, 8, 4, 64),         # the smallest: one strip, one partial row block
+])
+@pytest.mark.parametrize("shrink", [1.0, 0.7])
+def test_bf16_streaming_merge_edges(T, i, o, r, bits, g, shrink):
+    """Shapes at the edges of the streaming merge + quantize kernel (64-column strips, 32-row blocks, rank chunks of
+    16, one or two groups per strip): codes / mask / merged weight through the export form, Wq / Wq^T / factor through
+    the workspace, all bit for bit, plus the float outputs."""
+    spec = LayerSpec(f"bf16_stream_{T}x{i}x{o}_r{r}", T, i, o, r, 2.0 * r, bits, g, DTYPE_BF16)
+    rep, _, _ = run_case(spec, seed=i + r, shrink=shrink)
+    if shrink < 1.0:
+        assert rep["clipped"] > 0
+
+
+def test_bf16_scale_outside_the_reciprocal_range_takes_the_ieee_divide():
+    """Scales below 2^-60 (and zeros of the same order) leave the range in which the streaming kernel divides by
+    multiplication; the wave-uniform fallback must give the same bits as the oracle's division."""
+    def tiny(arrs):
+        for k in ("W0", "B"):
+            arrs[k] *= np.float32(2.0 ** -70)
+            arrs[k][...] = inputs.round_to_bf16(arrs[k])
+    spec = LayerSpec("bf16_tiny_scales", 64, 256, 72, 8, 16.0, 4, 64, DTYPE_BF16)
+    arrs = inputs.make_layer_inputs(spec, 3)
+    tiny(arrs)
+    from oracle import l4q_oracle as O
+    s, _ = host_qparams(spec, arrs, "asymm", 0.8)
+    assert s.max() < 2.0 ** -60 and s.min() > 0
+    rep, _, _ = run_case(spec, seed=3, shrink=0.8, mutate=tiny)
+    assert rep["clipped"] > 0
+
+
 def _random_cases(count=16, seed=2402):
     """Seeded draw of layer shapes: group a power of two, in-features a multiple of it, ranks on both sides of the
     fused epilogue's limit, every code width, both storage types, scale shrunk so that some weights clip."""
