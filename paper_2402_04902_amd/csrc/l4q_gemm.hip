@@ -1,7 +1,7 @@
 // bf16 MFMA GEMMs of the layer with a plain store epilogue (main loop: l4q_gemm_core.h).
 //
-//   forward   Y  [T,o] = X  [T,i] . Wq  [o,ipad]^T      both operands K-contiguous
-//   dX        dX [T,i] = dY [T,o] . WqT [i,opad]^T      both operands K-contiguous
+//   forward   Y  [T,o] = X  [T,i] . Wq  [o,ipad]^T      both operands K-contiguous; Wq in blocks of 32 k-values
+//   dX        dX [T,i] = dY [T,o] . WqT [i,opad]^T      both operands K-contiguous; WqT likewise
 //   dWq       dWq[o,i] = dY [T,o]^T . X [T,i]           both operands K-major (unfused backward only;
 //                                                       the fused form lives in l4q_bwd_fused.hip)
 // The workspace operand (Wq, WqT) is zero-padded along k to the 32-wide k-step; the caller's operand is
@@ -17,27 +17,17 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // Direct-to-LDS ring pipeline (l4q_gemm_core.h) + plain store epilogue.  Operands below 1 GiB.
 // ---------------------------------------------------------------------------------------------
-// One macro tile: main loop, then the store epilogue.
-template <class T, bool OUT_BF16, bool A_KM, bool B_KM, bool MASK_A_K>
-__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
-                                          int64_t ldb, int M, int N, int K, int K_a, void* __restrict__ Cout,
-                                          int64_t ldc, int m0, int n0, unsigned char* lds) {
-  gemm::Accum<T> acc;
-#pragma unroll
-  for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-    for (int b = 0; b < T::TN; ++b)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
-  gemm::mainloop<T, A_KM, B_KM, gemm::NoTailLoads, MASK_A_K>(A, lda, B, ldb, M, N, K, m0, n0, lds, acc,
-                                                            gemm::NoTailLoads(), K_a);
+// Store epilogue of a macro tile; `LDS_BYTES` of LDS at `lds` are free.
+template <class T, bool OUT_BF16, int LDS_BYTES>
+__device__ __forceinline__ void store_tile(gemm::Accum<T>& acc, int M, int N, void* __restrict__ Cout, int64_t ldc,
+                                           int m0, int n0, unsigned char* lds) {
   // bf16 output through LDS (free after the main loop): a lane holds 4 consecutive columns of 64 different
   // rows, which as direct stores are 16-byte pieces of 32 cache lines per instruction.  Each wave instead
   // parks its 128 x 128 block in its own LDS region (rows padded to 272 bytes) and writes it out as 16 bytes
   // per lane, 16 lanes per 256-byte row segment.  Needs 16-byte aligned rows: ldc % 8 == 0 and N % 8 == 0.
   constexpr int EP_ROW = T::WTN * 2 + 16;
   constexpr int EP_LPR = T::WTN / 8;  // lanes that cover a row of the wave's block with 16 bytes each
-  constexpr bool EP_FITS = OUT_BF16 && (T::WTN == 128 || T::WTN == 64) && T::NW * T::WTM * EP_ROW <= T::LDS_BYTES;
+  constexpr bool EP_FITS = OUT_BF16 && (T::WTN == 128 || T::WTN == 64) && T::NW * T::WTM * EP_ROW <= LDS_BYTES;
   if (EP_FITS && (ldc & 7) == 0 && (N & 7) == 0) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -85,7 +75,24 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t 
   }
 }
 
-template <class T, bool OUT_BF16, bool A_KM = false, bool B_KM = false, bool MASK_A_K = false>
+// One macro tile: main loop, then the store epilogue.
+template <class T, bool OUT_BF16, bool A_KM, bool B_KM, bool MASK_A_K, bool B_BLK>
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
+                                          int64_t ldb, int M, int N, int K, int K_a, void* __restrict__ Cout,
+                                          int64_t ldc, int m0, int n0, unsigned char* lds) {
+  gemm::Accum<T> acc;
+#pragma unroll
+  for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc.v[a][b][e] = 0.f;
+  gemm::mainloop<T, A_KM, B_KM, gemm::NoTailLoads, MASK_A_K, B_BLK>(A, lda, B, ldb, M, N, K, m0, n0, lds, acc,
+                                                                   gemm::NoTailLoads(), K_a);
+  store_tile<T, OUT_BF16, T::LDS_BYTES>(acc, M, N, Cout, ldc, m0, n0, lds);
+}
+
+template <class T, bool OUT_BF16, bool A_KM = false, bool B_KM = false, bool MASK_A_K = false, bool B_BLK = false>
 __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* __restrict__ A, int64_t lda,
                                                                    const bf16_t* __restrict__ B, int64_t ldb, int M,
                                                                    int N, int K, int K_a, void* __restrict__ Cout,
@@ -93,8 +100,8 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* 
   __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
   int tile_m, tile_n;
   gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-  gemm_tile<T, OUT_BF16, A_KM, B_KM, MASK_A_K>(A, lda, B, ldb, M, N, K, K_a, Cout, ldc, tile_m * T::BM,
-                                               tile_n * T::BN, lds);
+  gemm_tile<T, OUT_BF16, A_KM, B_KM, MASK_A_K, B_BLK>(A, lda, B, ldb, M, N, K, K_a, Cout, ldc, tile_m * T::BM,
+                                                      tile_n * T::BN, lds);
 }
 
 // Matrix-core-only loop with the GEMM's register shape (4 x 4 accumulator tiles, 8 fragments per wave) and
@@ -163,13 +170,13 @@ void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t 
   // rows of A end at K_a: where that is short of the k-step, the chunks past it are masked (a second instance, so
   // that the usual shapes do not pay for the selection)
   if (K_a == K)
-    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false, false>), dim3((unsigned)(tiles_m * tiles_n)),
-                       dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (int)K_a, (void*)C, ldc, tiles_m,
-                       tiles_n);
+    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false, false, true>),
+                       dim3((unsigned)(tiles_m * tiles_n)), dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K,
+                       (int)K_a, (void*)C, ldc, tiles_m, tiles_n);
   else
-    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false, true>), dim3((unsigned)(tiles_m * tiles_n)),
-                       dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K, (int)K_a, (void*)C, ldc, tiles_m,
-                       tiles_n);
+    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, true, false, false, true, true>),
+                       dim3((unsigned)(tiles_m * tiles_n)), dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M, (int)N, (int)K,
+                       (int)K_a, (void*)C, ldc, tiles_m, tiles_n);
 }
 
 void launch_gemm_bf16_kmajor_f32(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,

@@ -143,7 +143,13 @@ struct TailLoads {
 // follows a row in memory is the next row, not padding: the 16-byte chunks of the last stage that start at k >= K_a
 // get an out-of-range offset and read as zero, so that a NaN or Inf in row m + 1 cannot reach row m of the product
 // through 0 x Inf.
-template <class T, bool A_KM = false, bool B_KM = false, class Tail = NoTailLoads, bool MASK_A_K = false>
+// B_BLK (K-contiguous B only): operand B lies in memory in blocks of 32 k-values, B[k / 32][row][k % 32] with all N rows
+// of a k-block contiguous (ldb is not used): a stage of the tile is then 256 x 64 contiguous bytes and every wave-wide
+// load reads 1 KiB of consecutive addresses, eight whole cache lines, instead of sixteen separate half lines (measured:
+// 0.5 .. 1 % of the GEMM; what pays is that the merge + quantize pass, which writes Wq and Wq^T this way, stores whole
+// 1 KiB / 4 KiB runs).
+template <class T, bool A_KM = false, bool B_KM = false, class Tail = NoTailLoads, bool MASK_A_K = false,
+          bool B_BLK = false>
 __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t lda, const bf16_t* __restrict__ B,
                                          int64_t ldb, int M, int N, int K, int m0, int n0, unsigned char* lds,
                                          Accum<T>& acc, const Tail& tail = Tail(), int K_a = 0) {
@@ -160,7 +166,7 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
   const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<bf16_t*>(A), 0, (int)((int64_t)(A_KM ? K : M) * lda * 2), 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<bf16_t*>(B), 0, (int)((int64_t)(B_KM ? K : N) * ldb * 2), 0x00020000);
+      const_cast<bf16_t*>(B), 0, (int)((int64_t)(B_KM ? K : N) * (B_BLK ? (int64_t)K : ldb) * 2), 0x00020000);
 
   // per-lane source offsets (bytes) of the loads this wave issues each stage
   unsigned voffA[T::A_INSTR], voffB[T::B_INSTR];
@@ -179,10 +185,14 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
       }
     }
   };
+  static_assert(!B_BLK || (!B_KM && T::BK == 32), "blocked B: K-contiguous, 32-k stages");
   setup_voff(std::integral_constant<bool, A_KM>(), voffA, T::A_INSTR, lda, m0, M);
-  setup_voff(std::integral_constant<bool, B_KM>(), voffB, T::B_INSTR, ldb, n0, N);
+  // blocked B: a row is T::BK elements long inside its k-block, and a stage further is N rows further
+  setup_voff(std::integral_constant<bool, B_KM>(), voffB, T::B_INSTR, B_BLK ? (int64_t)T::BK : ldb, n0, N);
   const unsigned stage_bytes_a = A_KM ? (unsigned)(T::BK * lda * 2) : (unsigned)(T::BK * 2);
-  const unsigned stage_bytes_b = B_KM ? (unsigned)(T::BK * ldb * 2) : (unsigned)(T::BK * 2);
+  const unsigned stage_bytes_b = B_KM    ? (unsigned)(T::BK * ldb * 2)
+                                 : B_BLK ? (unsigned)N * (T::BK * 2)
+                                         : (unsigned)(T::BK * 2);
 
   // per-lane LDS offsets of the MFMA fragments.
   // K-contiguous: row (lane % 32) of a 32-row block, logical chunk 2 kk + lane / 32; block bases are
@@ -315,8 +325,9 @@ __device__ __forceinline__ void mainloop(const bf16_t* __restrict__ A, int64_t l
       }
     }
     auto issue_pair = [&](int stage0, int slot0, int slot1, int part) {
-      const unsigned k0 = stage0 < nk ? (unsigned)stage0 * stage_bytes_a : PAST_END_OFFSET;
-      const unsigned k1 = stage0 + 1 < nk ? (unsigned)(stage0 + 1) * stage_bytes_a : PAST_END_OFFSET;
+      const unsigned sb = part == 0 ? stage_bytes_a : stage_bytes_b;
+      const unsigned k0 = stage0 < nk ? (unsigned)stage0 * sb : PAST_END_OFFSET;
+      const unsigned k1 = stage0 + 1 < nk ? (unsigned)(stage0 + 1) * sb : PAST_END_OFFSET;
       unsigned char* base0 = lds + slot0 * T::STAGE;
       unsigned char* base1 = lds + slot1 * T::STAGE;
       if (part == 0) {

@@ -23,10 +23,14 @@ struct LayerDims {
 // Every output is optional (null = not written).
 template <class T>
 struct MergeQuantOut {
-  T* wq = nullptr;           // dequantized Wq [o, ld_wq], storage type
-  int64_t ld_wq = 0;
-  bf16_t* wqT = nullptr;     // Wq^T [i, ld_wqT] bf16; columns o..ld_wqT-1 are written as zeros (bf16 mode only)
-  int64_t ld_wqT = 0;        // multiple of 8
+  // bfloat16 storage: Wq and Wq^T are written for the matrix-core GEMM's B operand, in blocks of 32 k-values:
+  //   wq  [ld_wq / 32][o][32]:  Wq[p, j]  at ((j / 32) o + p) 32 + j % 32;  columns i..ld_wq-1 zeros
+  //   wqT [ld_wqT / 32][i][32]: Wq[p, j]  at ((p / 32) i + j) 32 + p % 32;  rows o..ld_wqT-1 zeros
+  // binary32 storage: wq [o, ld_wq] row-major.
+  T* wq = nullptr;
+  int64_t ld_wq = 0;         // multiple of 32 (bfloat16)
+  bf16_t* wqT = nullptr;
+  int64_t ld_wqT = 0;        // multiple of 32
   bf16_t* bT = nullptr;      // B^T [r, ld_wqT] bf16 for the fused backward; columns o..ld_wqT-1 zeros (bf16 mode only)
   uint16_t* fgrad = nullptr; // [o,i] binary16: d(Wq)/d(scale) = code - w in range, code (= Q_N or Q_P) when clipped;
                              // |value| <= 1/2 exactly when the element is in range
@@ -65,9 +69,10 @@ void launch_quant_errors(const LayerDims& d, const T* W0, const T* A, const T* B
 int device_compute_units();
 
 // ---- bf16 MFMA GEMM  C[M,N] = A[M,K] . B[N,K]^T, fp32 accumulate, bf16 output ----
-// A, B row-major and K-contiguous with leading dimensions lda, ldb (elements, multiples of 8).  K is rounded up to
-// 32; B must hold zeros for k in [K_a, K); rows of A end at K_a (a multiple of 8, K - 32 < K_a <= K) and are not
-// read past it.  Every operand below 1 GiB, N % 4 == 0, ldc % 4 == 0.
+// A row-major and K-contiguous with leading dimension lda (elements, a multiple of 8); rows of A end at K_a (a
+// multiple of 8, K - 32 < K_a <= K) and are not read past it.  B K-contiguous in blocks of 32 k-values,
+// B[k / 32][n][k % 32] with the N rows of a block contiguous (what the merge + quantize pass writes; ldb unused), K
+// rounded up to 32 with zeros for k in [K_a, K).  Every operand below 1 GiB, N % 4 == 0, ldc % 4 == 0.
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
                          int64_t K, int64_t K_a, bf16_t* C, int64_t ldc, hipStream_t stream);
 

@@ -89,9 +89,9 @@ struct WeightLoads {
 // B^T).  MODE 3: export (any of int8 codes, binary32 merged weight, mask; all [o, i]).
 // Grid: x = 256-column strips, y = partitions of the row blocks; wavefront w of a workgroup walks the row blocks
 // [nrb y / gridDim.y, nrb (y + 1) / gridDim.y) of its 64 columns.
-// Transposed tile of the backward form (two row blocks, 64 columns x 64 rows of bf16, column-major): pitch 144 bytes;
-// it takes the place of the sums tile once both row blocks have been streamed
-constexpr int MS_TPITCH = 144;
+// Transposed tile of the backward form (64 columns x 32 rows of bf16, column-major): pitch 80 bytes; it takes the place
+// of the sums tile once the row block has been streamed
+constexpr int MS_TPITCH = 80;
 static_assert(64 * MS_TPITCH <= MS_WAVE_LDS, "transposed tile aliases the sums tile");
 template <int MODE> constexpr int ms_wave_lds() { return MS_WAVE_LDS; }
 
@@ -111,11 +111,8 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
   const int jw = blockIdx.x * MS_COLS + wave * 64;  // first column of this wavefront
   const int i = (int)d.i, o = (int)d.o, r = d.r, g = d.g;
   const int G = i / g;
-  // the backward form pairs row blocks (64 rows of Wq^T are 128 contiguous bytes): its runs are whole pairs
-  const int unit = MODE == 2 ? 2 : 1;
-  const int nun = (nrb + unit - 1) / unit;
-  const int rb_begin = unit * (int)((int64_t)nun * blockIdx.y / gridDim.y);
-  const int rb_end = unit * (int)((int64_t)nun * (blockIdx.y + 1) / gridDim.y);
+  const int rb_begin = (int)((int64_t)nrb * blockIdx.y / gridDim.y);
+  const int rb_end = (int)((int64_t)nrb * (blockIdx.y + 1) / gridDim.y);
   if constexpr (MODE == 2) {
     // the first column strip also leaves B^T for its rows (zeros from o to the padded width)
     if (blockIdx.x == 0 && out.bT) {
@@ -131,7 +128,11 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
   }
   if (jw >= i) return;  // a whole wavefront past the last column (no workgroup barrier exists to miss)
 
-  // streaming role: 4 consecutive columns, 8 consecutive rows of the row block
+  // streaming role: 4 consecutive columns and 8 rows of the row block.  Forward: rows 4 rr + lane / 16, so that one
+  // store instruction covers 4 consecutive rows (Wq is written in blocks of 32 columns, [j / 32][p][j % 32]: 4 rows of a
+  // block are 256 contiguous bytes).  Backward / export: rows 8 (lane / 16) + rr, 8 consecutive rows per lane (a lane's
+  // column of the transposed tile is then 16 contiguous bytes).
+  constexpr int ROW_G = MODE == 1 ? 1 : 8, ROW_R = MODE == 1 ? 4 : 1;  // row = ROW_G (lane / 16) + ROW_R rr
   const int g16 = lane >> 4, c16 = lane & 15;
   const int j0 = jw + 4 * c16;
   const bool col_ok = j0 < i;
@@ -151,6 +152,8 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
   constexpr unsigned OOB = 0x80000000u;
   // outputs of the streaming layout
   const int ld_out = MODE == 1 ? (int)out.ld_wq : i;
+  // forward: byte offset of the lane's 4 columns in row 0 of their 32-column block of Wq
+  const unsigned wq_col_off = j0 < ld_out ? (unsigned)((((jw >> 5) + (c16 >> 3)) * o * 32 + 4 * (c16 & 7)) * 2) : OOB;
   const __amdgpu_buffer_rsrc_t rsOut = __builtin_amdgcn_make_buffer_rsrc(
       MODE == 1 ? (void*)out.wq : MODE == 2 ? (void*)out.fgrad : (void*)out.codes, 0,
       MODE == 3 ? o * i : o * ld_out * 2, 0x00020000);
@@ -183,18 +186,22 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
   };
   auto request_weights = [&](WeightLoads& L, int rb) {
     const int p0 = rb * 32;
-    // rows are valid in blocks of 8 (o % 8 == 0): this lane's 8 rows are all inside or all outside
-    const unsigned vw = rb < rb_end && p0 + 8 * g16 < o && col_ok ? (unsigned)(((p0 + 8 * g16) * i + j0) * 2) : OOB;
+    // rows are valid in blocks of 8 (o % 8 == 0).  Backward / export: this lane's 8 rows are all inside or all outside.
+    // Forward: rows 4 rr .. 4 rr + 3 of the block are inside or outside together (uniform in the wave): rows past o
+    // re-read the block's first rows, and nothing is stored for them.
+    const bool lane_rows_ok = MODE == 1 ? true : p0 + 8 * g16 < o;
+    const unsigned vw = rb < rb_end && lane_rows_ok && col_ok ? (unsigned)(((p0 + ROW_G * g16) * i + j0) * 2) : OOB;
 #pragma unroll
-    for (int rr = 0; rr < 8; ++rr) L.w0[rr] = __builtin_amdgcn_raw_buffer_load_b64(rsW0, (int)vw, rr * i * 2, 0);
+    for (int rr = 0; rr < 8; ++rr) {
+      const int rsel = MODE == 1 && p0 + ROW_R * rr >= o ? 0 : ROW_R * rr;
+      L.w0[rr] = __builtin_amdgcn_raw_buffer_load_b64(rsW0, (int)vw, rsel * i * 2, 0);
+    }
   };
 
   FactorLoads F;
-  uint32_t wqpack[2][4][4];  // backward form: dequantized weights of a pair of row blocks, [half][column][row pair]
-  auto compute = [&](WeightLoads& L, int rb, auto half_tag) {
-    constexpr int HALF = decltype(half_tag)::value;  // 0 / 1: first / second row block of a 64-row pair
+  auto compute = [&](WeightLoads& L, int rb) {
     const int p0 = rb * 32;
-    const bool rows_ok = p0 + 8 * g16 < o;
+    const bool rows_ok = MODE == 1 ? true : p0 + 8 * g16 < o;  // (forward: decided per row, uniformly)
     // ---- rank sums on the matrix core, k ascending
     f32x32_t sum;
 #pragma unroll
@@ -244,14 +251,16 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     // ---- stream: 8 rows x 4 columns per lane.  Forward: the padding columns i .. ld_wq - 1 are written as zeros.
-    const unsigned vo_out = rows_ok && j0 < ld_out ? (unsigned)(((p0 + 8 * g16) * ld_out + j0) * (MODE == 3 ? 1 : 2)) : OOB;
-    const int row_bytes = ld_out * (MODE == 3 ? 1 : 2);
+    const unsigned vo_out = MODE == 1 ? (wq_col_off == OOB ? OOB : wq_col_off + (unsigned)((p0 + g16) * 64))
+                            : rows_ok && j0 < ld_out ? (unsigned)(((p0 + 8 * g16) * ld_out + j0) * (MODE == 3 ? 1 : 2)) : OOB;
+    const int row_bytes = MODE == 1 ? ROW_R * 64 : ld_out * (MODE == 3 ? 1 : 2);
+    uint32_t wqpack[4][4];  // backward form: dequantized weights of the row block, [column][row pair]
     auto stream_rows = [&](auto fast_tag) {
       constexpr bool FAST = decltype(fast_tag)::value;
       float wqprev[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int rr = 0; rr < 8; ++rr) {
-        const int row = 8 * g16 + rr;
+        const int row = ROW_G * g16 + ROW_R * rr;
         const float4 acc = *reinterpret_cast<const float4*>(S + row * MS_SPITCH + 4 * c16);
         const float4 tab = *reinterpret_cast<const float4*>(S + row * MS_SPITCH + 64 + 4 * grp_lane);
         const float s = tab.x, b = tab.y, rc = tab.z, hi = tab.w;
@@ -276,7 +285,8 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
         }
         if (MODE == 1) {
           const u32x2 v = {col_ok ? pack_bf16x2(wq[0], wq[1]) : 0u, col_ok ? pack_bf16x2(wq[2], wq[3]) : 0u};
-          __builtin_amdgcn_raw_buffer_store_b64(v, rsOut, (int)vo_out, rr * row_bytes, 0);
+          if (p0 + ROW_R * rr < o)  // uniform
+            __builtin_amdgcn_raw_buffer_store_b64(v, rsOut, (int)vo_out, rr * row_bytes, 0);
         } else if (MODE == 2) {
           if (want_f) {
             typedef _Float16 h4 __attribute__((ext_vector_type(4)));
@@ -288,7 +298,7 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             if ((rr & 1) == 0) wqprev[c] = wq[c];
-            else wqpack[HALF][c][rr >> 1] = rows_ok ? pack_bf16x2(wqprev[c], wq[c]) : 0u;
+            else wqpack[c][rr >> 1] = rows_ok ? pack_bf16x2(wqprev[c], wq[c]) : 0u;
           }
         } else {
           if (out.codes) __builtin_amdgcn_raw_buffer_store_b32(cpack, rsOut, (int)vo_out, rr * row_bytes, 0);
@@ -306,27 +316,25 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
     __builtin_amdgcn_wave_barrier();  // every lane's reads of the sums tile are done: it may be overwritten
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    if constexpr (MODE == 2 && HALF == 1) {
-      // ---- Wq^T of the pair: through LDS, column-major, then 128 contiguous bytes (64 rows) per column
+    if constexpr (MODE == 2) {
+      // ---- Wq^T in blocks of 32 rows, [p / 32][j][p % 32]: this row block's 64 columns are 4 KiB of consecutive
+      //      addresses.  Through LDS, column-major, then 16 bytes per lane, 1 KiB per store instruction.
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const u32x4 v = {wqpack[h][c][0], wqpack[h][c][1], wqpack[h][c][2], wqpack[h][c][3]};
-          *reinterpret_cast<u32x4*>(Tt + (4 * c16 + c) * MS_TPITCH + (32 * h + 8 * g16) * 2) = v;
-        }
+      for (int c = 0; c < 4; ++c) {
+        const u32x4 v = {wqpack[c][0], wqpack[c][1], wqpack[c][2], wqpack[c][3]};
+        *reinterpret_cast<u32x4*>(Tt + (4 * c16 + c) * MS_TPITCH + 16 * g16) = v;
+      }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       const int ld = (int)out.ld_wqT;
       const __amdgpu_buffer_rsrc_t rsT = __builtin_amdgcn_make_buffer_rsrc(out.wqT, 0, i * ld * 2, 0x00020000);
-      const int ch = lane & 7;
-      const int p = p0 - 32 + 8 * ch;
+      const int ch = lane & 3;
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int col = it * 8 + (lane >> 3);
+      for (int it = 0; it < 4; ++it) {
+        const int col = it * 16 + (lane >> 2);
         const u32x4 v = *reinterpret_cast<const u32x4*>(Tt + col * MS_TPITCH + ch * 16);
-        const unsigned vo = jw + col < i && p < ld ? (unsigned)(((jw + col) * ld + p) * 2) : OOB;
+        const unsigned vo = jw + col < i ? (unsigned)(((rb * i + jw + col) * 32 + 8 * ch) * 2) : OOB;
         __builtin_amdgcn_raw_buffer_store_b128(v, rsT, (int)vo, 0, 0);
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -335,38 +343,25 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
     }
   };
 
-  // Forward / export: row blocks alternate between two register sets, so that the weight rows of the next row block
-  // are in flight while this one is worked on.
+  // Row blocks alternate between two register sets, so that the weight rows of the next row block are in flight while
+  // this one is worked on.
   int rb = rb_begin;
   request_factors(F, rb);
-  if constexpr (MODE == 2) {
-    // one register set (the pair's dequantized weights take the room of a second one): a row block's weight rows are
-    // requested when its matrix ops start.  Whole pairs: the odd one out reads nothing and writes the zero padding.
-    WeightLoads L;
-    while (rb < rb_end) {
-      request_weights(L, rb);
-      compute(L, rb, std::integral_constant<int, 0>{});
-      request_weights(L, rb + 1);
-      compute(L, rb + 1, std::integral_constant<int, 1>{});
-      rb += 2;
-    }
-  } else {
-    WeightLoads L0, L1;
-    request_weights(L0, rb);
-    while (rb < rb_end) {
-      request_weights(L1, rb + 1);
-      compute(L0, rb, std::integral_constant<int, 0>{});
-      if (++rb >= rb_end) break;
-      request_weights(L0, rb + 1);
-      compute(L1, rb, std::integral_constant<int, 1>{});
-      ++rb;
-    }
+  WeightLoads L0, L1;
+  request_weights(L0, rb);
+  while (rb < rb_end) {
+    request_weights(L1, rb + 1);
+    compute(L0, rb);
+    if (++rb >= rb_end) break;
+    request_weights(L0, rb + 1);
+    compute(L1, rb);
+    ++rb;
   }
 #endif
 }
 
-// Forward and export: 4 workgroups (16 wavefronts, 144 KiB of LDS) per compute unit.  Backward: 3 (12 wavefronts,
-// 168 registers each, 168 KiB of LDS asked for: its transposed tile and the wider streaming phase need the room.
+// Forward and export: 4 workgroups (16 wavefronts, 144 KiB of LDS) per compute unit.  Backward: MS_BWD_WAVES (the
+// dequantized weights of a row block wait in registers for the transposition: 152 registers per lane).
 template <bool GAMMA_POW2>
 __global__ __launch_bounds__(MS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void merge_quant_stream_fwd_kernel(LayerDims d, const bf16_t* __restrict__ W0, const bf16_t* __restrict__ A,
@@ -448,7 +443,8 @@ bool merge_quant_stream_supported(const LayerDims& d, const MergeQuantOut<bf16_t
   const bool fwd = out.wq && !out.wqT && !out.fgrad && !misc;
   const bool bwd = !out.wq && out.wqT && !misc;
   const bool exp = !out.wq && !out.wqT && !out.fgrad && misc;
-  return (fwd || bwd || exp) && d.r % 8 == 0 && d.g >= 32;
+  const bool blocks = (!out.wq || out.ld_wq % 32 == 0) && (!out.wqT || out.ld_wqT % 32 == 0);
+  return (fwd || bwd || exp) && blocks && d.r % 8 == 0 && d.g >= 32;
 }
 
 void launch_merge_quant_stream(const LayerDims& d, const bf16_t* W0, const bf16_t* A, const bf16_t* B,
@@ -461,8 +457,7 @@ void launch_merge_quant_stream(const LayerDims& d, const bf16_t* W0, const bf16_
   const int strips = (int)((d.i + MS_COLS - 1) / MS_COLS);
   int parts = (mode == 2 ? MS_BWD_WAVES : 4) * device_compute_units() / strips;
   if (parts < 1) parts = 1;
-  const int units = mode == 2 ? (nrb + 1) / 2 : nrb;
-  if (parts > units) parts = units;
+  if (parts > nrb) parts = nrb;
   dim3 grid((unsigned)strips, (unsigned)parts);
   // gamma acc is exact when gamma is a power of two >= 1 (no underflow of the product)
   const uint32_t gb = __builtin_bit_cast(uint32_t, d.gamma);

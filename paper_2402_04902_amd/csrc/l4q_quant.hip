@@ -291,11 +291,12 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
     if (want_wq && (MODE == 1 || out.wq) && p < d.o) {
       // the dequantized weight is zero-padded up to its leading dimension (k-step of the GEMM)
       if constexpr (BUF) {  // one store per lane: the values, zeros in the padding, dropped (offset out of range) past it
+        // bf16: Wq lies in blocks of 32 columns, [j / 32][p][j % 32] (the GEMM's blocked B operand; ld_wq % 32 == 0)
         const __amdgpu_buffer_rsrc_t rsrcWq = __builtin_amdgcn_make_buffer_rsrc(
             out.wq, 0, (int)(d.o * out.ld_wq * 2), 0x00020000);
         const u32x2 v = {col_ok ? pack_bf16x2(wqv[0], wqv[1]) : 0u, col_ok ? pack_bf16x2(wqv[2], wqv[3]) : 0u};
-        const unsigned voff = j0 < out.ld_wq ? j32 * 2u : 0x80000000u;
-        __builtin_amdgcn_raw_buffer_store_b64(v, rsrcWq, (int)voff, (int)(p * out.ld_wq * 2), 0);
+        const unsigned voff = j0 < out.ld_wq ? ((j32 >> 5) * (unsigned)d.o * 32u + (j32 & 31u)) * 2u : 0x80000000u;
+        __builtin_amdgcn_raw_buffer_store_b64(v, rsrcWq, (int)voff, (int)(p * 64), 0);
       } else {
         if (col_ok) store4((out.wq + p * out.ld_wq) + j32, wqv);
         else if (j0 < out.ld_wq) store4((out.wq + p * out.ld_wq) + j32, zero4);
@@ -359,7 +360,8 @@ __global__ __launch_bounds__(MQ_THREADS) void merge_quant_tile_kernel(LayerDims 
       if (j < d.i && p < out.ld_wqT) {
         uint4 v = *reinterpret_cast<const uint4*>(tile + jr * MQ_TROW + ch * 16);
         if (p >= d.o) v = make_uint4(0u, 0u, 0u, 0u);
-        *reinterpret_cast<uint4*>(out.wqT + j * out.ld_wqT + p) = v;
+        // Wq^T lies in blocks of 32 rows of Wq, [p / 32][j][p % 32] (the GEMM's blocked B operand; ld_wqT % 32 == 0)
+        *reinterpret_cast<uint4*>(out.wqT + ((p >> 5) * d.i + j) * 32 + (p & 31)) = v;
       }
     }
   }

@@ -146,8 +146,9 @@ def check_workspace_state(spec, layer, dec, w32, s, b, fused):
     bit for bit against the oracle's binary32 chain.  The training path takes its discrete decisions in kernels of its
     own (not the export kernel check_discrete looks at), and they reach the outputs only through floating-point sums;
     here they are looked at directly.  Workspace layout (documented with the library's design): forward Wq [o, ipad]
-    bfloat16 first; backward Wq^T [i, opad] bfloat16 first, then (fused weight-gradient kernel only) the binary16
-    factor d(Wq)/d(scale) [o, i], each 256-byte aligned; ipad / opad = i / o rounded up to 32.
+    bfloat16 first, stored in blocks of 32 columns as [ipad / 32][o][32]; backward Wq^T [i, opad] bfloat16 first, in
+    blocks of 32 rows of Wq as [opad / 32][i][32], then (fused weight-gradient kernel only) the binary16 factor
+    d(Wq)/d(scale) [o, i] row-major, each 256-byte aligned; ipad / opad = i / o rounded up to 32.
     Call after layer.forward() and layer.backward() in this order, synchronised."""
     import torch
     o, i = spec.out_features, spec.in_features
@@ -162,7 +163,8 @@ def check_workspace_state(spec, layer, dec, w32, s, b, fused):
     wq_bits = inputs.bf16_bits(inputs.round_to_bf16(wq32))
     # backward workspace (the last call): Wq^T and the factor
     ws = layer.ws
-    wqT = ws[: i * opad * 2].view(torch.int16).reshape(i, opad).cpu().numpy().view(np.uint16)
+    wqT = ws[: i * opad * 2].view(torch.int16).reshape(opad // 32, i, 32).cpu().numpy().view(np.uint16)
+    wqT = np.ascontiguousarray(wqT.transpose(1, 0, 2)).reshape(i, opad)
     assert np.array_equal(wqT[:, :o], wq_bits.T), f"{(wqT[:, :o] != wq_bits.T).sum()} elements of Wq^T differ"
     assert not wqT[:, o:].any(), "padding of Wq^T is not zero"
     if fused:
@@ -173,6 +175,7 @@ def check_workspace_state(spec, layer, dec, w32, s, b, fused):
     # forward workspace: run the forward pass once more (it overwrites the workspace)
     layer.forward()
     torch.cuda.synchronize()
-    wq = ws[: o * ipad * 2].view(torch.int16).reshape(o, ipad).cpu().numpy().view(np.uint16)
+    wq = ws[: o * ipad * 2].view(torch.int16).reshape(ipad // 32, o, 32).cpu().numpy().view(np.uint16)
+    wq = np.ascontiguousarray(wq.transpose(1, 0, 2)).reshape(o, ipad)
     assert np.array_equal(wq[:, :i], wq_bits), f"{(wq[:, :i] != wq_bits).sum()} elements of Wq differ"
     assert not wq[:, i:].any(), "padding of Wq is not zero"
