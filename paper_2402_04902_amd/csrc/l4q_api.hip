@@ -71,7 +71,7 @@ struct Carver {
 };
 
 struct FwdWs {
-  void* wq;      // [o,ipad] storage type; ipad = i rounded up to the GEMM k-step in bf16 mode
+  void* wq;      // [o,ipad] storage type; ipad = i rounded up to the GEMM k-step in bf16 mode (bf16: in blocks of 32 columns)
   int64_t ipad;
   size_t bytes;
 };
@@ -82,7 +82,7 @@ struct BwdWs {
   float* rawA;       // [r,i]                      (bf16 masked)
   float* rawB;       // [o,r]                      (bf16 masked)
   float* wq32;       // [o,i]                      (binary32 mode)
-  bf16_t* wqT;       // [i,opad]                   (bf16)
+  bf16_t* wqT;       // [i,opad], in blocks of 32  (bf16)
   uint16_t* fgrad;   // [o,i] binary16             (bf16 fused)
   bf16_t* bT;        // [r,opad]                   (bf16 fused)
   float* dB_part;    // [2 tiles_n, o, r]          (bf16 fused)
@@ -230,14 +230,14 @@ void merge_quant_bf16(const LayerDims& d, const bf16_t* W0, const bf16_t* A, con
 }
 
 struct QlFwdWs {
-  void* wq;       // [o, ipad] storage type
+  void* wq;       // [o, ipad] storage type (bf16: in blocks of 32 columns)
   float* xa;      // [T, r]
   int64_t ipad;
   size_t bytes;
 };
 struct QlBwdWs {
   float* wq32;    // [o, i]      (binary32 mode)
-  bf16_t* wqT;    // [i, opad]   (bf16)
+  bf16_t* wqT;    // [i, opad], in blocks of 32   (bf16)
   float* dwq;     // [o, i]      the stored weight gradient
   float* dyb;     // [T, r]
   float* xa;      // [T, r]

@@ -12,7 +12,9 @@
 //  * rank sums sum_k B[p,k] A[k,j] on the matrix core as a chain of K = 1 binary32 ops, one per k in ascending order:
 //    each step is RN(acc + b a) with the bfloat16 product exact, i.e. the stated sequential order bit for bit.
 //    The accumulators come out one column per lane and pass through LDS once to become 4 consecutive columns of 8
-//    rows per lane: 16 lanes then cover 128 contiguous bytes of a weight row, a cache line, in every load and store.
+//    rows per lane: 16 lanes then cover 128 contiguous bytes of a weight row, a cache line, in every load.
+//  * Wq and Wq^T leave in the blocked layout the GEMM reads (32 k-values of all rows together): the forward form
+//    stores 256-byte runs, the backward form turns the row block over in LDS and stores 1 KiB runs.
 //  * the division w = (Wc - b) / s is not the 11-instruction IEEE expansion per weight.  One lane per (row, group)
 //    loads s and b, forms the correctly rounded reciprocal r = RN(1 / s) (hardware estimate, one Newton step, then the
 //    choice among the result and its two neighbours by the exact residual 1 - s r), and parks (s, b, r, 1024 s) in
@@ -85,8 +87,8 @@ struct WeightLoads {
   u32x2 w0[8];      // streaming role: W0[p0 + 8 (lane / 16) + rr, 4 columns]
 };
 
-// MODE 1: forward (dequantized Wq [o, ld_wq]).  MODE 2: backward (Wq^T [i, ld_wqT]; optionally the factor [o, i] and
-// B^T).  MODE 3: export (any of int8 codes, binary32 merged weight, mask; all [o, i]).
+// MODE 1: forward (dequantized Wq, [ld_wq / 32][o][32]).  MODE 2: backward (Wq^T, [ld_wqT / 32][i][32]; optionally the
+// factor [o, i] and B^T).  MODE 3: export (any of int8 codes, binary32 merged weight, mask; all [o, i]).
 // Grid: x = 256-column strips, y = partitions of the row blocks; wavefront w of a workgroup walks the row blocks
 // [nrb y / gridDim.y, nrb (y + 1) / gridDim.y) of its 64 columns.
 // Transposed tile of the backward form (64 columns x 32 rows of bf16, column-major): pitch 80 bytes; it takes the place
@@ -255,8 +257,13 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
                             : rows_ok && j0 < ld_out ? (unsigned)(((p0 + 8 * g16) * ld_out + j0) * (MODE == 3 ? 1 : 2)) : OOB;
     const int row_bytes = MODE == 1 ? ROW_R * 64 : ld_out * (MODE == 3 ? 1 : 2);
     uint32_t wqpack[4][4];  // backward form: dequantized weights of the row block, [column][row pair]
-    auto stream_rows = [&](auto fast_tag) {
+    // (the padding columns are zeroed with a mask, not a select: a select over the whole quantizer chain is compiled
+    // into a branch per row, which cuts the eight rows into pieces that cannot be scheduled together; for the same
+    // reason the row guard of the forward form exists only in the instance for the matrix's last, partial row block)
+    const uint32_t colmask = col_ok ? 0xFFFFFFFFu : 0u;
+    auto stream_rows = [&](auto fast_tag, auto guard_tag) {
       constexpr bool FAST = decltype(fast_tag)::value;
+      constexpr bool GUARD_ROWS = decltype(guard_tag)::value;
       float wqprev[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int rr = 0; rr < 8; ++rr) {
@@ -284,8 +291,8 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
           }
         }
         if (MODE == 1) {
-          const u32x2 v = {col_ok ? pack_bf16x2(wq[0], wq[1]) : 0u, col_ok ? pack_bf16x2(wq[2], wq[3]) : 0u};
-          if (p0 + ROW_R * rr < o)  // uniform
+          const u32x2 v = {pack_bf16x2(wq[0], wq[1]) & colmask, pack_bf16x2(wq[2], wq[3]) & colmask};
+          if (!GUARD_ROWS || p0 + ROW_R * rr < o)  // uniform
             __builtin_amdgcn_raw_buffer_store_b64(v, rsOut, (int)vo_out, rr * row_bytes, 0);
         } else if (MODE == 2) {
           if (want_f) {
@@ -310,8 +317,13 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
         }
       }
     };
-    if (!slow) stream_rows(std::true_type{});
-    else stream_rows(std::false_type{});
+    if (MODE == 1 && p0 + 32 > o) {  // last, partial row block of the forward form
+      if (!slow) stream_rows(std::true_type{}, std::true_type{});
+      else stream_rows(std::false_type{}, std::true_type{});
+    } else {
+      if (!slow) stream_rows(std::true_type{}, std::false_type{});
+      else stream_rows(std::false_type{}, std::false_type{});
+    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // every lane's reads of the sums tile are done: it may be overwritten
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
