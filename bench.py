@@ -362,6 +362,9 @@ def main() -> int:
             "C4_llama7b_up_3bit_g64": measure_config(c4[2:3], 41),
             "C4_llama7b_up_3bit_g256": measure_config(c4[3:4], 42),
             "C5_mistral7b_seven_layers_T8192": measure_config(inputs.config5(), 50),
+            # the headline layers at token counts with one and four tile rows (forward / dX products split along k)
+            "C3_llama7b_mlp_T256": measure_config([sp.with_(tokens=256) for sp in inputs.config3()], 60, steps=10),
+            "C3_llama7b_mlp_T1024": measure_config([sp.with_(tokens=1024) for sp in inputs.config3()], 61, steps=10),
         }
     out["vendor_gemm_reference"] = {"what": "the step's six GEMMs alone via torch.matmul (hipBLASLt), bf16",
                                     "ms": vendor_ms, "TFLOP_per_s": flops_per_step / (vendor_ms * 1e-3) / 1e12,

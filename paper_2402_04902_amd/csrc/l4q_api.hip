@@ -72,6 +72,7 @@ struct Carver {
 
 struct FwdWs {
   void* wq;      // [o,ipad] storage type; ipad = i rounded up to the GEMM k-step in bf16 mode (bf16: in blocks of 32 columns)
+  float* splitk;  // [slices][T][o] binary32 tiles of the forward product's k-slices (bf16, few tokens), else null
   int64_t ipad;
   size_t bytes;
 };
@@ -88,6 +89,7 @@ struct BwdWs {
   float* dB_part;    // [2 tiles_n, o, r]          (bf16 fused)
   float* dwq;        // [o,i]                      (binary32 mode, bf16 unfused)
   float* dA_part;    // [tiles_m or ceil(o/kDaRowBlock), r, i]
+  float* splitk;     // [slices][T][i] binary32 tiles of the dX product's k-slices (bf16, few tokens), else null
   int64_t opad;
   int tiles_m, tiles_n;
   size_t bytes;
@@ -99,6 +101,11 @@ FwdWs carve_fwd(const l4q_desc* d, void* ws) {
   w.ipad = d->dtype == L4Q_DTYPE_BF16 ? (int64_t)align_up((size_t)d->in_features, 32) : d->in_features;
   const size_t n = (size_t)d->out_features * (size_t)w.ipad;
   w.wq = d->dtype == L4Q_DTYPE_BF16 ? (void*)c.take<bf16_t>(n) : (void*)c.take<float>(n);
+  w.splitk = nullptr;
+  if (d->dtype == L4Q_DTYPE_BF16) {
+    const int slices = l4q::gemm_nt_splitk_slices(d->tokens, d->out_features, w.ipad);
+    if (slices > 1) w.splitk = c.take<float>((size_t)slices * (size_t)d->tokens * (size_t)d->out_features);
+  }
   w.bytes = c.used;
   return w;
 }
@@ -134,6 +141,10 @@ BwdWs carve_bwd(const l4q_desc* d, void* ws) {
     w.wq32 = c.take<float>(n);
     w.dwq = c.take<float>(n);
     w.dA_part = c.take<float>(nrb * r * i);
+  }
+  if (d->dtype == L4Q_DTYPE_BF16) {  // (last: the arrays above keep their places whatever the token count)
+    const int slices = l4q::gemm_nt_splitk_slices(d->tokens, d->in_features, w.opad);
+    if (slices > 1) w.splitk = c.take<float>((size_t)slices * (size_t)d->tokens * i);
   }
   w.bytes = c.used;
   return w;
@@ -205,10 +216,11 @@ struct Timed {
 };
 
 // Enqueue one bf16 GEMM (rows of A end at K_algorithmic, the padded operand B at K).
+// `splitk`: room for the k-slices' tiles where the product has too few tiles for the chip (or null: one pass).
 void gemm_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
-             int64_t K_algorithmic, bf16_t* C, int64_t ldc, hipStream_t stream) {
+             int64_t K_algorithmic, bf16_t* C, int64_t ldc, hipStream_t stream, float* splitk = nullptr) {
   Timed t(stream, kKindGemm, 2.0 * (double)M * (double)N * (double)K_algorithmic);
-  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, K_algorithmic, C, ldc, stream);
+  l4q::launch_gemm_bf16_nt(A, lda, B, ldb, M, N, K, K_algorithmic, C, ldc, stream, splitk);
 }
 
 // The fused weight-gradient kernel is a GEMM launch too: time it the same way.
@@ -323,7 +335,7 @@ int l4q_forward(const l4q_desc* desc, const void* X, const void* W0, const void*
     mq.wq = wq;
     mq.ld_wq = w.ipad;
     merge_quant_bf16(d, (const bf16_t*)W0, (const bf16_t*)A, (const bf16_t*)B, scale, zero, mq, stream);
-    gemm_nt((const bf16_t*)X, d.i, wq, w.ipad, d.T, d.o, w.ipad, d.i, (bf16_t*)Y, d.o, stream);
+    gemm_nt((const bf16_t*)X, d.i, wq, w.ipad, d.T, d.o, w.ipad, d.i, (bf16_t*)Y, d.o, stream, w.splitk);
   } else {
     float* wq = static_cast<float*>(w.wq);
     l4q::MergeQuantOut<float> mq;
@@ -381,7 +393,7 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
       l4q::launch_reduce_two_partials(w.rawA, 1, (int64_t)d.r * d.i, dA, w.rawB, 1, d.o * d.r, dB, d.gamma,
                                       d.accumulate, stream);
     }
-    gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream);
+    gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream, w.splitk);
     if (!w.fused && !w.masked) {
       l4q::launch_gemm_bf16_kmajor_f32((const bf16_t*)dY, d.o, (const bf16_t*)X, d.i, d.o, d.i, d.T, w.dwq, d.i, stream);
       l4q::launch_quant_grads<bf16_t>(d, W0b, Ab, Bb, scale, zero, w.dwq, dscale, dzero, dB, stream);

@@ -104,6 +104,42 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* 
                                                       tile_n * T::BN, lds);
 }
 
+// One (tile, k-slice) of the forward / dX product with few tiles: slice blockIdx.y of gridDim.y takes a run of whole
+// stage pairs of the k range and leaves its binary32 tile in part[slice][M][N].  B in blocks of 32 k-values.
+template <class T, bool MASK_A_K>
+__global__ __launch_bounds__(T::NT) void gemm_bf16_nt_splitk_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                     const bf16_t* __restrict__ B, int M, int N, int K,
+                                                                     int K_a, float* __restrict__ part, int tiles_m,
+                                                                     int tiles_n) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+  int tile_m, tile_n;
+  gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int slices = gridDim.y, slice = blockIdx.y;
+  const int pairs = ((K + T::BK - 1) / T::BK + 1) / 2;
+  const int k0 = (int)((int64_t)pairs * slice / slices) * (2 * T::BK);
+  int k1 = (int)((int64_t)pairs * (slice + 1) / slices) * (2 * T::BK);
+  if (k1 > K) k1 = K;
+  // rows of A end at K_a: inside the last slice, at or past the end of every other
+  const int ka = (K_a < k1 ? K_a : k1) - k0;
+  gemm_tile<T, false, false, false, MASK_A_K, true>(A + k0, lda, B + (int64_t)(k0 / T::BK) * N * T::BK, 0, M, N, k1 - k0, ka,
+                                                    part + (int64_t)slice * M * N, N, tile_m * T::BM, tile_n * T::BN, lds);
+}
+
+// C[m, n] = bf16(sum over the slices, in slice order, of part[slice][m][n]); N % 4 == 0, four columns per thread.
+__global__ __launch_bounds__(256) void splitk_sum_kernel(const float* __restrict__ part, int slices, int64_t M, int64_t N,
+                                                         bf16_t* __restrict__ C, int64_t ldc) {
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (q >= M * N / 4) return;
+  float4 v = reinterpret_cast<const float4*>(part)[q];
+  for (int s = 1; s < slices; ++s) {
+    const float4 w = reinterpret_cast<const float4*>(part + (int64_t)s * M * N)[q];
+    v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+  }
+  const int64_t m = q * 4 / N, n = q * 4 - m * N;
+  const float f[4] = {v.x, v.y, v.z, v.w};
+  store4(C + m * ldc + n, f);
+}
+
 // Matrix-core-only loop with the GEMM's register shape (4 x 4 accumulator tiles, 8 fragments per wave) and
 // no memory traffic inside the loop: what the matrix pipeline sustains on this chip for the given data.
 __global__ __launch_bounds__(256) void mfma_probe_kernel(const bf16_t* __restrict__ data, int iterations,
@@ -161,12 +197,42 @@ int device_compute_units() {
   return cached[dev];
 }
 
+// Slices of the k range for a product with few tiles: as many as put a workgroup on every compute unit, each at
+// least four stage pairs (256 k) long, at most 8, and no more than keep the partial tiles (slices x M x N x 4 bytes,
+// written and read once) within the size of operand B (N x K x 2 bytes).
+int gemm_nt_splitk_slices(int64_t M, int64_t N, int64_t K) {
+  typedef gemm::Tile<256, 256, 32, 5, true, 4> F;
+  const int64_t tiles = ((M + F::BM - 1) / F::BM) * ((N + F::BN - 1) / F::BN);
+  const int64_t cus = device_compute_units();
+  if (tiles <= 0 || 2 * tiles > cus) return 1;
+  const int64_t pairs = ((K + F::BK - 1) / F::BK + 1) / 2;
+  int64_t s = cus / tiles;
+  if (s > pairs / 4) s = pairs / 4;
+  if (s > 8) s = 8;
+  if (s > K / (2 * M)) s = K / (2 * M);
+  return s < 1 ? 1 : (int)s;
+}
+
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
-                         int64_t K, int64_t K_a, bf16_t* C, int64_t ldc, hipStream_t stream) {
+                         int64_t K, int64_t K_a, bf16_t* C, int64_t ldc, hipStream_t stream, float* partial) {
   // K-contiguous operands: stages loaded in cache-line pairs; 8 waves (2 x 4, two per SIMD, 128 x 64 each): a second
   // wave on the SIMD keeps the matrix pipe busy while the first waits for a barrier or for operands (1.5 % over 2 x 2)
   typedef gemm::Tile<256, 256, 32, 5, true, 4> F;
   const int tiles_m = (int)((M + F::BM - 1) / F::BM), tiles_n = (int)((N + F::BN - 1) / F::BN);
+  const int slices = partial ? gemm_nt_splitk_slices(M, N, K) : 1;
+  if (slices > 1) {
+    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)slices);
+    if (K_a == K)
+      hipLaunchKernelGGL((gemm_bf16_nt_splitk_kernel<F, false>), grid, dim3(F::NT), 0, stream, A, lda, B, (int)M, (int)N,
+                         (int)K, (int)K_a, partial, tiles_m, tiles_n);
+    else
+      hipLaunchKernelGGL((gemm_bf16_nt_splitk_kernel<F, true>), grid, dim3(F::NT), 0, stream, A, lda, B, (int)M, (int)N,
+                         (int)K, (int)K_a, partial, tiles_m, tiles_n);
+    const int64_t quads = M * N / 4;
+    hipLaunchKernelGGL(splitk_sum_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, partial, slices,
+                       M, N, C, ldc);
+    return;
+  }
   // rows of A end at K_a: where that is short of the k-step, the chunks past it are masked (a second instance, so
   // that the usual shapes do not pay for the selection)
   if (K_a == K)

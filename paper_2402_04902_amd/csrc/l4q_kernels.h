@@ -73,8 +73,14 @@ int device_compute_units();
 // multiple of 8, K - 32 < K_a <= K) and are not read past it.  B K-contiguous in blocks of 32 k-values,
 // B[k / 32][n][k % 32] with the N rows of a block contiguous (what the merge + quantize pass writes; ldb unused), K
 // rounded up to 32 with zeros for k in [K_a, K).  Every operand below 1 GiB, N % 4 == 0, ldc % 4 == 0.
+// Few tiles (small M: few tokens): the k range is split into `slices` = gemm_nt_splitk_slices(M, N, K) > 1 runs of
+// whole stage pairs, one workgroup per (tile, slice); the slices' binary32 tiles go to `partial`
+// [slices][M][N] and a second launch adds them in slice order (the result does not depend on the run) and rounds to
+// bf16.  With `partial` == nullptr, or one slice, the product is a single pass.
+int gemm_nt_splitk_slices(int64_t M, int64_t N, int64_t K);
 void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, int64_t M, int64_t N,
-                         int64_t K, int64_t K_a, bf16_t* C, int64_t ldc, hipStream_t stream);
+                         int64_t K, int64_t K_a, bf16_t* C, int64_t ldc, hipStream_t stream,
+                         float* partial = nullptr);
 
 // ---- matrix-core-only probe: `workgroups` x 4 waves x `iterations` x 16 MFMA 32x32x16 on fragments taken from the
 // first 64 KiB of `data`; sink [workgroups * 256] floats.  Returns the FLOPs the launch performs. ----

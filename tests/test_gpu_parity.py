@@ -241,6 +241,23 @@ def test_larger_model_shapes():
     run_case(LayerSpec("down_28672x8192_T64", 64, 28672, 8192, 16, 32.0, 4, 128, DTYPE_BF16), seed=70, shrink=0.8)
 
 
+@pytest.mark.parametrize("tokens", [256, 200, 1000])
+def test_bf16_few_tokens_split_k(tokens):
+    """Benchmark layers at token counts whose forward / dX products have too few tiles for the chip (one to four tile
+    rows): the k range is split over workgroups and the slices are added in a fixed order.  200 and 1000: ragged last
+    tile row.  Run twice: the same bits."""
+    import torch
+    for idx, (o, i) in enumerate(((11008, 4096), (4096, 11008))):
+        spec = LayerSpec(f"split_k_{o}x{i}_T{tokens}", tokens, i, o, 16, 32.0, 4, 128, DTYPE_BF16)
+        _, layer, _ = run_case(spec, seed=90 + idx, shrink=0.8, discrete=False)
+        y1, dx1 = layer.Y.clone(), layer.dX.clone()
+        layer.forward()
+        layer.backward()
+        torch.cuda.synchronize()
+        assert torch.equal(y1.view(torch.int16), layer.Y.view(torch.int16))
+        assert torch.equal(dx1.view(torch.int16), layer.dX.view(torch.int16))
+
+
 # ------------------------------------------------------------------ initialisation kernel
 
 @pytest.mark.parametrize("dtype", [DTYPE_F32, DTYPE_BF16])
