@@ -24,7 +24,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 # HBM-side bytes per GEMM launch (mean over the 4 plain + 2 fused launches of a step) from the
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/l4q_layer__llama7b_mlp_T4096.md
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = (2 * (588e6 + 90e6) + 2 * (546e6 + 34e6) + 2 * (718e6 + 39e6)) / 6
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = (2 * (589e6 + 90e6) + 2 * (541e6 + 34e6) + 2 * (717e6 + 39e6)) / 6
 
 
 def cpu_baseline(specs, host_inputs):
