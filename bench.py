@@ -274,6 +274,12 @@ def main() -> int:
 
         decode3["T%d" % tok] = time_decode(descs3, xs, packs3, ys, qfws3, tok)
     del packs3
+    # and at 2 bits, one token (the streaming one-token kernel covers 2, 4 and 8 bits)
+    packs2 = [torch.randint(-2**31, 2**31 - 1, (l.spec.out_features, 2 * l.spec.in_features // 32), dtype=torch.int32,
+                            device="cuda:0", generator=gen3) for l in layers]
+    descs2 = [binding.make_desc(l.spec.with_(tokens=1, bits=2)) for l in layers]
+    decode2 = {"T1": time_decode(descs2, [l.X[:1] for l in layers], packs2, [l.Y[:1] for l in layers], qfws, 1)}
+    del packs2
 
     # the QAT-LoRA layer (Sec. 3.1) on the same workload: separate LoRA path, stored weight gradient
     qws_f, qws_b = zip(*[binding.l4q_qatlora_workspace_bytes(l.desc) for l in layers])
@@ -348,6 +354,7 @@ def main() -> int:
                                  / args.profile_steps / ms_per_step)
     out["quantized_forward"] = decode
     out["quantized_forward_3bit"] = decode3
+    out["quantized_forward_2bit"] = decode2
     out["qat_lora_same_workload"] = {"ms_per_step": qat_ms, "workspace_bytes_fwd": max(qws_f),
                                      "workspace_bytes_bwd": max(qws_b),
                                      "l4q_speedup": qat_ms / ms_per_step}

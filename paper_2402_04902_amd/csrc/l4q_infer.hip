@@ -5,7 +5,7 @@
 // row's little-endian bit string; rows are n * i / 32 words.
 //
 // Five kernels compute the product, chosen by launch_qgemm from the code width, the token count and the layer's
-// shape (each is described where it is defined): qgemm_decode_kernel (4 / 8 bits, activations resident in LDS),
+// shape (each is described where it is defined): qgemm_decode_kernel (2 / 4 / 8 bits, activations resident in LDS),
 // qgemm_decode3_kernel (3 bits, likewise), qgemm_stream_kernel (4 / 8 bits, up to 32 tokens per pass),
 // qgemm_tile_kernel (3 / 4 / 8 bits, 64-row tiles, up to 64 tokens per pass, optionally in k-slices whose partial
 // sums qgemm_slices_sum_kernel adds), and qgemm_kernel, which covers every other layout:
@@ -313,6 +313,16 @@ __device__ __forceinline__ bf16x8_t code_fragment(const code_chunk_t& w, int f) 
       asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
       d[r] = pair;
     }
+  } else if (BITS == 2) {
+    // the chunk's first two dwords hold 32 codes; fragment f is the 16-bit half f % 2 of dword f / 2, its code pairs are
+    // 4-bit fields: times 0x4001 puts a copy 14 bits up, the mask leaves code 2r in bits 0..1 and code 2r + 1 in bits
+    // 16..17 (the caller's K0 is 128 + 2)
+    const uint32_t v = w[f >> 1];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t spread = __builtin_amdgcn_ubfe(v, 16 * (f & 1) + 4 * r, 4) * 0x4001u;
+      d[r] = (spread & 0x00030003u) | 0x43004300u;
+    }
   } else if (BITS == 3) {
     // the chunk's first three dwords hold 32 codes; fragment f is the 24-bit window from bit 24 f, its code pairs are
     // 6-bit fields: times 0x2001 puts a copy 13 bits up, the mask leaves code 2r in bits 0..2 and code 2r + 1 in bits
@@ -517,7 +527,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_stream_kernel(const bf16_t* __re
 // (lanes of one token and k-group read the same address, which the LDS serves as a broadcast).  NSW = ring stages
 // per wave: 4 when several workgroups share a compute unit, 8 when there is at most one per unit and a wave has to
 // keep more of the stream in flight by itself.
-constexpr int QD_X_MAX = 96 * 1024;   // bytes of X held in LDS
+constexpr int QD_X_MAX = 100 * 1024;  // bytes of X held in LDS
 constexpr int QD_SB_MAX = 17 * 1024;  // bytes of scale + zero held in LDS (up to 128 groups per row)
 constexpr int QD_LDS_MAX = 160 * 1024; // LDS of a compute unit
 
@@ -527,17 +537,20 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
                                                                const float* __restrict__ scale,
                                                                const float* __restrict__ zero,
                                                                bf16_t* __restrict__ Y, int T, int o, int i, int g,
-                                                               int x_bytes, int sb_pitch) {
+                                                               int xpitch, int sb_pitch) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char dlds[];
 #if defined(__HIP_DEVICE_COMPILE__)
-  static_assert(BITS == 4 || BITS == 8, "bits");
+  static_assert(BITS == 2 || BITS == 4 || BITS == 8, "bits");
   constexpr int ROWS = 16;
   constexpr int STAGE = ROWS * 128;
   typedef QsMfma<ROWS> M;
   typedef typename M::acc_t acc_t;
   constexpr int NACC = M::NACC;
-  constexpr int KG = 64 / ROWS, NH = 8 / KG, NDMA = ROWS / 8;
-  constexpr int CH = 128 / BITS, KS = 8 * CH, FR = CH / 8, SUB = KG * CH;
+  // A lane group's share of a sub-step: 16 bytes of its row's stage, or 8 for 2 bits (32 codes either way at 2 and 4
+  // bits), so that a sub-step's 4 x 32 codes never span more than one group of 128.
+  constexpr int LB = BITS == 2 ? 8 : 16;
+  constexpr int KG = 64 / ROWS, NDMA = ROWS / 8;
+  constexpr int CH = LB * 8 / BITS, KS = 128 * 8 / BITS, FR = CH / 8, SUB = KG * CH, NH = KS / SUB;
   constexpr float K0 = BITS == 8 ? 0.f : 128.f + (float)(1 << (BITS - 1));
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   typedef gemm::lds_ptr_t lds_ptr_t;
@@ -547,14 +560,19 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
   const int p0 = blockIdx.x * ROWS;
   const int p = p0 + ln;
   const int rb = i / 8 * BITS;
-  const int nst = rb / 128;
+  // A row need not be a whole number of 128-byte stages: its last stage then runs into the next row's codes (or past
+  // the matrix: zeros), which meet activations that are zero (every token's row in LDS is zero beyond k = i) and
+  // scale / zero values that are the zeros of the table's padding.
+  const int nst = (rb + 127) / 128;
   const int G = i / g;
   const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
 
   unsigned char* ring = dlds + wave * (NSW * STAGE);
-  unsigned char* xl = dlds + 4 * NSW * STAGE;                // [T][i] bf16, as in memory
-  float* sl = reinterpret_cast<float*>(xl + x_bytes);           // [16][sb_pitch], odd pitch: conflict-free columns
+  // [T][xpitch bytes] bf16: a token's row, zero from k = i to the end of its last stage; rows 16 bytes apart in the
+  // banks, so that the tokens of a fragment read spread over the bank groups
+  unsigned char* xl = dlds + 4 * NSW * STAGE;
+  float* sl = reinterpret_cast<float*>(xl + T * xpitch);        // [16][sb_pitch], odd pitch: conflict-free columns
   float* bl = sl + ROWS * sb_pitch;
 
   const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -581,9 +599,15 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
   // as zero), then scale / zero of the tile's rows, all by DMA into LDS
 #pragma unroll
   for (int j = 0; j < NSW - 1; ++j) issue_dma(j);
-  for (int q = wave; q < x_bytes / 1024; q += 4)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xl + q * 1024), 16, (unsigned)(q * 1024 + lane * 16), 0,
-                                             0, 0);
+  {
+    const int npc = xpitch / 1024;  // 1 KiB pieces of a token's row
+    for (int q = wave; q < T * npc; q += 4) {
+      const int t = q / npc, c = q - t * npc;
+      const int byte = c * 1024 + lane * 16;
+      const unsigned off = byte < i * 2 ? (unsigned)((int64_t)t * i * 2 + byte) : gemm::OOB_OFFSET;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xl + t * xpitch + c * 1024), 16, off, 0, 0, 0);
+    }
+  }
   {
     // Per table row ceil(G / 64) wave-wide loads of 4 bytes per lane, straight into the padded LDS row: nothing passes
     // through registers and nothing waits before the common wait below (a loop of load - wait - store rounds cost a
@@ -594,7 +618,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
         const_cast<float*>(scale), 0, (int)((int64_t)o * G * 4), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float*>(zero), 0, (int)((int64_t)o * G * 4), 0x00020000);
-    const int per_row = (G + 63) / 64;
+    const int per_row = (sb_pitch - 1) / 64;  // (the pitch covers the groups of the padded row)
     for (int u = wave; u < ROWS * per_row; u += 4) {
       const int row = u / per_row, c = u - row * per_row;
       const int idx = c * 64 + lane;
@@ -609,7 +633,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
   const unsigned frag_row = ln * 128;
   const int swz = (ln >> 1) & 7;
   const int tok = ln < T ? ln : T - 1;
-  const unsigned char* xrow = xl + (size_t)tok * i * 2;
+  const unsigned char* xrow = xl + (size_t)tok * xpitch;
   const float* srow = sl + ln * sb_pitch;
   const float* brow = bl + ln * sb_pitch;
 
@@ -625,7 +649,15 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
     const int k0 = (wave + 4 * j) * KS;
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
-      const u32x4 w = *reinterpret_cast<const u32x4*>(src + (((KG * h + kg) ^ swz) << 4));
+      u32x4 w;
+      if constexpr (BITS == 2) {  // half a 16-byte chunk: piece KG h + kg of the row's sixteen
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        const int piece = KG * h + kg;
+        const u32x2 w2 = *reinterpret_cast<const u32x2*>(src + ((((piece >> 1) ^ swz) << 4) | ((piece & 1) << 3)));
+        w = u32x4{w2[0], w2[1], 0u, 0u};
+      } else {
+        w = *reinterpret_cast<const u32x4*>(src + (((KG * h + kg) ^ swz) << 4));
+      }
       const int grp = (k0 + h * SUB) / g;
       const float sc = srow[grp], bz = brow[grp] - K0 * sc;
       acc_t tw, tx;
@@ -1189,6 +1221,15 @@ int qgemm_stream_rows(const LayerDims& d, int tokens_in_pass) {
   return 0;
 }
 
+// Whether qgemm_decode_kernel can run this layer (any token count it has LDS for): 2 / 4 / 8 bits, packed rows whose
+// 16-byte pieces are aligned, a group a whole number of sub-steps (128 codes; 64 at 8 bits).
+bool qgemm_decode_ok(const LayerDims& d) {
+  if (d.bits != 2 && d.bits != 4 && d.bits != 8) return false;
+  const int64_t rb = d.i / 8 * d.bits;
+  if (d.i % 8 != 0 || rb % 16 != 0 || (d.o + 16) * rb >= (1ll << 31) || 16 * d.i * 2 >= (1ll << 31)) return false;
+  return d.g % (d.bits == 8 ? 64 : 128) == 0;
+}
+
 // How the 64-row tile kernel would run this layer: token blocks per pass (0: not at all), k-slices per row tile,
 // the pitch of its tables in LDS (groups a slice can meet, made odd) and the LDS of a pass of tb token blocks (rings,
 // sum table, scale table; the zero-point table reuses the rings; 0 where that does not fit).
@@ -1262,9 +1303,11 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
   dim3 grid((unsigned)((d.o + 31) / 32));
   // more than 32 tokens: the general kernel reads the weights once per 64 tokens, the streaming form once per 32
   // smallest batches: activations and the tile's scale / zero in LDS
-  if (d.T <= 16 && qgemm_stream_rows(d, (int)d.T) == 16) {
-    const int64_t xb = (d.T * d.i * 2 + 1023) / 1024 * 1024;
-    const int64_t G = d.i / d.g, pitch = 64 * ((G + 63) / 64) + 1;  // whole 64-lane loads per row, odd: no bank conflicts
+  if (d.T <= 16 && qgemm_decode_ok(d)) {
+    const int64_t rb = d.i / 8 * d.bits, ks = 128 * 8 / d.bits, nst = (rb + 127) / 128;
+    const int64_t xpitch = (nst * ks * 2 + 1023) / 1024 * 1024 + 16;  // a token's row up to the end of its last stage
+    const int64_t xb = d.T * xpitch;
+    const int64_t Gp = (nst * ks + d.g - 1) / d.g, pitch = 64 * ((Gp + 63) / 64) + 1;  // whole 64-lane loads per row, odd: no bank conflicts
     const int64_t sbb = 2 * 16 * pitch * 4;
     const int64_t tiles = (d.o + 15) / 16;
     int nsw = tiles <= device_compute_units() ? 8 : 4;
@@ -1279,9 +1322,11 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode_kernel<B, N>),                          \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                                   \
     hipLaunchKernelGGL((qgemm_decode_kernel<B, N>), sgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y, \
-                       (int)d.T, (int)d.o, (int)d.i, d.g, (int)xb, (int)pitch);                                     \
+                       (int)d.T, (int)d.o, (int)d.i, d.g, (int)xpitch, (int)pitch);                                 \
   } while (0)
-      if (d.bits == 4 && nsw == 4) L4Q_QD(4, 4);
+      if (d.bits == 2 && nsw == 4) L4Q_QD(2, 4);
+      else if (d.bits == 2) L4Q_QD(2, 8);
+      else if (d.bits == 4 && nsw == 4) L4Q_QD(4, 4);
       else if (d.bits == 4) L4Q_QD(4, 8);
       else if (nsw == 4) L4Q_QD(8, 4);
       else L4Q_QD(8, 8);

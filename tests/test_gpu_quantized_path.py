@@ -127,6 +127,14 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     # 70B-class projections: the widest layer at a small batch, the longest rows (too many groups for the tile kernel's
     # tables: the streaming forms take it)
     (4, 8192, 28672, 4, 128), (40, 28672, 8192, 4, 128),
+    # 2 bits in the LDS-resident form (half-chunk sub-steps): both projections at one token and a few (rows of 11008
+    # codes are 21.5 stages: the last stage runs into the next row), groups of two sub-steps, a ragged row tile, a row
+    # of less than one stage, 12 tokens of a short row; beyond the activations' LDS room: the general kernel
+    (1, 4096, 11008, 2, 128), (1, 11008, 4096, 2, 128), (4, 4096, 11008, 2, 128), (8, 11008, 4096, 2, 128),
+    (3, 2048, 1000, 2, 256), (5, 256, 40, 2, 128), (12, 1024, 264, 2, 128), (16, 4096, 520, 2, 128),
+    # 4 and 8 bits with packed rows that are not whole stages (16-byte aligned only): the last stage is shared with
+    # the next row; the last row's runs past the matrix
+    (2, 4096 + 128, 1000, 4, 128), (7, 1152, 264, 4, 128), (3, 2048 + 64, 72, 8, 64), (1, 11008 + 128, 4096, 4, 128),
 ])
 def test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g):
     import torch
