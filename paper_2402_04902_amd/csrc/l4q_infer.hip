@@ -526,8 +526,8 @@ __global__ __launch_bounds__(256, 2) void qgemm_stream_kernel(const bf16_t* __re
 // workgroup, and the stage loop issues nothing but the weight stream: fragments, scale and zero are LDS reads
 // (lanes of one token and k-group read the same address, which the LDS serves as a broadcast).  NSW = ring stages
 // per wave: 4 when several workgroups share a compute unit, 8 when there is at most one per unit and a wave has to
-// keep more of the stream in flight by itself.
-constexpr int QD_X_MAX = 100 * 1024;  // bytes of X held in LDS
+// keep more of the stream in flight by itself, 2 where the activations leave room for no more.
+constexpr int QD_X_MAX = 132 * 1024;  // bytes of X held in LDS
 constexpr int QD_SB_MAX = 17 * 1024;  // bytes of scale + zero held in LDS (up to 128 groups per row)
 constexpr int QD_LDS_MAX = 160 * 1024; // LDS of a compute unit
 
@@ -1312,6 +1312,7 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     const int64_t tiles = (d.o + 15) / 16;
     int nsw = tiles <= device_compute_units() ? 8 : 4;
     if (4 * nsw * 16 * 128 + xb + sbb > QD_LDS_MAX) nsw = 4;
+    if (4 * nsw * 16 * 128 + xb + sbb > QD_LDS_MAX) nsw = 2;  // (16 tokens of a 4096-wide layer: 17.0 against 18.3 us in 64-row tiles)
     if (xb <= QD_X_MAX && sbb <= QD_SB_MAX && 4 * nsw * 16 * 128 + xb + sbb <= QD_LDS_MAX) {
       const size_t lds_bytes = (size_t)(4 * nsw * 16 * 128 + xb + sbb);
       dim3 sgrid((unsigned)tiles);
@@ -1324,10 +1325,13 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     hipLaunchKernelGGL((qgemm_decode_kernel<B, N>), sgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y, \
                        (int)d.T, (int)d.o, (int)d.i, d.g, (int)xpitch, (int)pitch);                                 \
   } while (0)
-      if (d.bits == 2 && nsw == 4) L4Q_QD(2, 4);
+      if (d.bits == 2 && nsw == 2) L4Q_QD(2, 2);
+      else if (d.bits == 2 && nsw == 4) L4Q_QD(2, 4);
       else if (d.bits == 2) L4Q_QD(2, 8);
+      else if (d.bits == 4 && nsw == 2) L4Q_QD(4, 2);
       else if (d.bits == 4 && nsw == 4) L4Q_QD(4, 4);
       else if (d.bits == 4) L4Q_QD(4, 8);
+      else if (nsw == 2) L4Q_QD(8, 2);
       else if (nsw == 4) L4Q_QD(8, 4);
       else L4Q_QD(8, 8);
 #undef L4Q_QD
@@ -1343,7 +1347,7 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
     const int64_t tiles = (d.o + 15) / 16;
     const auto fits = [&](int n) { return 4 * n * 3 * 2048 + xb + sbb <= QD_LDS_MAX; };
     int nss = tiles <= device_compute_units() && fits(3) ? 3 : 2;  // a lone workgroup per unit keeps more in flight
-    if (xb <= QD_X_MAX && sbb <= QD_SB_MAX && fits(nss)) {
+    if (xb <= 96 * 1024 && sbb <= QD_SB_MAX && fits(nss)) {
       const size_t lds_bytes = (size_t)(4 * nss * 3 * 2048 + xb + sbb);
       dim3 sgrid((unsigned)tiles);
 #define L4Q_QD3(N)                                                                                                 \
