@@ -105,8 +105,10 @@ typedef struct l4q_desc {
   int32_t flags;        /* L4Q_FLAG_* */
 } l4q_desc;
 
-/* Bytes of device workspace l4q_forward and l4q_backward need for this descriptor.
- * Either output pointer may be NULL.  The workspace must be 256-byte aligned. */
+/* Bytes of device workspace l4q_forward and l4q_backward need for this descriptor (all of its fields count: at
+ * few tokens a bfloat16 layer's forward and dX products are split along k over the compute units, and the
+ * slices' binary32 tiles live in the workspace).  Either output pointer may be NULL.  The workspace must be
+ * 256-byte aligned. */
 int l4q_workspace_bytes(const l4q_desc* desc, size_t* forward_bytes, size_t* backward_bytes);
 
 /* Forward pass (Sec. 3.2, Eqs. l4q_Wcombine, l4q_Wquant, l4q_Wdequant, l4q_forward):
