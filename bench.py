@@ -372,6 +372,11 @@ def main() -> int:
             # the headline layers at token counts with one and four tile rows (forward / dX products split along k)
             "C3_llama7b_mlp_T256": measure_config([sp.with_(tokens=256) for sp in inputs.config3()], 60, steps=10),
             "C3_llama7b_mlp_T1024": measure_config([sp.with_(tokens=1024) for sp in inputs.config3()], 61, steps=10),
+            # the paper's rank sweep (Table 6) on the headline layers: rank 32 is the last the fused epilogue forms
+            # dA / dB for; above it the masked gradient is handed on in bfloat16 and dA / dB are two thin products
+            "C3_llama7b_mlp_rank32": measure_config([sp.with_(rank=32, alpha=64.0) for sp in inputs.config3()], 62),
+            "C3_llama7b_mlp_rank64": measure_config([sp.with_(rank=64, alpha=128.0) for sp in inputs.config3()], 63),
+            "C3_llama7b_mlp_rank128": measure_config([sp.with_(rank=128, alpha=256.0) for sp in inputs.config3()], 64),
         }
     out["vendor_gemm_reference"] = {"what": "the step's six GEMMs alone via torch.matmul (hipBLASLt), bf16",
                                     "ms": vendor_ms, "TFLOP_per_s": flops_per_step / (vendor_ms * 1e-3) / 1e12,

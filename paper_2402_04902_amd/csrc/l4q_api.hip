@@ -80,8 +80,9 @@ struct BwdWs {
   bool fused;        // bf16: weight-gradient GEMM with the fused quantizer epilogue
   bool masked;       // bf16, ranks above 32: its second form (masked gradient stored as bf16, thin dA / dB products);
                      // the masked gradient takes the place of the factor array, tile by tile
-  float* rawA;       // [r,i]                      (bf16 masked)
-  float* rawB;       // [o,r]                      (bf16 masked)
+  float* rawA;       // [slices_a][r,i]            (bf16 masked)
+  float* rawB;       // [slices_b][o,r]            (bf16 masked)
+  int slices_a, slices_b;
   float* wq32;       // [o,i]                      (binary32 mode)
   bf16_t* wqT;       // [i,opad], in blocks of 32  (bf16)
   uint16_t* fgrad;   // [o,i] binary16             (bf16 fused)
@@ -125,8 +126,9 @@ BwdWs carve_bwd(const l4q_desc* d, void* ws) {
     w.wqT = c.take<bf16_t>(i * (size_t)w.opad);
     if (w.masked) {
       w.fgrad = c.take<uint16_t>(n);
-      w.rawA = c.take<float>(r * i);
-      w.rawB = c.take<float>(o * r);
+      l4q::dw_masked_product_slices(L, &w.slices_a, &w.slices_b);
+      w.rawA = c.take<float>((size_t)w.slices_a * r * i);
+      w.rawB = c.take<float>((size_t)w.slices_b * o * r);
     } else if (w.fused) {
       l4q::dw_fused_tiles(L, &w.tiles_m, &w.tiles_n);
       w.fgrad = c.take<uint16_t>(n);
@@ -390,7 +392,7 @@ int l4q_backward(const l4q_desc* desc, const void* X, const void* dY, const void
         l4q::launch_dw_masked(d, (const bf16_t*)dY, (const bf16_t*)X, w.fgrad, dscale, dzero, (bf16_t*)w.fgrad, stream);
       }
       l4q::launch_dw_masked_products(d, (const bf16_t*)w.fgrad, Ab, Bb, w.rawA, w.rawB, stream);
-      l4q::launch_reduce_two_partials(w.rawA, 1, (int64_t)d.r * d.i, dA, w.rawB, 1, d.o * d.r, dB, d.gamma,
+      l4q::launch_reduce_two_partials(w.rawA, w.slices_a, (int64_t)d.r * d.i, dA, w.rawB, w.slices_b, d.o * d.r, dB, d.gamma,
                                       d.accumulate, stream);
     }
     gemm_nt((const bf16_t*)dY, d.o, w.wqT, w.opad, d.T, d.i, w.opad, d.o, (bf16_t*)dX, d.i, stream, w.splitk);

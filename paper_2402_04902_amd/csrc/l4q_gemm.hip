@@ -104,13 +104,14 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_fast_kernel(const bf16_t* 
                                                       tile_n * T::BN, lds);
 }
 
-// One (tile, k-slice) of the forward / dX product with few tiles: slice blockIdx.y of gridDim.y takes a run of whole
-// stage pairs of the k range and leaves its binary32 tile in part[slice][M][N].  B in blocks of 32 k-values.
-template <class T, bool MASK_A_K>
+// One (tile, k-slice) of a product with few tiles: slice blockIdx.y of gridDim.y takes a run of whole stage pairs of
+// the k range and leaves its binary32 tile in part[slice][M][N].  K-contiguous operands; B row-major (ldb) or, B_BLK, in
+// blocks of 32 k-values.
+template <class T, bool MASK_A_K, bool B_BLK>
 __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_splitk_kernel(const bf16_t* __restrict__ A, int64_t lda,
-                                                                     const bf16_t* __restrict__ B, int M, int N, int K,
-                                                                     int K_a, float* __restrict__ part, int tiles_m,
-                                                                     int tiles_n) {
+                                                                     const bf16_t* __restrict__ B, int64_t ldb, int M,
+                                                                     int N, int K, int K_a, float* __restrict__ part,
+                                                                     int tiles_m, int tiles_n) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
   int tile_m, tile_n;
   gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -121,8 +122,28 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_nt_splitk_kernel(const bf16_t
   if (k1 > K) k1 = K;
   // rows of A end at K_a: inside the last slice, at or past the end of every other
   const int ka = (K_a < k1 ? K_a : k1) - k0;
-  gemm_tile<T, false, false, false, MASK_A_K, true>(A + k0, lda, B + (int64_t)(k0 / T::BK) * N * T::BK, 0, M, N, k1 - k0, ka,
-                                                    part + (int64_t)slice * M * N, N, tile_m * T::BM, tile_n * T::BN, lds);
+  const bf16_t* Bs = B_BLK ? B + (int64_t)(k0 / T::BK) * N * T::BK : B + k0;
+  gemm_tile<T, false, false, false, MASK_A_K, B_BLK>(A + k0, lda, Bs, ldb, M, N, k1 - k0, ka,
+                                                     part + (int64_t)slice * M * N, N, tile_m * T::BM, tile_n * T::BN, lds);
+}
+
+// The same for K-major operands (rows = k): slice blockIdx.y takes a run of whole stages.
+template <class T>
+__global__ __launch_bounds__(T::NT) void gemm_bf16_kmajor_splitk_kernel(const bf16_t* __restrict__ A, int64_t lda,
+                                                                         const bf16_t* __restrict__ B, int64_t ldb,
+                                                                         int M, int N, int K, float* __restrict__ part,
+                                                                         int tiles_m, int tiles_n) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+  int tile_m, tile_n;
+  gemm::tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int slices = gridDim.y, slice = blockIdx.y;
+  const int nk = (K + T::BK - 1) / T::BK;
+  const int k0 = (int)((int64_t)nk * slice / slices) * T::BK;
+  int k1 = (int)((int64_t)nk * (slice + 1) / slices) * T::BK;
+  if (k1 > K) k1 = K;
+  gemm_tile<T, false, true, true, false, false>(A + (int64_t)k0 * lda, lda, B + (int64_t)k0 * ldb, ldb, M, N, k1 - k0,
+                                                k1 - k0, part + (int64_t)slice * M * N, N, tile_m * T::BM,
+                                                tile_n * T::BN, lds);
 }
 
 // C[m, n] = bf16(sum over the slices, in slice order, of part[slice][m][n]); N % 4 == 0, four columns per thread.
@@ -223,11 +244,11 @@ void launch_gemm_bf16_nt(const bf16_t* A, int64_t lda, const bf16_t* B, int64_t 
   if (slices > 1) {
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)slices);
     if (K_a == K)
-      hipLaunchKernelGGL((gemm_bf16_nt_splitk_kernel<F, false>), grid, dim3(F::NT), 0, stream, A, lda, B, (int)M, (int)N,
-                         (int)K, (int)K_a, partial, tiles_m, tiles_n);
+      hipLaunchKernelGGL((gemm_bf16_nt_splitk_kernel<F, false, true>), grid, dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M,
+                         (int)N, (int)K, (int)K_a, partial, tiles_m, tiles_n);
     else
-      hipLaunchKernelGGL((gemm_bf16_nt_splitk_kernel<F, true>), grid, dim3(F::NT), 0, stream, A, lda, B, (int)M, (int)N,
-                         (int)K, (int)K_a, partial, tiles_m, tiles_n);
+      hipLaunchKernelGGL((gemm_bf16_nt_splitk_kernel<F, true, true>), grid, dim3(F::NT), 0, stream, A, lda, B, ldb, (int)M,
+                         (int)N, (int)K, (int)K_a, partial, tiles_m, tiles_n);
     const int64_t quads = M * N / 4;
     hipLaunchKernelGGL(splitk_sum_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, partial, slices,
                        M, N, C, ldc);
@@ -254,18 +275,41 @@ void launch_gemm_bf16_kmajor_f32(const bf16_t* A, int64_t lda, const bf16_t* B, 
                      tiles_n);
 }
 
+// k-slices of the two thin products of the masked form (dB = dWm A^T: [o, r], k = i; dA = B^T dWm: [r, i], k = o): each
+// has o / 256 or i / 256 tiles only, one tile row or column, and a long k range; as many slices as put a workgroup on
+// every compute unit, each at least 8 stages long, at most 8 (and 32 MiB of partial results).
+void dw_masked_product_slices(const LayerDims& d, int* slices_a, int* slices_b) {
+  const int64_t cus = device_compute_units();
+  auto pick = [&](int64_t tiles, int64_t stages, int64_t out_elems) {
+    int64_t s = cus / (tiles > 0 ? tiles : 1);
+    if (s > stages / 8) s = stages / 8;
+    if (s > 8) s = 8;
+    while (s > 1 && s * out_elems * 4 > (32ll << 20)) --s;
+    return (int)(s < 1 ? 1 : s);
+  };
+  const int64_t tr = (d.r + 255) / 256;
+  *slices_b = pick(((d.o + 255) / 256) * tr, (d.i + 31) / 32, d.o * d.r);
+  *slices_a = pick(tr * ((d.i + 255) / 256), (d.o + 31) / 32, (int64_t)d.r * d.i);
+}
+
 void launch_dw_masked_products(const LayerDims& d, const bf16_t* dWm, const bf16_t* A, const bf16_t* B, float* rawA,
                                float* rawB, hipStream_t stream) {
-  // rawB [o, r] = dWm [o, i] . A [r, i]^T: both K-contiguous, k = i (a multiple of 32: nothing to pad or mask)
+  int sa = 1, sb = 1;
+  dw_masked_product_slices(d, &sa, &sb);
+  // rawB [sb][o, r] = dWm [o, i] . A [r, i]^T: both K-contiguous, k = i (a multiple of 32: nothing to pad or mask)
   {
     typedef gemm::Tile<256, 256, 32, 5, true, 4> F;
     const int tiles_m = (int)((d.o + F::BM - 1) / F::BM), tiles_n = (d.r + F::BN - 1) / F::BN;
-    hipLaunchKernelGGL((gemm_bf16_nt_fast_kernel<F, false, false, false, false>), dim3((unsigned)(tiles_m * tiles_n)),
-                       dim3(F::NT), 0, stream, dWm, d.i, A, d.i, (int)d.o, d.r, (int)d.i, (int)d.i, (void*)rawB,
-                       (int64_t)d.r, tiles_m, tiles_n);
+    hipLaunchKernelGGL((gemm_bf16_nt_splitk_kernel<F, false, false>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)sb),
+                       dim3(F::NT), 0, stream, dWm, d.i, A, d.i, (int)d.o, d.r, (int)d.i, (int)d.i, rawB, tiles_m, tiles_n);
   }
-  // rawA [r, i] = B [o, r]^T . dWm [o, i]: both K-major, k = o
-  launch_gemm_bf16_kmajor_f32(B, d.r, dWm, d.i, d.r, d.i, d.o, rawA, d.i, stream);
+  // rawA [sa][r, i] = B [o, r]^T . dWm [o, i]: both K-major, k = o
+  {
+    typedef gemm::Tile<256, 256, 32, 4> F;
+    const int tiles_m = (d.r + F::BM - 1) / F::BM, tiles_n = (int)((d.i + F::BN - 1) / F::BN);
+    hipLaunchKernelGGL((gemm_bf16_kmajor_splitk_kernel<F>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)sa), dim3(F::NT),
+                       0, stream, B, (int64_t)d.r, dWm, d.i, d.r, (int)d.i, (int)d.o, rawA, tiles_m, tiles_n);
+  }
 }
 
 }  // namespace l4q

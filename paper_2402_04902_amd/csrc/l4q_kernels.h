@@ -149,11 +149,13 @@ void launch_dw_fused(const LayerDims& d, const bf16_t* dY, const bf16_t* X, cons
 
 // Second form for ranks 33 .. 256 (see l4q_bwd_fused.hip): dscale, dzero as above, and the masked gradient m * dWq
 // written as bfloat16 dWm [o, i]; then launch_dw_masked_products forms
-//   rawA [r, i] = B^T . dWm  and  rawB [o, r] = dWm . A^T   (binary32, no gamma yet)
-// with the library's GEMM kernels.
+//   rawA [slices_a][r, i] = B^T . dWm  and  rawB [slices_b][o, r] = dWm . A^T   (binary32, no gamma yet)
+// with the library's GEMM kernels, each product split along k into dw_masked_product_slices() partial results that
+// the caller adds in slice order.
 bool dw_masked_supported(const LayerDims& d);
 void launch_dw_masked(const LayerDims& d, const bf16_t* dY, const bf16_t* X, const uint16_t* fgrad, float* dscale,
                       float* dzero, bf16_t* dWm, hipStream_t stream);
+void dw_masked_product_slices(const LayerDims& d, int* slices_a, int* slices_b);
 void launch_dw_masked_products(const LayerDims& d, const bf16_t* dWm, const bf16_t* A, const bf16_t* B, float* rawA,
                                float* rawB, hipStream_t stream);
 

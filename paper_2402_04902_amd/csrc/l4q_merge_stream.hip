@@ -97,7 +97,9 @@ constexpr int MS_TPITCH = 80;
 static_assert(64 * MS_TPITCH <= MS_WAVE_LDS, "transposed tile aliases the sums tile");
 template <int MODE> constexpr int ms_wave_lds() { return MS_WAVE_LDS; }
 
-template <int MODE, bool GAMMA_POW2>
+// ACH: 16-k chunks of the rank whose A values a wavefront keeps in registers for its whole run (1: ranks up to 16;
+// 4: ranks up to 64, further chunks are loaded where they are used).
+template <int MODE, bool GAMMA_POW2, int ACH>
 __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, const bf16_t* __restrict__ W0,
                                                         const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                         const float* __restrict__ scale,
@@ -163,16 +165,17 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
   const __amdgpu_buffer_rsrc_t rsWc = __builtin_amdgcn_make_buffer_rsrc(out.wcomb, 0, o * i * 4, 0x00020000);
   const bool want_f = MODE == 2 && out.fgrad != nullptr;
 
-  // A[k, jm] of the first rank chunk, two bfloat16 per register: loaded once per wavefront
-  uint32_t apk[8];
+  // A[k, jm] of the first ACH rank chunks, two bfloat16 per register: loaded once per wavefront
+  uint32_t apk[8 * ACH];
   const unsigned voffA = jm < i ? (unsigned)(jm * 2) : OOB;
-  {
+#pragma unroll
+  for (int c = 0; c < ACH; ++c) {
     uint32_t araw[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k)  // steps past the rank: a valid row is read; the B factor of that step is zero
-      araw[k] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsA, (int)voffA, (k < r ? k : r - 1) * i * 2, 0);
+      araw[k] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rsA, (int)voffA, (16 * c + k < r ? 16 * c + k : r - 1) * i * 2, 0);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) apk[k] = araw[2 * k] | (araw[2 * k + 1] << 16);
+    for (int k = 0; k < 8; ++k) apk[8 * c + k] = araw[2 * k] | (araw[2 * k + 1] << 16);
   }
 
   // every load of row block rb; past the wavefront's range (or the matrix) the offsets are out of range: nothing moves
@@ -208,6 +211,16 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
     f32x32_t sum;
 #pragma unroll
     for (int e = 0; e < 32; ++e) sum[e] = 0.f;
+    // B[p0 + lane % 32, 16 c .. 16 c + 15] of the chunks 1 .. ACH - 1, requested before the first chunk's matrix ops
+    u32x4 bx[ACH > 1 ? ACH - 1 : 1][2];
+    if constexpr (ACH > 1) {
+#pragma unroll
+      for (int c = 1; c < ACH; ++c) {
+        const unsigned vb = p0 + l32 < o && 16 * c < r ? (unsigned)((p0 + l32) * r * 2 + 32 * c) : OOB;
+        bx[c - 1][0] = __builtin_amdgcn_raw_buffer_load_b128(rsB, (int)vb, 0, 0);
+        bx[c - 1][1] = __builtin_amdgcn_raw_buffer_load_b128(rsB, (int)(16 * c + 8 < r ? vb + 16u : vb), 0, 0);
+      }
+    }
     {
       const uint32_t bw[8] = {F.bq0[0], F.bq0[1], F.bq0[2], F.bq0[3], F.bq1[0], F.bq1[1], F.bq1[2], F.bq1[3]};
 #pragma unroll
@@ -218,7 +231,22 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
         sum = __builtin_amdgcn_mfma_f32_32x32x1f32(bk, ak, sum, 0, 0, 0);
       }
     }
-    for (int k0 = 16; k0 < r; k0 += 16) {  // further chunks of a rank above 16: loaded where they are used
+    if constexpr (ACH > 1) {
+#pragma unroll
+      for (int c = 1; c < ACH; ++c) {
+        if (16 * c < r) {  // (uniform)
+          const uint32_t bw[8] = {bx[c - 1][0][0], bx[c - 1][0][1], bx[c - 1][0][2], bx[c - 1][0][3],
+                                  bx[c - 1][1][0], bx[c - 1][1][1], bx[c - 1][1][2], bx[c - 1][1][3]};
+#pragma unroll
+          for (int k = 0; k < 16; ++k) {
+            const float bk = 16 * c + k < r ? __uint_as_float(k & 1 ? bw[k >> 1] & 0xFFFF0000u : bw[k >> 1] << 16) : 0.f;
+            const float ak = __uint_as_float(k & 1 ? apk[8 * c + (k >> 1)] & 0xFFFF0000u : apk[8 * c + (k >> 1)] << 16);
+            sum = __builtin_amdgcn_mfma_f32_32x32x1f32(bk, ak, sum, 0, 0, 0);
+          }
+        }
+      }
+    }
+    for (int k0 = 16 * ACH; k0 < r; k0 += 16) {  // chunks beyond those in registers: loaded where they are used
       const unsigned voffB = p0 + l32 < o ? (unsigned)((p0 + l32) * r * 2 + 2 * k0) : OOB;
       const u32x4 q0 = __builtin_amdgcn_raw_buffer_load_b128(rsB, (int)voffB, 0, 0);
       const u32x4 q1 = __builtin_amdgcn_raw_buffer_load_b128(rsB, (int)(k0 + 8 < r ? voffB + 16u : voffB), 0, 0);
@@ -374,13 +402,13 @@ __device__ __forceinline__ void merge_quant_stream_body(const LayerDims& d, cons
 
 // Forward and export: 4 workgroups (16 wavefronts, 144 KiB of LDS) per compute unit.  Backward: MS_BWD_WAVES (the
 // dequantized weights of a row block wait in registers for the transposition: 152 registers per lane).
-template <bool GAMMA_POW2>
-__global__ __launch_bounds__(MS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
+template <bool GAMMA_POW2, int ACH = 1>
+__global__ __launch_bounds__(MS_THREADS) __attribute__((amdgpu_waves_per_eu(ACH == 1 ? 4 : 3, ACH == 1 ? 4 : 3)))
 void merge_quant_stream_fwd_kernel(LayerDims d, const bf16_t* __restrict__ W0, const bf16_t* __restrict__ A,
                                    const bf16_t* __restrict__ B, const float* __restrict__ scale,
                                    const float* __restrict__ zero, MergeQuantOut<bf16_t> out, int nrb) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * ms_wave_lds<1>()];
-  merge_quant_stream_body<1, GAMMA_POW2>(d, W0, A, B, scale, zero, out, nrb, lds_all);
+  merge_quant_stream_body<1, GAMMA_POW2, ACH>(d, W0, A, B, scale, zero, out, nrb, lds_all);
 }
 template <bool GAMMA_POW2>
 __global__ __launch_bounds__(MS_THREADS) __attribute__((amdgpu_waves_per_eu(MS_BWD_WAVES, MS_BWD_WAVES)))
@@ -388,7 +416,7 @@ void merge_quant_stream_bwd_kernel(LayerDims d, const bf16_t* __restrict__ W0, c
                                    const bf16_t* __restrict__ B, const float* __restrict__ scale,
                                    const float* __restrict__ zero, MergeQuantOut<bf16_t> out, int nrb) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * ms_wave_lds<2>()];
-  merge_quant_stream_body<2, GAMMA_POW2>(d, W0, A, B, scale, zero, out, nrb, lds_all);
+  merge_quant_stream_body<2, GAMMA_POW2, 1>(d, W0, A, B, scale, zero, out, nrb, lds_all);
 }
 template <bool GAMMA_POW2>
 __global__ __launch_bounds__(MS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
@@ -396,7 +424,7 @@ void merge_quant_stream_export_kernel(LayerDims d, const bf16_t* __restrict__ W0
                                       const bf16_t* __restrict__ B, const float* __restrict__ scale,
                                       const float* __restrict__ zero, MergeQuantOut<bf16_t> out, int nrb) {
   __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * ms_wave_lds<3>()];
-  merge_quant_stream_body<3, GAMMA_POW2>(d, W0, A, B, scale, zero, out, nrb, lds_all);
+  merge_quant_stream_body<3, GAMMA_POW2, 1>(d, W0, A, B, scale, zero, out, nrb, lds_all);
 }
 
 // ------------------------------------------------------------------ check of the reciprocal-based quotient
@@ -467,16 +495,20 @@ void launch_merge_quant_stream(const LayerDims& d, const bf16_t* W0, const bf16_
   const int nrb = (int)((rows + 31) / 32);
   // one resident round: 4 (backward: 3) workgroups per compute unit, each wavefront walking a run of row blocks
   const int strips = (int)((d.i + MS_COLS - 1) / MS_COLS);
-  int parts = (mode == 2 ? MS_BWD_WAVES : 4) * device_compute_units() / strips;
+  // Forward form at ranks above 16: A for four chunks in registers, 3 wavefronts per SIMD (rank 64: 111 against 134 us;
+  // the backward form, which would be down to 2 wavefronts per SIMD, does not gain: 124 against 120 us)
+  const bool wide = d.r > 16 && mode == 1;
+  int parts = (mode == 2 ? MS_BWD_WAVES : wide ? 3 : 4) * device_compute_units() / strips;
   if (parts < 1) parts = 1;
   if (parts > nrb) parts = nrb;
   dim3 grid((unsigned)strips, (unsigned)parts);
   // gamma acc is exact when gamma is a power of two >= 1 (no underflow of the product)
   const uint32_t gb = __builtin_bit_cast(uint32_t, d.gamma);
   const bool pow2 = (gb & 0x807FFFFFu) == 0 && d.gamma >= 1.f && d.gamma <= 1048576.f;
-#define L4Q_MS_LAUNCH(K, P) \
-  hipLaunchKernelGGL((K<P>), grid, dim3(MS_THREADS), 0, stream, d, W0, A, B, scale, zero, out, nrb)
-  if (mode == 1) { if (pow2) L4Q_MS_LAUNCH(merge_quant_stream_fwd_kernel, true); else L4Q_MS_LAUNCH(merge_quant_stream_fwd_kernel, false); }
+#define L4Q_MS_LAUNCH(K, ...) \
+  hipLaunchKernelGGL((K<__VA_ARGS__>), grid, dim3(MS_THREADS), 0, stream, d, W0, A, B, scale, zero, out, nrb)
+  if (mode == 1 && wide) { if (pow2) L4Q_MS_LAUNCH(merge_quant_stream_fwd_kernel, true, 4); else L4Q_MS_LAUNCH(merge_quant_stream_fwd_kernel, false, 4); }
+  else if (mode == 1) { if (pow2) L4Q_MS_LAUNCH(merge_quant_stream_fwd_kernel, true); else L4Q_MS_LAUNCH(merge_quant_stream_fwd_kernel, false); }
   else if (mode == 2) { if (pow2) L4Q_MS_LAUNCH(merge_quant_stream_bwd_kernel, true); else L4Q_MS_LAUNCH(merge_quant_stream_bwd_kernel, false); }
   else { if (pow2) L4Q_MS_LAUNCH(merge_quant_stream_export_kernel, true); else L4Q_MS_LAUNCH(merge_quant_stream_export_kernel, false); }
 #undef L4Q_MS_LAUNCH
