@@ -241,6 +241,12 @@ def test_larger_model_shapes():
     run_case(LayerSpec("down_28672x8192_T64", 64, 28672, 8192, 16, 32.0, 4, 128, DTYPE_BF16), seed=70, shrink=0.8)
 
 
+def test_bf16_few_tokens_split_k_with_a_k_tail():
+    """The k-split forward / dX products where the caller's rows end inside the last slice (1032 and 1096 features:
+    multiples of 8, not of 32)."""
+    run_case(LayerSpec("split_k_tail_1096x1032_T70", 70, 1032, 1096, 8, 16.0, 4, 8, DTYPE_BF16), seed=95, shrink=0.8)
+
+
 @pytest.mark.parametrize("tokens", [256, 200, 1000])
 def test_bf16_few_tokens_split_k(tokens):
     """Benchmark layers at token counts whose forward / dX products have too few tiles for the chip (one to four tile
@@ -384,13 +390,15 @@ def test_bf16_largest_operands(name, T, i, o):
 
 # ------------------------------------------------------------------ a non-finite row stays in its own row
 
-def test_bf16_non_finite_row_does_not_reach_its_neighbours():
-    """In-features 264 and out-features 136 are multiples of 8 but not of the 32-wide k-step of the matrix-core
-    kernels.  An Inf planted in one row of X (or dY) must poison that row of Y (dX) only: all other rows stay bit for
-    bit what they were."""
+@pytest.mark.parametrize("i,o", [(264, 136), (1032, 1096)])
+def test_bf16_non_finite_row_does_not_reach_its_neighbours(i, o):
+    """In- and out-features that are multiples of 8 but not of the 32-wide k-step of the matrix-core kernels (the
+    second pair long enough for the few-token form that splits the k range over workgroups: the rows' ends then lie
+    inside the last slice).  An Inf planted in one row of X (or dY) must poison that row of Y (dX) only: all other
+    rows stay bit for bit what they were."""
     import torch
     from paper_2402_04902_amd import binding
-    spec = LayerSpec("bf16_k_tail", 70, 264, 136, 4, 8.0, 4, 8, DTYPE_BF16)
+    spec = LayerSpec(f"bf16_k_tail_{i}x{o}", 70, i, o, 4, 8.0, 4, 8, DTYPE_BF16)
     print("case", spec.name, flush=True)
     arrs = inputs.make_layer_inputs(spec, seed=9)
     s, b = host_qparams(spec, arrs, "asymm", 0.8)
