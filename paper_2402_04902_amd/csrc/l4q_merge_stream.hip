@@ -90,7 +90,8 @@ struct WeightLoads {
 // MODE 1: forward (dequantized Wq, [ld_wq / 32][o][32]).  MODE 2: backward (Wq^T, [ld_wqT / 32][i][32]; optionally the
 // factor [o, i] and B^T).  MODE 3: export (any of int8 codes, binary32 merged weight, mask; all [o, i]).
 // Grid: x = 256-column strips, y = partitions of the row blocks; wavefront w of a workgroup walks the row blocks
-// [nrb y / gridDim.y, nrb (y + 1) / gridDim.y) of its 64 columns.
+// [nrb y / gridDim.y, nrb (y + 1) / gridDim.y) of its 64 columns (forward / export: one resident round of workgroups
+// covers the matrix; backward: four rounds' worth of shorter runs).
 // Transposed tile of the backward form (64 columns x 32 rows of bf16, column-major): pitch 80 bytes; it takes the place
 // of the sums tile once the row block has been streamed
 constexpr int MS_TPITCH = 80;
@@ -499,6 +500,10 @@ void launch_merge_quant_stream(const LayerDims& d, const bf16_t* W0, const bf16_
   // the backward form, which would be down to 2 wavefronts per SIMD, does not gain: 124 against 120 us)
   const bool wide = d.r > 16 && mode == 1;
   int parts = (mode == 2 ? MS_BWD_WAVES : wide ? 3 : 4) * device_compute_units() / strips;
+  // backward: four times as many, shorter runs (about two row blocks each), handed out as workgroups finish: its
+  // wavefronts are fewer and their phases longer, and one round of 5-or-6-block runs ends ragged (stand-alone 62-65
+  // against 68-75 us; inside a training step 65 against 66)
+  if (mode == 2) parts *= 4;
   if (parts < 1) parts = 1;
   if (parts > nrb) parts = nrb;
   dim3 grid((unsigned)strips, (unsigned)parts);
