@@ -152,6 +152,33 @@ def test_random_shapes(k, T, i, o, r, bits, g, dtype, shrink):
         assert rep["clipped"] > 0
 
 
+def _random_mid_cases(count=14, seed=4902):
+    """Seeded draw of bfloat16 layers of a few hundred to a few thousand features: long k ranges at few tokens (the
+    k-split forward / dX products, with and without a row tail), ranks on both sides of 16 and of 32 (streaming merge
+    kernel with and without further rank chunks, both forms of the weight-gradient epilogue, k-split dA / dB
+    products), out-features that are not whole row blocks."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for k in range(count):
+        g = int(rng.choice([32, 64, 128, 256]))
+        i = g * int(rng.integers(max(1, 512 // g), 4096 // g + 1))
+        o = 8 * int(rng.integers(32, 513))
+        T = int(rng.choice([1, 17, 64, 100, 256, 300, 700, 1100]))
+        r = int(rng.choice([8, 16, 24, 40, 64, 96]))
+        if r > 32 and i % 32 != 0:
+            r = 16
+        bits = int(rng.choice([3, 4]))
+        shrink = float(rng.choice([1.0, 0.8]))
+        cases.append((k, T, i, o, r, bits, g, shrink))
+    return cases
+
+
+@pytest.mark.parametrize("k,T,i,o,r,bits,g,shrink", _random_mid_cases())
+def test_random_mid_size_bf16_shapes(k, T, i, o, r, bits, g, shrink):
+    spec = LayerSpec(f"mid{k}_{T}x{i}x{o}_r{r}", T, i, o, r, 2.0 * r, bits, g, DTYPE_BF16)
+    run_case(spec, seed=2000 + k, shrink=shrink)
+
+
 @pytest.mark.parametrize("T,i,o,r,bits,g", [(300, 640, 264, 16, 4, 128), (513, 768, 1032, 8, 4, 64)])
 def test_bf16_unfused_backward_flag(T, i, o, r, bits, g):
     """The unfused backward (dWq through the workspace) must agree with the oracle as well."""
