@@ -7,7 +7,7 @@
 //  * a wavefront is the unit of work and shares nothing with the other wavefronts of its workgroup (no workgroup
 //    barrier anywhere): four wavefronts per SIMD sit in different phases and overlap their loads, matrix ops, LDS
 //    round trips, vector arithmetic and stores.  A wavefront owns 64 columns of the weight and walks a run of row
-//    blocks of 32 down them (one resident round of wavefronts covers the matrix), with the loads of the next row
+//    blocks of 32 down them (forward: one resident round of wavefronts covers the matrix), with the loads of the next row
 //    block in flight while it works on the current one; it has 9 KiB of LDS.
 //  * rank sums sum_k B[p,k] A[k,j] on the matrix core as a chain of K = 1 binary32 ops, one per k in ascending order:
 //    each step is RN(acc + b a) with the bfloat16 product exact, i.e. the stated sequential order bit for bit.
