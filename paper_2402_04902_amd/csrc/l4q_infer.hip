@@ -16,6 +16,8 @@
 // as the row operand; the token operand comes straight from X (L1/L2 resident at decode sizes).  The k-slot
 // order inside a chunk differs from memory order, identically for both operands, which a contraction allows.
 // Partial sums of the 8 waves meet in LDS.  The weight stream is read once per pass: HBM-bound.
+#include <type_traits>
+
 #include "l4q_device.h"
 #include "l4q_gemm_core.h"
 #include "l4q_kernels.h"
@@ -1190,6 +1192,271 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
 #endif
 }
 
+// Weights resident in registers, activations streamed: the form for a few tokens to a few token blocks.
+// The compute units' register files are the largest fast memory of the chip (512 KB each, against 160 KB of LDS), and a
+// layer's packed codes divided over the units are small (22.5 MB / 256 = 88 KB).  One workgroup of 16 waves takes NT
+// 16-row tiles (tiles blockIdx.x + n gridDim.x) and the whole of k, cut into chunks of 256 k-values: wave w owns chunks
+// w, w + 16, ... (CPW of them) of every tile of the workgroup, i.e. NT x CPW units of 16 rows x 256 codes.  Every load of
+// the kernel's weight stream - a unit is BITS x 2 dwords per lane - is issued in the first instructions, straight into
+// registers: no ring, no stage barriers, and the whole matrix is in flight at once over the chip.  Lane (row r, group
+// kq) of a unit holds the two 32-code pieces at k = 128 h + 32 kq (h = 0, 1) of its row; matrix op d of half h takes
+// dword-sized fragment d of that piece, so one op covers k = 128 h + {32 kq + 8 d + j}: groups of 128 and more are
+// whole numbers of halves.  The activations of a token block (16 tokens x the wave's chunks) are loaded with the same
+// k assignment, 16 bytes per lane and op, from the L2; their sums per (token, half) come from ops against ones.  Each
+// token block ends with the partial sums of the 16 waves meeting in LDS (double-buffered: one barrier per block) and
+// 256 outputs per tile written by 256 threads.  With more than one token block the codes are converted again for
+// each block (the registers hold the packed codes, not the operands).
+constexpr int WR_WAVES = 16;
+constexpr int WR_UNITS_MAX = 4;  // units (tiles x chunks) per wave that fit 128 registers
+
+template <int BITS, int NT, int CPW>
+__global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t* __restrict__ X,
+                                                                    const uint32_t* __restrict__ packed,
+                                                                    const float* __restrict__ scale,
+                                                                    const float* __restrict__ zero,
+                                                                    bf16_t* __restrict__ Y, int T, int o, int i, int g) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char wlds[];
+#if defined(__HIP_DEVICE_COMPILE__)
+  static_assert(BITS == 2 || BITS == 3 || BITS == 4 || BITS == 8, "bits");
+  static_assert(NT * CPW <= WR_UNITS_MAX, "units per wave");
+  typedef QsMfma<16> M;
+  typedef typename M::acc_t acc_t;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+  constexpr float K0 = BITS == 8 ? 0.f : 128.f + (float)(1 << (BITS - 1));
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ln = lane & 15, kq = lane >> 4;
+  const int rb = i / 8 * BITS, G = i / g;
+  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
+
+  const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint32_t*>(packed), 0, (int)((int64_t)o * rb), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcX = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(X), 0, (int)((int64_t)T * i * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcS = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(scale), 0, (int)((int64_t)o * G * 4), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float*>(zero), 0, (int)((int64_t)o * G * 4), 0x00020000);
+
+  // The scale and zero values of the workgroup's rows (NT x 16 rows x G groups each): one 16-byte piece of either table
+  // per thread, requested ahead of everything else, and passed on through LDS in rows of odd pitch (a lane reading its
+  // row's value of a group per unit straight from memory would touch 16 cache lines per wave-wide load, and the
+  // kernel would spend more time on those loads than on the weight stream).  zero is stored as zero - K0 scale.
+  const int ppr = (G + 3) / 4, pitch = G | 1;
+  float* tab = reinterpret_cast<float*>(wlds) + 2 * NT * WR_WAVES * 256;  // [NT * 16][pitch][scale, zero - K0 scale]
+  const bool tab_thread = (int)threadIdx.x < NT * 16 * ppr;
+  const int tab_nr = (int)threadIdx.x / ppr, tab_c = (int)threadIdx.x - tab_nr * ppr;
+  float tab_sv[4], tab_zv[4];
+  {
+    const int row = ((int)blockIdx.x + (tab_nr >> 4) * (int)gridDim.x) * 16 + (tab_nr & 15);
+    const unsigned off = tab_thread && row < o ? (unsigned)((row * G + 4 * tab_c) * 4) : gemm::OOB_OFFSET;
+    const float4 sv = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrcS, off, 0, 0));
+    const float4 zv = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrcZ, off, 0, 0));
+    tab_sv[0] = sv.x; tab_sv[1] = sv.y; tab_sv[2] = sv.z; tab_sv[3] = sv.w;
+    tab_zv[0] = zv.x; tab_zv[1] = zv.y; tab_zv[2] = zv.z; tab_zv[3] = zv.w;
+  }
+
+  // Steps of a token block: the wave's half-chunks (q, h) in order, S = 2 CPW of them.  The activations of a step (four
+  // fragments per lane) sit in a ring of D buffers over the steps of all blocks: the step that frees a buffer requests
+  // the one D steps ahead into it.
+  constexpr int S = 2 * CPW, D = CPW == 3 ? 3 : (CPW == 2 && NT == 1) ? 4 : 2;  // (what 128 registers hold)
+  constexpr int WW = BITS == 8 ? 8 : 4;
+  // 4 bits: the four dwords of a lane's piece are exchanged with those of the three other lanes of its row (a 4 x 4
+  // transpose over lane group and dword, two lane-swap steps, once per kernel), so that op d covers
+  // k = 128 h + {32 d + 8 kq + j} and the four lanes of a token read 64 contiguous bytes of it per load: the
+  // activation loads touch half as many cache lines, and they set the time per token block.
+  constexpr bool XT = BITS == 4;
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  unsigned xoff[CPW][2];  // token ln of a block, k = chunk 256 + 128 h + 32 kq (+ 8 d: 16 bytes each); halves past i: off
+#pragma unroll
+  for (int q = 0; q < CPW; ++q)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
+      xoff[q][h] = k0 < i ? (unsigned)((ln * i + k0 + kq * (XT ? 8 : 32)) * 2) : gemm::OOB_OFFSET;
+    }
+  bf16x8_t xb[D][4];
+  auto load_x = [&](int buf, int q, int h, int tb) {  // tokens past T lie outside the buffer and read as zero
+    const int sbase = tb * 16 * i * 2;
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+      xb[buf][d] = __builtin_bit_cast(
+          bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xoff[q][h], sbase + d * (XT ? 64 : 16), 0));
+  };
+#pragma unroll
+  for (int st = 0; st < D; ++st) load_x(st, st / 2, st % 2, 0);
+
+  // the weight stream: everything this wave will ever read of it, requested now, in the order of the steps (loads
+  // return in order: a step waits for exactly what it needs)
+  uint32_t w[NT][CPW][2][WW];
+#pragma unroll
+  for (int q = 0; q < CPW; ++q)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        const int row = ((int)blockIdx.x + n * (int)gridDim.x) * 16 + ln;
+        const bool live = row < o && k0 < i;
+        const unsigned off = live ? (unsigned)(row * rb + (k0 + kq * 32) / 8 * BITS) : gemm::OOB_OFFSET;
+        if constexpr (BITS == 4) {
+          const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off, 0, 0);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) w[n][q][h][c] = v[c];
+        } else if constexpr (BITS == 3) {
+          const u32x3 v = __builtin_amdgcn_raw_buffer_load_b96(rsrcW, off, 0, 0);
+#pragma unroll
+          for (int c = 0; c < 3; ++c) w[n][q][h][c] = v[c];
+          w[n][q][h][3] = 0u;
+        } else if constexpr (BITS == 2) {
+          const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrcW, off, 0, 0);
+          w[n][q][h][0] = v[0]; w[n][q][h][1] = v[1]; w[n][q][h][2] = 0u; w[n][q][h][3] = 0u;
+        } else {
+          const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off, 0, 0);
+          const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrcW, off, 16, 0);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) { w[n][q][h][c] = v0[c]; w[n][q][h][4 + c] = v1[c]; }
+        }
+      }
+    }
+  // the tables: written once the two pieces are here (the oldest loads in flight), visible after one barrier
+  if (tab_thread) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (4 * tab_c + c < G) {
+        *reinterpret_cast<float2*>(tab + (tab_nr * pitch + 4 * tab_c + c) * 2) =
+            make_float2(tab_sv[c], tab_zv[c] - K0 * tab_sv[c]);
+      }
+  }
+  __syncthreads();
+  const float* tab_row = tab + ln * pitch * 2;  // this lane's row of the first tile
+  int grp[CPW][2];  // group of each step, capped to the table
+#pragma unroll
+  for (int q = 0; q < CPW; ++q)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
+      grp[q][h] = k0 < i ? k0 / g : 0;
+    }
+
+  float* red = reinterpret_cast<float*>(wlds);  // [2][NT][16 waves][64 lanes][4]
+  const int ntb = (T + 15) / 16;
+  // one token block; par: the block's position in the ring's period (S steps per block, D buffers)
+  auto block = [&](auto par, int tb) {
+    constexpr int P = decltype(par)::value;
+    acc_t acc[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[n][e] = 0.f;
+#pragma unroll
+    for (int st = 0; st < S; ++st) {
+      const int q = st / 2, h = st % 2, buf = (P * S + st) % D;
+      acc_t xs;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) xs[e] = 0.f;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) xs = M::mma(xb[buf][d], ones, xs);
+      if constexpr (BITS == 4) {
+        // 4 bits: the codes of a dword are paired (j, j + 4) - one shift and one mask-or per pair instead of three ops
+        // for the pair (2 j, 2 j + 1) - and the activations follow: elements (0 4 1 5 2 6 3 7) of each fragment
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const u32x4 x = __builtin_bit_cast(u32x4, xb[buf][d]);
+          const u32x4 y = {__builtin_amdgcn_perm(x[2], x[0], 0x05040100u), __builtin_amdgcn_perm(x[2], x[0], 0x07060302u),
+                           __builtin_amdgcn_perm(x[3], x[1], 0x05040100u), __builtin_amdgcn_perm(x[3], x[1], 0x07060302u)};
+          xb[buf][d] = __builtin_bit_cast(bf16x8_t, y);
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        // (the packed codes are made opaque here, so that their conversion is not hoisted out of the loop over the
+        // token blocks: the converted operands of every unit would not fit the registers)
+#pragma unroll
+        for (int c = 0; c < (BITS == 8 ? 8 : BITS); ++c) asm volatile("" : "+v"(w[n][q][h][c]));
+        if constexpr (XT) {
+          if (tb == 0) {  // first use of the piece: transpose it
+            uint32_t (&p)[WW] = w[n][q][h];
+            const u32x2 a = __builtin_amdgcn_permlane32_swap(p[0], p[2], false, false);
+            const u32x2 b = __builtin_amdgcn_permlane32_swap(p[1], p[3], false, false);
+            const u32x2 c = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
+            const u32x2 e = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
+            p[0] = c[0]; p[1] = c[1]; p[2] = e[0]; p[3] = e[1];
+          }
+        }
+        acc_t tw;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tw[e] = 0.f;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          bf16x8_t wf;
+          if constexpr (BITS == 8) {
+            const u32x4 c = {w[n][q][h][4 * (d >> 1)], w[n][q][h][4 * (d >> 1) + 1], w[n][q][h][4 * (d >> 1) + 2],
+                             w[n][q][h][4 * (d >> 1) + 3]};
+            wf = code_fragment<8>(c, d & 1);
+          } else {
+            const u32x4 c = {w[n][q][h][0], w[n][q][h][1], w[n][q][h][2], w[n][q][h][3]};
+            if constexpr (BITS == 4) {
+              u32x4 f;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const uint32_t sh = c[d] >> (4 * e);
+                asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(f[e]) : "v"(sh), "s"(0x000F000Fu), "v"(0x43004300u));
+              }
+              wf = __builtin_bit_cast(bf16x8_t, f);
+            } else {
+              wf = code_fragment<BITS>(c, d);
+            }
+          }
+          tw = M::mma(xb[buf][d], wf, tw);
+        }
+        const int gofs = grp[q][h];
+        const float2 sz = *reinterpret_cast<const float2*>(tab_row + n * 16 * pitch * 2 + gofs * 2);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[n][e] = fmaf(sz.x, tw[e], fmaf(sz.y, xs[e], acc[n][e]));
+        // units one after the other (their operands do not all fit the registers), each one's sums folded into the
+        // outputs before the next starts
+        asm volatile("" : "+v"(acc[n][0]), "+v"(acc[n][1]), "+v"(acc[n][2]), "+v"(acc[n][3]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // the buffer is free: the step D ahead goes into it
+      const int st2 = (st + D) % S, dtb = (st + D) / S;
+      if (tb + dtb < ntb) load_x(buf, st2 / 2, st2 % 2, tb + dtb);
+    }
+    float* buf = red + (tb & 1) * (NT * WR_WAVES * 256);
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+      *reinterpret_cast<float4*>(buf + ((n * WR_WAVES + wave) * 64 + lane) * 4) =
+          make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
+    __syncthreads();
+    {
+      // thread -> (tile n, token te of the block, row r): 16 consecutive threads = 16 consecutive rows of one token
+      const int n = (int)threadIdx.x >> 8, idx = (int)threadIdx.x & 255;
+      const int r = idx & 15, te = idx >> 4;
+      if (n < NT) {
+        const float* src = buf + n * WR_WAVES * 256 + ((te >> 2) * 16 + r) * 4 + (te & 3);
+        float v = src[0];
+#pragma unroll
+        for (int wv = 1; wv < WR_WAVES; ++wv) v += src[wv * 256];
+        const int row = ((int)blockIdx.x + n * (int)gridDim.x) * 16 + r, t = tb * 16 + te;
+        if (t < T && row < o) Y[(int64_t)t * o + row] = f32_to_bf16(v);
+      }
+    }
+  };
+  if constexpr (S % D == 0) {
+    for (int tb = 0; tb < ntb; ++tb) block(std::integral_constant<int, 0>(), tb);
+  } else {
+    static_assert((2 * S) % D == 0, "the ring's period is two blocks");
+    for (int tb = 0; tb < ntb; tb += 2) {
+      block(std::integral_constant<int, 0>(), tb);
+      if (tb + 1 < ntb) block(std::integral_constant<int, 1>(), tb + 1);
+    }
+  }
+#endif
+}
+
 // Y[t0 + tl][p] = sum over the k-slices, in slice order, of part[slice][tl][p]; four rows per thread.
 __global__ __launch_bounds__(256) void qgemm_slices_sum_kernel(const float* __restrict__ part, bf16_t* __restrict__ Y,
                                                                int slices, int n_pass, int t0, int o) {
@@ -1282,6 +1549,95 @@ TilePlan qgemm_tile_plan(const LayerDims& d) {
   return plan;
 }
 
+// How the weights-in-registers kernel would run this layer: tiles per workgroup and chunks per wave (nt = 0: not at
+// all, or not faster than the streaming forms).  Measured against those (us; T = 1 / 5 / 16 / 33 / 64):
+//   4 bits [11008 x 4096] (3 tiles, 1 chunk): 8.3 / 8.9 / 11.2 / 18.2 / 24.0 against 7.1 / 12.8 / 17.1 / 26.6 / 27.8;
+//          [4096 x 4096] (1, 1): 4.5 / 5.0 / 6.9 / 12.0 / 17.9 against 4.8 / 5.3 / 6.5 / 12.9 / 14.1;
+//          [8192 x 8192] (2, 2): 10.7 / 11.3 / 14.7 / 26.7 / 38.5 against 9.7 / 14.7 / 28.8 / 29.5 / 31.2;
+//          [4096 x 11008] (1, 3): 9.6 / 10.4 / 15.2 / 29.4 / 45.4 against 8.8 / 10.0 / 15.6 / 23.7 / 25.1 (every
+//          compute unit reads the whole of X for its 16 rows: the time per token block grows with the chunks per wave);
+//   3 bits [11008 x 4096]: 8.8 / 9.5 / 11.8 / 20.1 / 25.3 against 9.7 / 15.2 / 22.2 / 32.8 / 35.1;
+//          [4096 x 11008]: 9.6 / 10.3 / 14.0 / 29.3 / 44.2 against 11.6 / 19.9 / 20.1 / 28.9 / 27.9;
+//   2 bits [11008 x 4096]: 8.8 / 9.4 / 11.5 / 20.1 / 24.9 against 7.7 / 13.7 / 18.2 / 43.3 / 52.5;
+//          [4096 x 11008]: 9.2 / 9.9 / 14.0 / 29.1 / 44.0 against 10.0 / 11.3 / 25.3 / 40.0 / 55.3;
+//   8 bits [4096 x 4096]: 5.7 / 6.2 / 8.3 / 13.8 / 19.3 against 6.9 / 7.5 / 8.6 / 14.6 / 15.3.
+struct WregPlan {
+  int nt, cpw;
+  unsigned grid;
+};
+#ifndef L4Q_WREG_SWITCH
+#define L4Q_WREG_SWITCH true
+#endif
+#ifndef L4Q_WREG_ANY
+#define L4Q_WREG_ANY false
+#endif
+WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
+  WregPlan plan = {0, 0, 0};
+  if (d.bits != 2 && d.bits != 3 && d.bits != 4 && d.bits != 8) return plan;
+  const int64_t rb = d.i / 8 * d.bits;
+  if (d.i % 128 != 0 || d.g % 128 != 0 || d.o * rb >= (1ll << 31) || d.T * d.i * 2 >= (1ll << 31) ||
+      d.o * (d.i / d.g) * 4 >= (1ll << 31))
+    return plan;
+  const int64_t tiles = (d.o + 15) / 16, chunks = (d.i + 255) / 256, cus = device_compute_units();
+  const int64_t cpw = (chunks + WR_WAVES - 1) / WR_WAVES;
+  if (cpw > WR_UNITS_MAX) return plan;
+  int64_t nt = (tiles + cus - 1) / cus;
+  if (nt > WR_UNITS_MAX / cpw) nt = WR_UNITS_MAX / cpw;
+  if (d.bits == 8) {  // twice the registers per unit
+    if (cpw > 2) return plan;
+    if (nt * cpw > 2) nt = cpw == 1 ? 2 : 1;
+  }
+  if (!any_size) {
+    const int64_t T = d.T;
+    int64_t lo = 2, hi = 16;
+    if (d.bits == 4) {
+      if (cpw == 1) { lo = nt == 1 ? 1 : 2; hi = nt >= 3 ? 64 : 48; }
+      else if (cpw == 2) hi = nt == 2 ? 48 : 16;
+      else if (cpw == 3) lo = 6;
+    } else if (d.bits == 3) {
+      lo = 1;
+      if (cpw == 1) hi = nt >= 3 ? 64 : 48;
+      else if (cpw == 2 && nt == 2) hi = 64;
+    } else if (d.bits == 2) {
+      lo = nt == 1 ? 1 : 2;
+      hi = 64;
+    } else {
+      if (cpw != 1 || nt != 1) return plan;
+      lo = 1; hi = 32;
+    }
+    if (2 * tiles < cus && lo < 17 && d.bits != 3) lo = 17;  // few tiles: the streaming forms split k further
+    if (T < lo || T > hi) return plan;
+  }
+  plan.nt = (int)nt;
+  plan.cpw = (int)cpw;
+  plan.grid = (unsigned)((tiles + nt - 1) / nt);
+  return plan;
+}
+
+template <int BITS>
+void launch_qgemm_wreg(const WregPlan& plan, const LayerDims& d, const bf16_t* X, const uint32_t* packed,
+                       const float* scale, const float* zero, bf16_t* Y, hipStream_t stream) {
+  const int64_t G = d.i / d.g;
+  const size_t lds_bytes = ((size_t)2 * plan.nt * WR_WAVES * 256 + (size_t)2 * plan.nt * 16 * (G | 1)) * sizeof(float);
+#define L4Q_WR(N, C)                                                                                                 \
+  do {                                                                                                               \
+    if (lds_bytes > 64 * 1024)                                                                                       \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_wreg_kernel<BITS, N, C>),                       \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                             \
+    hipLaunchKernelGGL((qgemm_wreg_kernel<BITS, N, C>), dim3(plan.grid), dim3(WR_WAVES * 64), lds_bytes, stream, X,  \
+                       packed, scale, zero, Y, (int)d.T, (int)d.o, (int)d.i, d.g);                                   \
+  } while (0)
+  const int key = plan.nt * 10 + plan.cpw;
+  if constexpr (BITS == 8) {
+    if (key == 11) L4Q_WR(1, 1); else if (key == 21) L4Q_WR(2, 1); else L4Q_WR(1, 2);
+  } else {
+    if (key == 11) L4Q_WR(1, 1); else if (key == 21) L4Q_WR(2, 1); else if (key == 31) L4Q_WR(3, 1);
+    else if (key == 41) L4Q_WR(4, 1); else if (key == 12) L4Q_WR(1, 2); else if (key == 22) L4Q_WR(2, 2);
+    else if (key == 13) L4Q_WR(1, 3); else L4Q_WR(1, 4);
+  }
+#undef L4Q_WR
+}
+
 }  // namespace
 
 void launch_pack_codes(const int8_t* codes, int64_t o, int64_t i, int bits, uint32_t* packed, hipStream_t stream) {
@@ -1301,6 +1657,17 @@ size_t qgemm_workspace_bytes(const LayerDims& d) {
 void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, const float* scale, const float* zero,
                   bf16_t* Y, float* partial, size_t partial_bytes, hipStream_t stream) {
   dim3 grid((unsigned)((d.o + 31) / 32));
+  // a few token blocks at most, groups of 128 and more: the packed codes resident in registers
+  if (L4Q_WREG_SWITCH) {
+    const WregPlan wr = qgemm_wreg_plan(d, L4Q_WREG_ANY);
+    if (wr.nt > 0) {
+      if (d.bits == 2) launch_qgemm_wreg<2>(wr, d, X, packed, scale, zero, Y, stream);
+      else if (d.bits == 3) launch_qgemm_wreg<3>(wr, d, X, packed, scale, zero, Y, stream);
+      else if (d.bits == 4) launch_qgemm_wreg<4>(wr, d, X, packed, scale, zero, Y, stream);
+      else launch_qgemm_wreg<8>(wr, d, X, packed, scale, zero, Y, stream);
+      return;
+    }
+  }
   // more than 32 tokens: the general kernel reads the weights once per 64 tokens, the streaming form once per 32
   // smallest batches: activations and the tile's scale / zero in LDS
   if (d.T <= 16 && qgemm_decode_ok(d)) {
