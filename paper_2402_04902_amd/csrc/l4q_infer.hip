@@ -311,9 +311,13 @@ __device__ __forceinline__ bf16x8_t code_fragment(const code_chunk_t& w, int f) 
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const uint32_t spread = __builtin_amdgcn_ubfe(v, 8 * r, 8) * 0x1001u;
-      uint32_t pair;  // (spread & mask) | bias in one instruction: one constant in a scalar, one in a vector register
-      asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(pair) : "v"(spread), "s"(0x000F000Fu), "v"(0x43004300u));
-      d[r] = pair;
+      // ((x & mask) | bias as one v_and_or_b32: the constants are made opaque so that they stay in registers - the op
+      // takes no literals; the op itself is left to the compiler: as inline assembly it would hide that a vector op wrote
+      // the register, and the wait states a matrix op needs before it reads such a register would be missing)
+      uint32_t mask = 0x000F000Fu, bias = 0x43004300u;
+      asm("" : "+s"(mask));
+      asm("" : "+v"(bias));
+      d[r] = (spread & mask) | bias;
     }
   } else if (BITS == 2) {
     // the chunk's first two dwords hold 32 codes; fragment f is the 16-bit half f % 2 of dword f / 2, its code pairs are
@@ -1263,11 +1267,22 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
   // the one D steps ahead into it.
   constexpr int S = 2 * CPW, D = CPW == 3 ? 3 : (CPW == 2 && NT == 1) ? 4 : 2;  // (what 128 registers hold)
   constexpr int WW = BITS == 8 ? 8 : 4;
+#ifndef WR_PRE
+#define WR_PRE (NT * S <= 2 ? S : 0)
+#endif
+  constexpr int PRE = WR_PRE;  // steps whose weights are requested ahead of the tables' barrier
   // 4 bits: the four dwords of a lane's piece are exchanged with those of the three other lanes of its row (a 4 x 4
   // transpose over lane group and dword, two lane-swap steps, once per kernel), so that op d covers
   // k = 128 h + {32 d + 8 kq + j} and the four lanes of a token read 64 contiguous bytes of it per load: the
   // activation loads touch half as many cache lines, and they set the time per token block.
   constexpr bool XT = BITS == 4;
+  // (x & mask) | bias as one v_and_or_b32 needs the two constants in registers (one scalar, one vector): they are
+  // made opaque so that the compiler keeps them there instead of folding them into two ops with literals.  (The op
+  // itself is left to the compiler: written as inline assembly it would hide from the compiler that a vector op
+  // wrote the register, and the two wait states a matrix op needs before it reads such a register would be missing.)
+  uint32_t pair_mask = 0x000F000Fu, pair_bias = 0x43004300u;
+  asm volatile("" : "+s"(pair_mask));
+  asm volatile("" : "+v"(pair_bias));
   typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
   unsigned xoff[CPW][2];  // token ln of a block, k = chunk 256 + 128 h + 32 kq (+ 8 d: 16 bytes each); halves past i: off
 #pragma unroll
@@ -1291,10 +1306,10 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
   // the weight stream: everything this wave will ever read of it, requested now, in the order of the steps (loads
   // return in order: a step waits for exactly what it needs)
   uint32_t w[NT][CPW][2][WW];
+  auto load_w = [&](int st_from, int st_to) {
 #pragma unroll
-  for (int q = 0; q < CPW; ++q)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
+  for (int st = st_from; st < st_to; ++st) {
+      const int q = st / 2, h = st % 2;
       const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
 #pragma unroll
       for (int n = 0; n < NT; ++n) {
@@ -1321,7 +1336,12 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
         }
       }
     }
-  // the tables: written once the two pieces are here (the oldest loads in flight), visible after one barrier
+  };
+  // The tables: written once the two pieces are here (the oldest loads in flight), visible after one barrier - which
+  // every wave reaches before it requests its weights: a wave cannot issue its whole stream at once (the memory
+  // pipeline of the compute unit takes so many requests), and behind the stream the barrier would complete only when
+  // most of it had arrived (3 us into a 6.5 us kernel), with all the arithmetic still to do.
+  load_w(0, PRE);
   if (tab_thread) {
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -1331,6 +1351,7 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
       }
   }
   __syncthreads();
+  load_w(PRE, S);
   const float* tab_row = tab + ln * pitch * 2;  // this lane's row of the first tile
   int grp[CPW][2];  // group of each step, capped to the table
 #pragma unroll
@@ -1402,8 +1423,7 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
               u32x4 f;
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
-                const uint32_t sh = c[d] >> (4 * e);
-                asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(f[e]) : "v"(sh), "s"(0x000F000Fu), "v"(0x43004300u));
+                f[e] = ((c[d] >> (4 * e)) & pair_mask) | pair_bias;
               }
               wf = __builtin_bit_cast(bf16x8_t, f);
             } else {
@@ -1551,20 +1571,23 @@ TilePlan qgemm_tile_plan(const LayerDims& d) {
 
 // How the weights-in-registers kernel would run this layer: tiles per workgroup and chunks per wave (nt = 0: not at
 // all, or not faster than the streaming forms).  Measured against those (us; T = 1 / 5 / 16 / 33 / 64):
-//   4 bits [11008 x 4096] (3 tiles, 1 chunk): 8.3 / 8.9 / 11.2 / 18.2 / 24.0 against 7.1 / 12.8 / 17.1 / 26.6 / 27.8;
-//          [4096 x 4096] (1, 1): 4.5 / 5.0 / 6.9 / 12.0 / 17.9 against 4.8 / 5.3 / 6.5 / 12.9 / 14.1;
-//          [8192 x 8192] (2, 2): 10.7 / 11.3 / 14.7 / 26.7 / 38.5 against 9.7 / 14.7 / 28.8 / 29.5 / 31.2;
-//          [4096 x 11008] (1, 3): 9.6 / 10.4 / 15.2 / 29.4 / 45.4 against 8.8 / 10.0 / 15.6 / 23.7 / 25.1 (every
+//   4 bits [11008 x 4096] (3 tiles, 1 chunk): 6.9 / 7.6 / 9.9 / 18.2 / 23.9 against 7.2 / 12.6 / 16.9 / 27.1 / 28.1;
+//          [16384 x 4096] (4, 1): 8.5 / 9.5 / 11.7 / 21.7 / 28.3 against 9.6 / 17.1 / 22.5 / 27.9 / 29.6;
+//          [4096 x 4096] (1, 1): 4.7 / 5.6 / 6.9 / 12.1 / 17.8 against 4.7 / 5.3 / 6.4 / 12.9 / 14.2;
+//          [8192 x 8192] (2, 2): 10.2 / 11.0 / 15.0 / 27.5 / 38.6 against 10.0 / 14.6 / 28.6 / 30.1 / 31.5;
+//          [4096 x 11008] (1, 3): 9.0 / 10.4 / 15.4 / 30.1 / 45.1 against 8.6 / 9.9 / 15.6 / 24.1 / 25.3 (every
 //          compute unit reads the whole of X for its 16 rows: the time per token block grows with the chunks per wave);
-//   3 bits [11008 x 4096]: 8.8 / 9.5 / 11.8 / 20.1 / 25.3 against 9.7 / 15.2 / 22.2 / 32.8 / 35.1;
-//          [4096 x 11008]: 9.6 / 10.3 / 14.0 / 29.3 / 44.2 against 11.6 / 19.9 / 20.1 / 28.9 / 27.9;
-//   2 bits [11008 x 4096]: 8.8 / 9.4 / 11.5 / 20.1 / 24.9 against 7.7 / 13.7 / 18.2 / 43.3 / 52.5;
-//          [4096 x 11008]: 9.2 / 9.9 / 14.0 / 29.1 / 44.0 against 10.0 / 11.3 / 25.3 / 40.0 / 55.3;
-//   8 bits [4096 x 4096]: 5.7 / 6.2 / 8.3 / 13.8 / 19.3 against 6.9 / 7.5 / 8.6 / 14.6 / 15.3.
+//   3 bits [11008 x 4096]: 7.5 / 8.2 / 10.5 / 20.2 / 26.0 against 9.7 / 15.2 / 22.2 / 33.0 / 35.8;
+//          [4096 x 11008]: 9.0 / 10.1 / 14.9 / 29.8 / 44.7 against 11.6 / 19.9 / 20.1 / 28.5 / 27.4;
+//   2 bits [11008 x 4096]: 7.3 / 8.2 / 10.2 / 20.1 / 25.7 against 7.7 / 13.8 / 18.3 / 43.6 / 54.0;
+//          [4096 x 11008]: 8.6 / 9.9 / 14.7 / 29.7 / 44.8 against 10.0 / 11.3 / 25.5 / 40.0 / 55.0;
+//   8 bits [4096 x 4096]: 5.7 / 6.2 / 8.3 / 13.8 / 19.1 against 7.3 / 8.2 / 8.6 / 14.5 / 15.0;
+//          [8192 x 4096] (2, 1): 7.5 / 8.0 / 10.1 / 19.9 / 25.8 against 9.0 / 13.0 / 16.1 / 22.8 / 22.8.
 struct WregPlan {
   int nt, cpw;
   unsigned grid;
 };
+inline int64_t plan_grid_rounds(int64_t tiles, int64_t nt, int64_t cus) { return ((tiles + nt - 1) / nt + cus - 1) / cus; }
 #ifndef L4Q_WREG_SWITCH
 #define L4Q_WREG_SWITCH true
 #endif
@@ -1589,23 +1612,28 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
   }
   if (!any_size) {
     const int64_t T = d.T;
-    int64_t lo = 2, hi = 16;
+    const bool few_tiles = 2 * tiles < cus;  // (the streaming forms split k further over the idle units)
+    int64_t lo = 1, hi = 0;
     if (d.bits == 4) {
-      if (cpw == 1) { lo = nt == 1 ? 1 : 2; hi = nt >= 3 ? 64 : 48; }
-      else if (cpw == 2) hi = nt == 2 ? 48 : 16;
-      else if (cpw == 3) lo = 6;
+      if (cpw == 1) { lo = nt == 1 ? 17 : 1; hi = nt >= 3 ? 64 : nt == 2 ? 48 : 40; }
+      else if (cpw == 2) { lo = nt == 2 ? 3 : 6; hi = nt == 2 ? 40 : 16; }
+      else if (cpw == 3) { lo = 6; hi = 16; }
+      else { lo = 3; hi = 16; }
+      if (few_tiles) { lo = 17; hi = cpw == 1 ? 64 : 0; }
     } else if (d.bits == 3) {
-      lo = 1;
-      if (cpw == 1) hi = nt >= 3 ? 64 : 48;
-      else if (cpw == 2 && nt == 2) hi = 64;
+      if (cpw == 1) hi = nt >= 3 ? 64 : nt == 2 ? 48 : 40;
+      else if (cpw == 2) hi = nt == 2 ? 64 : 16;
+      else hi = 32;
+      if (few_tiles && cpw == 1) hi = 64;
     } else if (d.bits == 2) {
-      lo = nt == 1 ? 1 : 2;
+      lo = nt == 1 && cpw == 1 ? 3 : 1;
       hi = 64;
-    } else {
-      if (cpw != 1 || nt != 1) return plan;
-      lo = 1; hi = 32;
+      if (few_tiles) lo = 17;
+    } else if (cpw == 1) {
+      lo = (int64_t)plan_grid_rounds(tiles, nt, cus) > 1 ? 2 : 1;
+      hi = lo > 1 ? 16 : 32;
+      if (few_tiles) { lo = 17; hi = 48; }
     }
-    if (2 * tiles < cus && lo < 17 && d.bits != 3) lo = 17;  // few tiles: the streaming forms split k further
     if (T < lo || T > hi) return plan;
   }
   plan.nt = (int)nt;

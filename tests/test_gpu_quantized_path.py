@@ -94,16 +94,16 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     # 256-wide chunks per wave (1 .. 4: up to 4096 / 8192 / 12288 / 16384 columns), for every code width that has it.
     # 4 bits: three tiles at 33 tokens with a ragged last tile; two tiles with half a chunk at the end of k; four
     # tiles with groups of 256; (1, 2); (2, 2) with groups of 512; (1, 3); (1, 4); (1, 4) with groups of 1024 and a
-    # ragged tile; one token on a 256-tile layer
+    # ragged tile; two token blocks on a 256-tile layer; four tiles over three token blocks; one token
     (33, 4096, 11000, 4, 128), (5, 2048 + 128, 6000, 4, 128), (40, 1024, 13000, 4, 256), (9, 8192, 3000, 4, 128),
     (20, 5120, 8000, 4, 512), (12, 11008, 4096, 4, 128), (7, 14336, 2400, 4, 128), (3, 16384, 2056, 4, 1024),
-    (1, 4096, 4096, 4, 128), (48, 4096, 12296, 4, 128),
+    (20, 4096, 4096, 4, 128), (48, 4096, 12296, 4, 128), (1, 4096, 11008, 4, 128),
     # 3 bits (12-byte pieces): (3, 1) over three token blocks, (1, 3), (2, 2), (1, 4) with groups of 256, one token
     (48, 4096, 11000, 3, 128), (16, 11008, 4096, 3, 128), (30, 8192, 8192, 3, 128), (2, 16384, 2056, 3, 256),
     (1, 4096, 4000, 3, 128),
-    # 2 bits (8-byte pieces): (3, 1), (2, 1) over four token blocks, (1, 3), (2, 2) with groups of 256, one token
+    # 2 bits (8-byte pieces): (3, 1), (2, 1) over four token blocks, (1, 3), (2, 2) with groups of 256, three tokens
     (5, 4096, 11008, 2, 128), (64, 4096, 6000, 2, 128), (16, 11008, 4096, 2, 128), (33, 8192, 8192, 2, 256),
-    (1, 4096, 4000, 2, 128),
+    (3, 4096, 4000, 2, 128),
     # 8 bits (one tile, one chunk only): one token, half a chunk at the end of k, groups of 256 with a ragged tile
     (1, 4096, 4096, 8, 128), (20, 2048 + 128, 4000, 8, 128), (32, 4096, 2072, 8, 256),
 ])
