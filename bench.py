@@ -274,11 +274,14 @@ def main() -> int:
 
         decode3["T%d" % tok] = time_decode(descs3, xs, packs3, ys, qfws3, tok)
     del packs3
-    # and at 2 bits, one token (the streaming one-token kernel covers 2, 4 and 8 bits)
+    # and at 2 bits, one token and one token block
     packs2 = [torch.randint(-2**31, 2**31 - 1, (l.spec.out_features, 2 * l.spec.in_features // 32), dtype=torch.int32,
                             device="cuda:0", generator=gen3) for l in layers]
-    descs2 = [binding.make_desc(l.spec.with_(tokens=1, bits=2)) for l in layers]
-    decode2 = {"T1": time_decode(descs2, [l.X[:1] for l in layers], packs2, [l.Y[:1] for l in layers], qfws, 1)}
+    decode2 = {}
+    for tok in (1, 16):
+        descs2 = [binding.make_desc(l.spec.with_(tokens=tok, bits=2)) for l in layers]
+        decode2["T%d" % tok] = time_decode(descs2, [l.X[:tok] for l in layers], packs2, [l.Y[:tok] for l in layers],
+                                           qfws, tok)
     del packs2
 
     # the QAT-LoRA layer (Sec. 3.1) on the same workload: separate LoRA path, stored weight gradient

@@ -5,10 +5,12 @@
 // row's little-endian bit string; rows are n * i / 32 words.
 //
 // Five kernels compute the product, chosen by launch_qgemm from the code width, the token count and the layer's
-// shape (each is described where it is defined): qgemm_decode_kernel (2 / 4 / 8 bits, activations resident in LDS),
-// qgemm_decode3_kernel (3 bits, likewise), qgemm_stream_kernel (4 / 8 bits, up to 32 tokens per pass),
-// qgemm_tile_kernel (3 / 4 / 8 bits, 64-row tiles, up to 64 tokens per pass, optionally in k-slices whose partial
-// sums qgemm_slices_sum_kernel adds), and qgemm_kernel, which covers every other layout:
+// shape (each is described where it is defined): qgemm_wreg_kernel (2 / 3 / 4 / 8 bits, groups of 128 and more, one
+// token to a few token blocks: the packed codes resident in registers, the activations streamed),
+// qgemm_decode_kernel (2 / 4 / 8 bits, activations resident in LDS, the weights streamed through rings),
+// qgemm_stream_kernel (4 / 8 bits, up to 32 tokens per pass), qgemm_tile_kernel (3 / 4 / 8 bits, 64-row tiles, up to
+// 64 tokens per pass, optionally in k-slices whose partial sums qgemm_slices_sum_kernel adds), and qgemm_kernel,
+// which covers every other layout:
 // qgemm_kernel: one workgroup = 32 weight rows, 8 waves splitting k in interleaved 64-wide chunks.
 // A lane owns one weight row: per chunk it loads the n words holding its 32 consecutive codes
 // (lane group 0: k 0..31 of the chunk, group 1: k 32..63), turns them into bf16 operands (integer codes with the
@@ -697,169 +699,6 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode_kernel(const bf16_t* __re
 #endif
 }
 
-// The same kernel for 3-bit codes.  A 128-byte stage is not a whole number of 3-bit codes; three stages (384 bytes =
-// 1024 codes) are, so the unit a wave streams, rings and consumes is such a super-stage, in 8 sub-steps of 128 codes:
-// lane group kg of sub-step h owns codes 32 (4 h + kg) .. + 31 = the 12 bytes from (4 h + kg) 12 of the row's 384, read
-// as three dwords (a piece can straddle two 16-byte chunks, or two stages, of the swizzled layout).  Rows need not be
-// whole cache lines nor whole super-stages (i = 11008: 4128 bytes, 10.75 super-stages): the activations sit in LDS with
-// every token padded with zeros to the next multiple of 1024 k-values, so whatever packed bytes follow a row's end
-// (the next row's codes, or zeros past the matrix) meet activations that are zero, and the padded groups' scale and
-// zero are the zeros of the table's own padding.  Fragment f of a piece is a 24-bit window; code pairs become bf16
-// pairs as for 4 bits, with 6-bit fields and 0x2001 as the spreading factor (K0 = 128 + 4).
-template <int NSS>
-__global__ __launch_bounds__(256, 2) void qgemm_decode3_kernel(const bf16_t* __restrict__ X,
-                                                                const uint32_t* __restrict__ packed,
-                                                                const float* __restrict__ scale,
-                                                                const float* __restrict__ zero,
-                                                                bf16_t* __restrict__ Y, int T, int o, int i, int g,
-                                                                int ipad, int sb_pitch) {
-  extern __shared__ __attribute__((aligned(1024))) unsigned char d3lds[];
-#if defined(__HIP_DEVICE_COMPILE__)
-  constexpr int ROWS = 16;
-  constexpr int STAGE = ROWS * 128, SS = 3 * STAGE;  // bytes of a stage and of a super-stage of one wave
-  typedef QsMfma<ROWS> M;
-  typedef typename M::acc_t acc_t;
-  constexpr int NACC = M::NACC;
-  constexpr int KG = 4, NH = 8, NDMA = 6;             // lane groups, sub-steps and DMA loads of a super-stage
-  constexpr int CH = 32, KS = 1024, FR = 4, SUB = 128;  // codes of a piece, a super-stage, fragments of a piece, codes of a sub-step
-  constexpr float K0 = 128.f + 4.f;
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  typedef gemm::lds_ptr_t lds_ptr_t;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int ln = lane % ROWS, kg = lane / ROWS;
-  const int p0 = blockIdx.x * ROWS;
-  const int p = p0 + ln;
-  const int rb = i / 8 * 3;        // bytes of a packed row
-  const int nss = ipad / KS;       // super-stages of a (padded) row
-  const int G = i / g, Gp = ipad / g;
-  const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-  const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
-  const int x_bytes = T * ipad * 2;
-
-  unsigned char* ring = d3lds + wave * (NSS * SS);
-  unsigned char* xl = d3lds + 4 * NSS * SS;                    // [T][ipad] bf16, zeros past i
-  float* sl = reinterpret_cast<float*>(xl + x_bytes);          // [16][sb_pitch]
-  float* bl = sl + ROWS * sb_pitch;
-
-  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint32_t*>(packed), 0, (int)((int64_t)o * rb), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrcX = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<bf16_t*>(X), 0, (int)((int64_t)T * i * 2), 0x00020000);
-  unsigned voff[2];
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int r = 8 * q + (lane >> 3);
-    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
-    voff[q] = p0 + r < o ? (unsigned)((p0 + r) * rb + chunk * 16) : gemm::OOB_OFFSET;
-  }
-  const int nj = wave < nss ? (nss - wave + 3) / 4 : 0;  // super-stages of this wave: wave, wave + 4, ...
-  auto issue_dma = [&](int j) {
-    unsigned char* dst = ring + (j % NSS) * SS;
-#pragma unroll
-    for (int s3 = 0; s3 < 3; ++s3) {
-      const unsigned kb = j < nj ? (unsigned)(3 * (wave + 4 * j) + s3) * 128u : gemm::PAST_END_OFFSET;
-#pragma unroll
-      for (int q = 0; q < 2; ++q)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(dst + s3 * STAGE + q * 1024), 16, voff[q] + kb, 0,
-                                                 0, 0);
-    }
-  };
-
-#pragma unroll
-  for (int j = 0; j < NSS - 1; ++j) issue_dma(j);
-  {  // X: 1 KiB pieces (512 k-values of one token) round-robin over the waves; k-values past i read as zero
-    const int ppr = ipad / 512;  // pieces per token
-    for (int u = wave; u < T * ppr; u += 4) {
-      const int t = u / ppr, c = u - t * ppr;
-      const int k = c * 512 + lane * 8;
-      const unsigned off = k < i ? (unsigned)(((int64_t)t * i + k) * 2) : gemm::OOB_OFFSET;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcX, (lds_ptr_t)(xl + (size_t)t * ipad * 2 + c * 1024), 16, off, 0, 0,
-                                               0);
-    }
-  }
-  {  // scale / zero rows of the tile, padded groups included (they read as zero)
-    const __amdgpu_buffer_rsrc_t rsrcS = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float*>(scale), 0, (int)((int64_t)o * G * 4), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrcZ = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float*>(zero), 0, (int)((int64_t)o * G * 4), 0x00020000);
-    const int per_row = (Gp + 63) / 64;
-    for (int u = wave; u < ROWS * per_row; u += 4) {
-      const int row = u / per_row, c = u - row * per_row;
-      const int idx = c * 64 + lane;
-      const unsigned off = idx < G && p0 + row < o ? (unsigned)(((p0 + row) * G + idx) * 4) : gemm::OOB_OFFSET;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcS, (lds_ptr_t)(sl + row * sb_pitch + c * 64), 4, off, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcZ, (lds_ptr_t)(bl + row * sb_pitch + c * 64), 4, off, 0, 0, 0);
-    }
-  }
-  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
-  __syncthreads();
-
-  const int swz = (ln >> 1) & 7;
-  const int tok = ln < T ? ln : T - 1;
-  const unsigned char* xrow = xl + (size_t)tok * ipad * 2;
-  const float* srow = sl + ln * sb_pitch;
-  const float* brow = bl + ln * sb_pitch;
-  // LDS offsets of the three dwords of this lane's piece in every sub-step, relative to the row's place in the slot
-  unsigned piece_off[NH][3];
-#pragma unroll
-  for (int h = 0; h < NH; ++h)
-#pragma unroll
-    for (int dw = 0; dw < 3; ++dw) {
-      const int byte = (4 * h + kg) * 12 + 4 * dw;
-      const int st = byte >> 7, b = byte & 127;
-      piece_off[h][dw] = (unsigned)(st * STAGE + (((b >> 4) ^ swz) << 4) + (b & 15));
-    }
-
-  acc_t acc;
-#pragma unroll
-  for (int e = 0; e < NACC; ++e) acc[e] = 0.f;
-
-  for (int j = 0; j < nj; ++j) {
-    issue_dma(j + NSS - 1);
-    __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm((NSS - 1) * NDMA));  // super-stage j has landed
-    __builtin_amdgcn_sched_barrier(0);
-    const unsigned char* src = ring + (j % NSS) * SS + ln * 128;
-    const int k0 = (wave + 4 * j) * KS;
-#pragma unroll
-    for (int h = 0; h < NH; ++h) {
-      const uint32_t d0 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][0]);
-      const uint32_t d1 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][1]);
-      const uint32_t d2 = *reinterpret_cast<const uint32_t*>(src + piece_off[h][2]);
-      const u32x4 w = {d0, d1, d2, 0u};
-      const int grp = (k0 + h * SUB) / g;
-      const float sc = srow[grp], bz = brow[grp] - K0 * sc;
-      acc_t tw, tx;
-#pragma unroll
-      for (int e = 0; e < NACC; ++e) { tw[e] = 0.f; tx[e] = 0.f; }
-#pragma unroll
-      for (int f = 0; f < FR; ++f) {
-        const bf16x8_t wf = code_fragment<3>(w, f);
-        const bf16x8_t xf = *reinterpret_cast<const bf16x8_t*>(xrow + (size_t)(k0 + (KG * h + kg) * CH + 8 * f) * 2);
-        tw = M::mma(xf, wf, tw);
-        tx = M::mma(xf, ones, tx);
-      }
-#pragma unroll
-      for (int e = 0; e < NACC; ++e) acc[e] = fmaf(bz, tx[e], fmaf(sc, tw[e], acc[e]));
-    }
-  }
-  __builtin_amdgcn_s_waitcnt(gemm::waitcnt_vm(0));
-  __syncthreads();  // every wave is done with its ring: the LDS is reused for the sum over the waves
-
-  float* red = reinterpret_cast<float*>(d3lds);
-#pragma unroll
-  for (int e = 0; e < NACC; ++e) red[(wave * NACC + e) * 64 + lane] = acc[e];
-  __syncthreads();
-  {
-    const int e = wave;  // wave w finishes register w: token 4 kg + w
-    const float v = (red[(0 * NACC + e) * 64 + lane] + red[(1 * NACC + e) * 64 + lane]) +
-                    (red[(2 * NACC + e) * 64 + lane] + red[(3 * NACC + e) * 64 + lane]);
-    const int t = M::token(e, kg);
-    if (t < T && p < o) Y[(int64_t)t * o + p] = f32_to_bf16(v);
-  }
-#endif
-}
-
 // Batches of up to 64 tokens per pass on wide layers (the smallest ones only when their activations do not fit the
 // kernel above).  One workgroup = 64 weight rows in four 16-row tiles, every wave walking its tile's whole row (or the
 // workgroup's k-slice of it), so all waves consume the same k-stage at the same time and can share its activations: a
@@ -881,8 +720,10 @@ __global__ __launch_bounds__(256, 2) void qgemm_decode3_kernel(const bf16_t* __r
 // rows sit in LDS too (odd row pitch), so the stage loop issues DMA loads only and its partial waits are exact.
 // BITS = 3: the activation side is that of 4 bits (256 k-values per stage, 32 codes per lane group and sub-step); the
 // weights of a row tile are streamed in units of three 128-byte stages = 1024 codes = four activation stages, held in
-// a ring of two units, and read as 12-byte pieces (see the 3-bit decode kernel above).  The activation ring has three
-// stages for every token-block count.
+// a ring of two units, and read as 12-byte pieces: lane group kg of sub-step h of a unit owns codes 32 (4 h + kg) .. +
+// 31 = the 12 bytes from (4 h + kg) 12 of the row's 384, three dwords that may straddle two 16-byte chunks or two
+// stages of the swizzled layout; fragment f of a piece is a 24-bit window whose code pairs are 6-bit fields.  The
+// activation ring has three stages for every token-block count.
 constexpr int qt_ring_stages(int token_blocks) { return token_blocks == 1 ? 8 : token_blocks == 2 ? 5 : token_blocks == 3 ? 4 : 3; }
 constexpr int QT_SLICES_MAX = 8;  // k-slices of a row tile at most
 constexpr int QT_ROWQ = 6;  // 16-byte pieces of a 64-row scale / zero block per thread: groups per row <= 96
@@ -1209,7 +1050,10 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
 // k assignment, 16 bytes per lane and op, from the L2; their sums per (token, half) come from ops against ones.  Each
 // token block ends with the partial sums of the 16 waves meeting in LDS (double-buffered: one barrier per block) and
 // 256 outputs per tile written by 256 threads.  With more than one token block the codes are converted again for
-// each block (the registers hold the packed codes, not the operands).
+// each block (the registers hold the packed codes, not the operands).  4 bits: the codes of a dword are paired
+// (j, j + 4), one shift and one mask-or per pair, and the activation fragment is permuted to match.
+// (Exchanging the dwords of a piece over the four lane groups of a row, so that the four lanes of a token read 64
+// contiguous bytes per load and the activation loads touch half as many cache lines, changed no time: dropped.)
 constexpr int WR_WAVES = 16;
 constexpr int WR_UNITS_MAX = 4;  // units (tiles x chunks) per wave that fit 128 registers
 
@@ -1271,11 +1115,7 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
 #define WR_PRE (NT * S <= 2 ? S : 0)
 #endif
   constexpr int PRE = WR_PRE;  // steps whose weights are requested ahead of the tables' barrier
-  // 4 bits: the four dwords of a lane's piece are exchanged with those of the three other lanes of its row (a 4 x 4
-  // transpose over lane group and dword, two lane-swap steps, once per kernel), so that op d covers
-  // k = 128 h + {32 d + 8 kq + j} and the four lanes of a token read 64 contiguous bytes of it per load: the
-  // activation loads touch half as many cache lines, and they set the time per token block.
-  constexpr bool XT = BITS == 4;
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
   // (x & mask) | bias as one v_and_or_b32 needs the two constants in registers (one scalar, one vector): they are
   // made opaque so that the compiler keeps them there instead of folding them into two ops with literals.  (The op
   // itself is left to the compiler: written as inline assembly it would hide from the compiler that a vector op
@@ -1290,7 +1130,7 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
-      xoff[q][h] = k0 < i ? (unsigned)((ln * i + k0 + kq * (XT ? 8 : 32)) * 2) : gemm::OOB_OFFSET;
+      xoff[q][h] = k0 < i ? (unsigned)((ln * i + k0 + kq * 32) * 2) : gemm::OOB_OFFSET;
     }
   bf16x8_t xb[D][4];
   auto load_x = [&](int buf, int q, int h, int tb) {  // tokens past T lie outside the buffer and read as zero
@@ -1298,7 +1138,7 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
 #pragma unroll
     for (int d = 0; d < 4; ++d)
       xb[buf][d] = __builtin_bit_cast(
-          bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xoff[q][h], sbase + d * (XT ? 64 : 16), 0));
+          bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xoff[q][h], sbase + d * 16, 0));
   };
 #pragma unroll
   for (int st = 0; st < D; ++st) load_x(st, st / 2, st % 2, 0);
@@ -1397,16 +1237,6 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
         // token blocks: the converted operands of every unit would not fit the registers)
 #pragma unroll
         for (int c = 0; c < (BITS == 8 ? 8 : BITS); ++c) asm volatile("" : "+v"(w[n][q][h][c]));
-        if constexpr (XT) {
-          if (tb == 0) {  // first use of the piece: transpose it
-            uint32_t (&p)[WW] = w[n][q][h];
-            const u32x2 a = __builtin_amdgcn_permlane32_swap(p[0], p[2], false, false);
-            const u32x2 b = __builtin_amdgcn_permlane32_swap(p[1], p[3], false, false);
-            const u32x2 c = __builtin_amdgcn_permlane16_swap(a[0], b[0], false, false);
-            const u32x2 e = __builtin_amdgcn_permlane16_swap(a[1], b[1], false, false);
-            p[0] = c[0]; p[1] = c[1]; p[2] = e[0]; p[3] = e[1];
-          }
-        }
         acc_t tw;
 #pragma unroll
         for (int e = 0; e < 4; ++e) tw[e] = 0.f;
@@ -1730,32 +1560,6 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
       else if (nsw == 4) L4Q_QD(8, 4);
       else L4Q_QD(8, 8);
 #undef L4Q_QD
-      return;
-    }
-  }
-  // 3 bits, smallest batches: the LDS-resident form with three-stage units
-  if (d.bits == 3 && d.T <= 16 && d.i % 128 == 0 && d.g % 128 == 0 && d.o * (d.i / 8 * 3) < (1ll << 31)) {
-    const int64_t ipad = (d.i + 1023) / 1024 * 1024;
-    const int64_t xb = d.T * ipad * 2;
-    const int64_t Gp = ipad / d.g, pitch = 64 * ((Gp + 63) / 64) + 1;
-    const int64_t sbb = 2 * 16 * pitch * 4;
-    const int64_t tiles = (d.o + 15) / 16;
-    const auto fits = [&](int n) { return 4 * n * 3 * 2048 + xb + sbb <= QD_LDS_MAX; };
-    int nss = tiles <= device_compute_units() && fits(3) ? 3 : 2;  // a lone workgroup per unit keeps more in flight
-    if (xb <= 96 * 1024 && sbb <= QD_SB_MAX && fits(nss)) {
-      const size_t lds_bytes = (size_t)(4 * nss * 3 * 2048 + xb + sbb);
-      dim3 sgrid((unsigned)tiles);
-#define L4Q_QD3(N)                                                                                                 \
-  do {                                                                                                             \
-    if (lds_bytes > 64 * 1024)                                                                                     \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_decode3_kernel<N>),                           \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                           \
-    hipLaunchKernelGGL((qgemm_decode3_kernel<N>), sgrid, dim3(256), lds_bytes, stream, X, packed, scale, zero, Y,  \
-                       (int)d.T, (int)d.o, (int)d.i, d.g, (int)ipad, (int)pitch);                                  \
-  } while (0)
-      if (nss == 2) L4Q_QD3(2);
-      else L4Q_QD3(3);
-#undef L4Q_QD3
       return;
     }
   }

@@ -135,24 +135,23 @@ def test_quantized_forward_weights_in_registers(T, i, o, bits, g):
     # boundary inside a group (g = 1024); 8-bit; two passes; stage counts that do not divide by the slices)
     (64, 11008, 4096, 4, 128), (33, 8192, 8192, 4, 128), (48, 5120, 5000, 4, 1024), (80, 2304, 4104, 8, 128),
     (17, 4096, 4096, 4, 128),
-    # 3 bits at the smallest batches: the LDS-resident form on three-stage units; both projections (rows of 11008
-    # codes are neither whole cache lines nor whole units), ragged row tiles, row lengths of 1.125, 2 and 1/8 units,
-    # groups of two sub-steps, 16 tokens
+    # 3 bits at the smallest batches: both projections (rows of 11008 codes are neither whole cache lines nor whole
+    # three-stage units), ragged row tiles, row lengths of 1.125, 2 and 1/8 units, groups of 256, 16 tokens
     (1, 4096, 11008, 3, 128), (1, 11008, 4096, 3, 128), (12, 4096, 1000, 3, 128), (5, 1152, 264, 3, 128),
     (16, 2048, 72, 3, 256), (3, 128, 40, 3, 128), (4, 11008, 4096, 3, 128),
-    # 3 bits beyond the LDS-resident form: 64-row tiles with weights in units of three stages; both projections (the
-    # narrow one in k-slices of whole units, the last one short), one to three token blocks per pass, two passes, a
-    # row of less than one unit, ragged last row tile, groups of two sub-steps
+    # 3 bits at larger batches (64-row tiles with weights in units of three stages where the in-register form does
+    # not take the case): both projections (the narrow one in k-slices of whole units, the last one short), one to
+    # three token blocks per pass, two passes, a row of less than one unit, ragged last row tile, groups of 256
     (64, 4096, 11008, 3, 128), (40, 11008, 4096, 3, 128), (16, 4096, 10240, 3, 128), (33, 1024, 10312, 3, 256),
     (24, 2048, 10304, 3, 128), (70, 768, 10248, 3, 128),
-    # ... and few tokens on narrow layers whose activations do not fit the LDS-resident form: k-slices at any batch size
+    # ... and few tokens on narrow layers
     (16, 4096, 4096, 3, 128), (7, 11008, 4096, 3, 128),
     # 70B-class projections: the widest layer at a small batch, the longest rows (too many groups for the tile kernel's
     # tables: the streaming forms take it)
     (4, 8192, 28672, 4, 128), (40, 28672, 8192, 4, 128),
-    # 2 bits in the LDS-resident form (half-chunk sub-steps): both projections at one token and a few (rows of 11008
-    # codes are 21.5 stages: the last stage runs into the next row), groups of two sub-steps, a ragged row tile, a row
-    # of less than one stage, 12 tokens of a short row; beyond the activations' LDS room: the general kernel
+    # 2 bits at small batches (the LDS-resident form with half-chunk sub-steps on narrow layers, else the in-register
+    # form): both projections at one token and a few (rows of 11008 codes are 21.5 stages: the last stage runs into
+    # the next row), groups of 256, a ragged row tile, a row of less than one stage, 12 tokens of a short row
     (1, 4096, 11008, 2, 128), (1, 11008, 4096, 2, 128), (4, 4096, 11008, 2, 128), (8, 11008, 4096, 2, 128),
     (3, 2048, 1000, 2, 256), (5, 256, 40, 2, 128), (12, 1024, 264, 2, 128), (16, 4096, 520, 2, 128),
     # 4 and 8 bits with packed rows that are not whole stages (16-byte aligned only): the last stage is shared with
