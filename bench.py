@@ -238,6 +238,11 @@ def main() -> int:
                 for k in ks:
                     one(k)
             torch.cuda.synchronize()
+            # These kernels take less time than the host needs to enqueue one through the Python binding (6-9 us per
+            # call): a spinning kernel goes first, untimed, so that the host runs ahead and the timed launches are
+            # queued back to back by the time the GPU reaches the first event.  (The same 22.5 MB of codes per layer
+            # are read by every launch: they are served by the 256 MB memory-side cache, not HBM, after the first.)
+            torch.cuda._sleep(3_000_000)
             ev0.record()
             for _ in range(50):
                 for k in ks:
@@ -257,6 +262,30 @@ def main() -> int:
         xs = [l.X[:tok] for l in layers]
         ys = [l.Y[:tok] for l in layers]
         decode["T%d" % tok] = time_decode(descs, xs, packs, ys, qfws, tok)
+
+    # one token again, each launch on another of 12 copies of the layer's packed codes (270 MB per layer between two
+    # reads of the same copy: more than the 256 MB memory-side cache holds), so that the codes do come from HBM
+    cold = {}
+    for k, name in ((0, "up_11008x4096"), (1, "down_4096x11008")):
+        copies = [packs[k].clone() for _ in range(12)]
+        d1 = binding.make_desc(layers[k].spec.with_(tokens=1))
+        x1, y1 = layers[k].X[:1], layers[k].Y[:1]
+        for c in copies:
+            binding.l4q_quantized_forward(d1, x1, c, layers[k].scale, layers[k].zero, y1, qfws[k])
+        torch.cuda.synchronize()
+        torch.cuda._sleep(3_000_000)
+        ev0.record()
+        for rep in range(4):
+            for c in copies:
+                binding.l4q_quantized_forward(d1, x1, c, layers[k].scale, layers[k].zero, y1, qfws[k])
+        ev1.record()
+        torch.cuda.synchronize()
+        us = ev0.elapsed_time(ev1) * 1e3 / 48
+        sp = layers[k].spec
+        nb = packs[k].numel() * 4 + 2 * layers[k].scale.numel() * 4 + (sp.in_features + sp.out_features) * 2
+        cold[name] = {"us": us, "GB_per_s": nb / (us * 1e-6) / 1e9, "frac_hbm_8TBs": nb / (us * 1e-6) / 8e12}
+        del copies
+    decode["T1_codes_from_hbm"] = cold
 
     # the same leg at 3 bits (the paper's other code width) on the same two shapes: seeded random packed words, the
     # layers' scale / zero
