@@ -1054,11 +1054,14 @@ __global__ __launch_bounds__(NWV * 64) void qgemm_tile_kernel(const bf16_t* __re
 // (j, j + 4), one shift and one mask-or per pair, and the activation fragment is permuted to match.
 // (Exchanging the dwords of a piece over the four lane groups of a row, so that the four lanes of a token read 64
 // contiguous bytes per load and the activation loads touch half as many cache lines, changed no time: dropped.)
+// Two shapes of workgroup: WV = 16 waves with one token block per pass (TBP = 1; 128 registers per lane: up to 4 units per
+// wave), and WV = 8 waves with twice the chunks each and two token blocks per pass (TBP = 2; 256 registers: the codes
+// are converted once for 32 tokens, which is what the time per block is made of beyond one block).
 constexpr int WR_WAVES = 16;
 constexpr int WR_UNITS_MAX = 4;  // units (tiles x chunks) per wave that fit 128 registers
 
-template <int BITS, int NT, int CPW>
-__global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t* __restrict__ X,
+template <int BITS, int NT, int CPW, int WV = WR_WAVES, int TBP = 1>
+__global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __restrict__ X,
                                                                     const uint32_t* __restrict__ packed,
                                                                     const float* __restrict__ scale,
                                                                     const float* __restrict__ zero,
@@ -1066,7 +1069,8 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
   extern __shared__ __attribute__((aligned(1024))) unsigned char wlds[];
 #if defined(__HIP_DEVICE_COMPILE__)
   static_assert(BITS == 2 || BITS == 3 || BITS == 4 || BITS == 8, "bits");
-  static_assert(NT * CPW <= WR_UNITS_MAX, "units per wave");
+  static_assert(NT * CPW <= (WV == WR_WAVES ? WR_UNITS_MAX : 6), "units per wave");
+  static_assert((WV == 16 && TBP == 1) || (WV == 8 && TBP == 2), "workgroup shapes");
   typedef QsMfma<16> M;
   typedef typename M::acc_t acc_t;
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -1093,7 +1097,7 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
   // row's value of a group per unit straight from memory would touch 16 cache lines per wave-wide load, and the
   // kernel would spend more time on those loads than on the weight stream).  zero is stored as zero - K0 scale.
   const int ppr = (G + 3) / 4, pitch = G | 1;
-  float* tab = reinterpret_cast<float*>(wlds) + 2 * NT * WR_WAVES * 256;  // [NT * 16][pitch][scale, zero - K0 scale]
+  float* tab = reinterpret_cast<float*>(wlds) + 2 * NT * TBP * WV * 256;  // [NT * 16][pitch][scale, zero - K0 scale]
   const bool tab_thread = (int)threadIdx.x < NT * 16 * ppr;
   const int tab_nr = (int)threadIdx.x / ppr, tab_c = (int)threadIdx.x - tab_nr * ppr;
   float tab_sv[4], tab_zv[4];
@@ -1109,7 +1113,8 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
   // Steps of a token block: the wave's half-chunks (q, h) in order, S = 2 CPW of them.  The activations of a step (four
   // fragments per lane) sit in a ring of D buffers over the steps of all blocks: the step that frees a buffer requests
   // the one D steps ahead into it.
-  constexpr int S = 2 * CPW, D = CPW == 3 ? 3 : (CPW == 2 && NT == 1) ? 4 : 2;  // (what 128 registers hold)
+  constexpr int S = 2 * CPW;
+  constexpr int D = TBP == 2 ? 2 : CPW == 3 ? 3 : (CPW == 2 && NT == 1) ? 4 : 2;  // (what the registers hold)
   constexpr int WW = BITS == 8 ? 8 : 4;
 #ifndef WR_PRE
 #define WR_PRE (NT * S <= 2 ? S : 0)
@@ -1129,16 +1134,19 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
   for (int q = 0; q < CPW; ++q)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
+      const int k0 = (wave + WV * q) * 256 + h * 128;
       xoff[q][h] = k0 < i ? (unsigned)((ln * i + k0 + kq * 32) * 2) : gemm::OOB_OFFSET;
     }
-  bf16x8_t xb[D][4];
-  auto load_x = [&](int buf, int q, int h, int tb) {  // tokens past T lie outside the buffer and read as zero
-    const int sbase = tb * 16 * i * 2;
+  bf16x8_t xb[D][TBP][4];
+  auto load_x = [&](int buf, int q, int h, int pass) {  // tokens past T lie outside the buffer and read as zero
 #pragma unroll
-    for (int d = 0; d < 4; ++d)
-      xb[buf][d] = __builtin_bit_cast(
-          bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xoff[q][h], sbase + d * 16, 0));
+    for (int t = 0; t < TBP; ++t) {
+      const int sbase = (pass * TBP + t) * 16 * i * 2;
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+        xb[buf][t][d] = __builtin_bit_cast(
+            bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xoff[q][h], sbase + d * 16, 0));
+    }
   };
 #pragma unroll
   for (int st = 0; st < D; ++st) load_x(st, st / 2, st % 2, 0);
@@ -1150,7 +1158,7 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
 #pragma unroll
   for (int st = st_from; st < st_to; ++st) {
       const int q = st / 2, h = st % 2;
-      const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
+      const int k0 = (wave + WV * q) * 256 + h * 128;
 #pragma unroll
       for (int n = 0; n < NT; ++n) {
         const int row = ((int)blockIdx.x + n * (int)gridDim.x) * 16 + ln;
@@ -1198,37 +1206,42 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
   for (int q = 0; q < CPW; ++q)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int k0 = (wave + WR_WAVES * q) * 256 + h * 128;
+      const int k0 = (wave + WV * q) * 256 + h * 128;
       grp[q][h] = k0 < i ? k0 / g : 0;
     }
 
-  float* red = reinterpret_cast<float*>(wlds);  // [2][NT][16 waves][64 lanes][4]
-  const int ntb = (T + 15) / 16;
+  float* red = reinterpret_cast<float*>(wlds);  // [2][NT][TBP][WV waves][64 lanes][4]
+  const int ntb = (T + 16 * TBP - 1) / (16 * TBP);  // passes of TBP token blocks
   // one token block; par: the block's position in the ring's period (S steps per block, D buffers)
   auto block = [&](auto par, int tb) {
     constexpr int P = decltype(par)::value;
-    acc_t acc[NT];
+    acc_t acc[NT][TBP];
 #pragma unroll
     for (int n = 0; n < NT; ++n)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) acc[n][e] = 0.f;
+      for (int t = 0; t < TBP; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[n][t][e] = 0.f;
 #pragma unroll
     for (int st = 0; st < S; ++st) {
       const int q = st / 2, h = st % 2, buf = (P * S + st) % D;
-      acc_t xs;
+      acc_t xs[TBP];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) xs[e] = 0.f;
+      for (int t = 0; t < TBP; ++t) {
 #pragma unroll
-      for (int d = 0; d < 4; ++d) xs = M::mma(xb[buf][d], ones, xs);
-      if constexpr (BITS == 4) {
-        // 4 bits: the codes of a dword are paired (j, j + 4) - one shift and one mask-or per pair instead of three ops
-        // for the pair (2 j, 2 j + 1) - and the activations follow: elements (0 4 1 5 2 6 3 7) of each fragment
+        for (int e = 0; e < 4; ++e) xs[t][e] = 0.f;
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const u32x4 x = __builtin_bit_cast(u32x4, xb[buf][d]);
-          const u32x4 y = {__builtin_amdgcn_perm(x[2], x[0], 0x05040100u), __builtin_amdgcn_perm(x[2], x[0], 0x07060302u),
-                           __builtin_amdgcn_perm(x[3], x[1], 0x05040100u), __builtin_amdgcn_perm(x[3], x[1], 0x07060302u)};
-          xb[buf][d] = __builtin_bit_cast(bf16x8_t, y);
+        for (int d = 0; d < 4; ++d) xs[t] = M::mma(xb[buf][t][d], ones, xs[t]);
+        if constexpr (BITS == 4) {
+          // 4 bits: the codes of a dword are paired (j, j + 4) - one shift and one mask-or per pair instead of three
+          // ops for the pair (2 j, 2 j + 1) - and the activations follow: elements (0 4 1 5 2 6 3 7) of each fragment
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const u32x4 x = __builtin_bit_cast(u32x4, xb[buf][t][d]);
+            const u32x4 y = {__builtin_amdgcn_perm(x[2], x[0], 0x05040100u), __builtin_amdgcn_perm(x[2], x[0], 0x07060302u),
+                             __builtin_amdgcn_perm(x[3], x[1], 0x05040100u), __builtin_amdgcn_perm(x[3], x[1], 0x07060302u)};
+            xb[buf][t][d] = __builtin_bit_cast(bf16x8_t, y);
+          }
         }
       }
 #pragma unroll
@@ -1237,9 +1250,11 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
         // token blocks: the converted operands of every unit would not fit the registers)
 #pragma unroll
         for (int c = 0; c < (BITS == 8 ? 8 : BITS); ++c) asm volatile("" : "+v"(w[n][q][h][c]));
-        acc_t tw;
+        acc_t tw[TBP];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) tw[e] = 0.f;
+        for (int t = 0; t < TBP; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) tw[t][e] = 0.f;
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
           bf16x8_t wf;
@@ -1260,38 +1275,47 @@ __global__ __launch_bounds__(WR_WAVES * 64) void qgemm_wreg_kernel(const bf16_t*
               wf = code_fragment<BITS>(c, d);
             }
           }
-          tw = M::mma(xb[buf][d], wf, tw);
+#pragma unroll
+          for (int t = 0; t < TBP; ++t) tw[t] = M::mma(xb[buf][t][d], wf, tw[t]);
         }
         const int gofs = grp[q][h];
         const float2 sz = *reinterpret_cast<const float2*>(tab_row + n * 16 * pitch * 2 + gofs * 2);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[n][e] = fmaf(sz.x, tw[e], fmaf(sz.y, xs[e], acc[n][e]));
-        // units one after the other (their operands do not all fit the registers), each one's sums folded into the
-        // outputs before the next starts
-        asm volatile("" : "+v"(acc[n][0]), "+v"(acc[n][1]), "+v"(acc[n][2]), "+v"(acc[n][3]));
+        for (int t = 0; t < TBP; ++t) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[n][t][e] = fmaf(sz.x, tw[t][e], fmaf(sz.y, xs[t][e], acc[n][t][e]));
+          // units one after the other (their operands do not all fit the registers), each one's sums folded into
+          // the outputs before the next starts
+          asm volatile("" : "+v"(acc[n][t][0]), "+v"(acc[n][t][1]), "+v"(acc[n][t][2]), "+v"(acc[n][t][3]));
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       // the buffer is free: the step D ahead goes into it
       const int st2 = (st + D) % S, dtb = (st + D) / S;
       if (tb + dtb < ntb) load_x(buf, st2 / 2, st2 % 2, tb + dtb);
     }
-    float* buf = red + (tb & 1) * (NT * WR_WAVES * 256);
+    float* buf = red + (tb & 1) * (NT * TBP * WV * 256);
 #pragma unroll
     for (int n = 0; n < NT; ++n)
-      *reinterpret_cast<float4*>(buf + ((n * WR_WAVES + wave) * 64 + lane) * 4) =
-          make_float4(acc[n][0], acc[n][1], acc[n][2], acc[n][3]);
+#pragma unroll
+      for (int t = 0; t < TBP; ++t)
+        *reinterpret_cast<float4*>(buf + (((n * TBP + t) * WV + wave) * 64 + lane) * 4) =
+            make_float4(acc[n][t][0], acc[n][t][1], acc[n][t][2], acc[n][t][3]);
     __syncthreads();
-    {
-      // thread -> (tile n, token te of the block, row r): 16 consecutive threads = 16 consecutive rows of one token
-      const int n = (int)threadIdx.x >> 8, idx = (int)threadIdx.x & 255;
+#pragma unroll
+    for (int it = 0; it < (NT * TBP * 256 + WV * 64 - 1) / (WV * 64); ++it) {
+      // thread -> (tile n, block t of the pass, token te of the block, row r): 16 consecutive threads = 16
+      // consecutive rows of one token
+      const int u = it * (WV / 4) + ((int)threadIdx.x >> 8), idx = (int)threadIdx.x & 255;
       const int r = idx & 15, te = idx >> 4;
-      if (n < NT) {
-        const float* src = buf + n * WR_WAVES * 256 + ((te >> 2) * 16 + r) * 4 + (te & 3);
+      if (u < NT * TBP) {
+        const int n = u / TBP, t = u - n * TBP;
+        const float* src = buf + u * WV * 256 + ((te >> 2) * 16 + r) * 4 + (te & 3);
         float v = src[0];
 #pragma unroll
-        for (int wv = 1; wv < WR_WAVES; ++wv) v += src[wv * 256];
-        const int row = ((int)blockIdx.x + n * (int)gridDim.x) * 16 + r, t = tb * 16 + te;
-        if (t < T && row < o) Y[(int64_t)t * o + row] = f32_to_bf16(v);
+        for (int wv = 1; wv < WV; ++wv) v += src[wv * 256];
+        const int row = ((int)blockIdx.x + n * (int)gridDim.x) * 16 + r, tok = (tb * TBP + t) * 16 + te;
+        if (tok < T && row < o) Y[(int64_t)tok * o + row] = f32_to_bf16(v);
       }
     }
   };
@@ -1416,6 +1440,7 @@ TilePlan qgemm_tile_plan(const LayerDims& d) {
 struct WregPlan {
   int nt, cpw;
   unsigned grid;
+  int wv, tbp;  // waves per workgroup, token blocks per pass
 };
 inline int64_t plan_grid_rounds(int64_t tiles, int64_t nt, int64_t cus) { return ((tiles + nt - 1) / nt + cus - 1) / cus; }
 #ifndef L4Q_WREG_SWITCH
@@ -1424,8 +1449,11 @@ inline int64_t plan_grid_rounds(int64_t tiles, int64_t nt, int64_t cus) { return
 #ifndef L4Q_WREG_ANY
 #define L4Q_WREG_ANY false
 #endif
+#ifndef L4Q_WREG_TWO_BLOCKS
+#define L4Q_WREG_TWO_BLOCKS true
+#endif
 WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
-  WregPlan plan = {0, 0, 0};
+  WregPlan plan = {0, 0, 0, WR_WAVES, 1};
   if (d.bits != 2 && d.bits != 3 && d.bits != 4 && d.bits != 8) return plan;
   const int64_t rb = d.i / 8 * d.bits;
   if (d.i % 128 != 0 || d.g % 128 != 0 || d.o * rb >= (1ll << 31) || d.T * d.i * 2 >= (1ll << 31) ||
@@ -1447,7 +1475,7 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
     if (d.bits == 4) {
       if (cpw == 1) { lo = nt == 1 ? 17 : 1; hi = nt >= 3 ? 64 : nt == 2 ? 48 : 40; }
       else if (cpw == 2) { lo = nt == 2 ? 3 : 6; hi = nt == 2 ? 40 : 16; }
-      else if (cpw == 3) { lo = 6; hi = 16; }
+      else if (cpw == 3) hi = 0;
       else { lo = 3; hi = 16; }
       if (few_tiles) { lo = 17; hi = cpw == 1 ? 64 : 0; }
     } else if (d.bits == 3) {
@@ -1465,6 +1493,18 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
       if (few_tiles) { lo = 17; hi = 48; }
     }
     if (T < lo || T > hi) return plan;
+    // One pass of two token blocks (17 .. 32 tokens) on layers of up to 16 chunks: 8 waves with two chunks each convert
+    // the codes once for both blocks (4 bits: [11008 x 4096] 11.3 / 13.7 us at 17 / 32 tokens against 13.4 / 18;
+    // [8192 x 4096] 9.2 / 12.0 against 10.8 / 15; [4096 x 4096] 7.9 / 10.4 against 8.3 / 12).
+    const int64_t cpw8 = (chunks + 7) / 8;
+    if (L4Q_WREG_TWO_BLOCKS && d.bits != 8 && T > 16 && T <= 32 && cpw8 <= 2 && nt <= 3 && nt * 16 * ((d.i / d.g + 3) / 4) <= 512) {
+      plan.wv = 8;
+      plan.tbp = 2;
+      plan.nt = (int)nt;
+      plan.cpw = (int)cpw8;
+      plan.grid = (unsigned)((tiles + nt - 1) / nt);
+      return plan;
+    }
   }
   plan.nt = (int)nt;
   plan.cpw = (int)cpw;
@@ -1476,22 +1516,30 @@ template <int BITS>
 void launch_qgemm_wreg(const WregPlan& plan, const LayerDims& d, const bf16_t* X, const uint32_t* packed,
                        const float* scale, const float* zero, bf16_t* Y, hipStream_t stream) {
   const int64_t G = d.i / d.g;
-  const size_t lds_bytes = ((size_t)2 * plan.nt * WR_WAVES * 256 + (size_t)2 * plan.nt * 16 * (G | 1)) * sizeof(float);
-#define L4Q_WR(N, C)                                                                                                 \
+  const size_t lds_bytes =
+      ((size_t)2 * plan.nt * plan.tbp * plan.wv * 256 + (size_t)2 * plan.nt * 16 * (G | 1)) * sizeof(float);
+#define L4Q_WR(N, C, W, P)                                                                                          \
   do {                                                                                                               \
     if (lds_bytes > 64 * 1024)                                                                                       \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_wreg_kernel<BITS, N, C>),                       \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_wreg_kernel<BITS, N, C, W, P>),                 \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                             \
-    hipLaunchKernelGGL((qgemm_wreg_kernel<BITS, N, C>), dim3(plan.grid), dim3(WR_WAVES * 64), lds_bytes, stream, X,  \
+    hipLaunchKernelGGL((qgemm_wreg_kernel<BITS, N, C, W, P>), dim3(plan.grid), dim3(W * 64), lds_bytes, stream, X,   \
                        packed, scale, zero, Y, (int)d.T, (int)d.o, (int)d.i, d.g);                                   \
   } while (0)
   const int key = plan.nt * 10 + plan.cpw;
-  if constexpr (BITS == 8) {
-    if (key == 11) L4Q_WR(1, 1); else if (key == 21) L4Q_WR(2, 1); else L4Q_WR(1, 2);
+  // (every combination qgemm_wreg_plan can return, and no other)
+  if (plan.wv == 8) {
+    if constexpr (BITS != 8) {
+      if (key == 11) L4Q_WR(1, 1, 8, 2); else if (key == 21) L4Q_WR(2, 1, 8, 2); else if (key == 31) L4Q_WR(3, 1, 8, 2);
+      else if (key == 12) L4Q_WR(1, 2, 8, 2); else if (key == 22) L4Q_WR(2, 2, 8, 2); else L4Q_WR(3, 2, 8, 2);
+    }
+  } else if constexpr (BITS == 8) {
+    if (key == 11) L4Q_WR(1, 1, 16, 1); else if (key == 21) L4Q_WR(2, 1, 16, 1); else L4Q_WR(1, 2, 16, 1);
   } else {
-    if (key == 11) L4Q_WR(1, 1); else if (key == 21) L4Q_WR(2, 1); else if (key == 31) L4Q_WR(3, 1);
-    else if (key == 41) L4Q_WR(4, 1); else if (key == 12) L4Q_WR(1, 2); else if (key == 22) L4Q_WR(2, 2);
-    else if (key == 13) L4Q_WR(1, 3); else L4Q_WR(1, 4);
+    if (key == 11) L4Q_WR(1, 1, 16, 1); else if (key == 21) L4Q_WR(2, 1, 16, 1); else if (key == 31) L4Q_WR(3, 1, 16, 1);
+    else if (key == 41) L4Q_WR(4, 1, 16, 1); else if (key == 12) L4Q_WR(1, 2, 16, 1); else if (key == 22) L4Q_WR(2, 2, 16, 1);
+    else if (key == 14) L4Q_WR(1, 4, 16, 1);
+    else if constexpr (BITS != 4) L4Q_WR(1, 3, 16, 1);  // (4 bits: one register too many, and no faster than the streaming forms)
   }
 #undef L4Q_WR
 }

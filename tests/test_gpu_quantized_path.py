@@ -93,7 +93,7 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     # combination of row tiles per workgroup (1 .. 4: up to 4096 / 8192 / 12288 / more rows on 256 compute units) and
     # 256-wide chunks per wave (1 .. 4: up to 4096 / 8192 / 12288 / 16384 columns), for every code width that has it.
     # 4 bits: three tiles at 33 tokens with a ragged last tile; two tiles with half a chunk at the end of k; four
-    # tiles with groups of 256; (1, 2); (2, 2) with groups of 512; (1, 3); (1, 4); (1, 4) with groups of 1024 and a
+    # tiles with groups of 256; (1, 2); (2, 2) with groups of 512; three chunks (4 bits: a streaming form); (1, 4); (1, 4) with groups of 1024 and a
     # ragged tile; two token blocks on a 256-tile layer; four tiles over three token blocks; one token
     (33, 4096, 11000, 4, 128), (5, 2048 + 128, 6000, 4, 128), (40, 1024, 13000, 4, 256), (9, 8192, 3000, 4, 128),
     (20, 5120, 8000, 4, 512), (12, 11008, 4096, 4, 128), (7, 14336, 2400, 4, 128), (3, 16384, 2056, 4, 1024),
@@ -106,6 +106,15 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     (3, 4096, 4000, 2, 128),
     # 8 bits (one tile, one chunk only): one token, half a chunk at the end of k, groups of 256 with a ragged tile
     (1, 4096, 4096, 8, 128), (20, 2048 + 128, 4000, 8, 128), (32, 4096, 2072, 8, 256),
+    # 17 .. 32 tokens on layers of up to 4096 columns: the 8-wave shape of the same kernel (two chunks per wave, two
+    # token blocks per pass), every tiles x chunks combination it has, at 4, 3 and 2 bits; a ragged last tile, half a
+    # chunk at the end of k, groups of 256, a partial second block
+    (24, 4096, 11000, 4, 128), (24, 4096, 11000, 3, 128), (24, 4096, 11000, 2, 128),
+    (17, 4096, 6000, 4, 128), (17, 4096, 6000, 3, 128), (17, 4096, 6000, 2, 128),
+    (32, 2176, 4000, 4, 128), (32, 2176, 4000, 3, 128), (32, 2176, 4000, 2, 128),
+    (20, 2048, 11008, 4, 128), (20, 2048, 11008, 3, 128), (20, 2048, 11008, 2, 128),
+    (25, 1024, 6008, 4, 256), (25, 1024, 6008, 3, 256), (25, 1024, 6008, 2, 256),
+    (31, 1152, 1000, 4, 128), (31, 1152, 1000, 3, 128), (31, 1152, 1000, 2, 128),
 ])
 def test_quantized_forward_weights_in_registers(T, i, o, bits, g):
     test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
