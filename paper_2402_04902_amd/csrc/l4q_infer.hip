@@ -1493,11 +1493,12 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
       if (few_tiles) { lo = 17; hi = 48; }
     }
     if (T < lo || T > hi) return plan;
-    // One pass of two token blocks (17 .. 32 tokens) on layers of up to 16 chunks: 8 waves with two chunks each convert
-    // the codes once for both blocks (4 bits: [11008 x 4096] 11.3 / 13.7 us at 17 / 32 tokens against 13.4 / 18;
-    // [8192 x 4096] 9.2 / 12.0 against 10.8 / 15; [4096 x 4096] 7.9 / 10.4 against 8.3 / 12).
+    // Whole passes of two token blocks (17 .. 32 and 49 .. 64 tokens) on layers of up to 16 chunks: 8 waves with two
+    // chunks each convert the codes once for both blocks (4 bits: [11008 x 4096] 11.1 / 13.6 us at 17 / 32 tokens
+    // against 13.0 / 15.5, 22.7 against 24.3 at 64; [8192 x 4096] 9.3 / 11.9 against 10.9 / 13.1; [4096 x 4096]
+    // 7.7 / 10.3 against 8.3 / 10.7; 2 bits [11008 x 4096] at 64 tokens: 22.9 against 25.7).
     const int64_t cpw8 = (chunks + 7) / 8;
-    if (L4Q_WREG_TWO_BLOCKS && d.bits != 8 && T > 16 && T <= 32 && cpw8 <= 2 && nt <= 3 && nt * 16 * ((d.i / d.g + 3) / 4) <= 512) {
+    if (L4Q_WREG_TWO_BLOCKS && d.bits != 8 && T > 16 && (T <= 32 || T > 48) && cpw8 <= 2 && nt <= 3 && nt * 16 * ((d.i / d.g + 3) / 4) <= 512) {
       plan.wv = 8;
       plan.tbp = 2;
       plan.nt = (int)nt;

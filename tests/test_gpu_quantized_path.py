@@ -115,6 +115,8 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     (20, 2048, 11008, 4, 128), (20, 2048, 11008, 3, 128), (20, 2048, 11008, 2, 128),
     (25, 1024, 6008, 4, 256), (25, 1024, 6008, 3, 256), (25, 1024, 6008, 2, 256),
     (31, 1152, 1000, 4, 128), (31, 1152, 1000, 3, 128), (31, 1152, 1000, 2, 128),
+    # ... and two passes of it (49 .. 64 tokens), the last block partial
+    (64, 4096, 11000, 4, 128), (64, 4096, 11000, 3, 128), (64, 4096, 11000, 2, 128), (50, 4096, 6000, 2, 128),
 ])
 def test_quantized_forward_weights_in_registers(T, i, o, bits, g):
     test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
