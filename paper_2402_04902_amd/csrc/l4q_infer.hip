@@ -1138,14 +1138,15 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
       xoff[q][h] = k0 < i ? (unsigned)((ln * i + k0 + kq * 32) * 2) : gemm::OOB_OFFSET;
     }
   bf16x8_t xb[D][TBP][4];
-  auto load_x = [&](int buf, int q, int h, int pass) {  // tokens past T lie outside the buffer and read as zero
+  // (The block's first token goes into the per-lane offset, not the scalar one: the range check that makes tokens
+  // past T read as zero - and keeps the loads inside X - looks at the per-lane offset only.)
+  auto load_x = [&](int buf, int q, int h, int pass) {
 #pragma unroll
     for (int t = 0; t < TBP; ++t) {
-      const int sbase = (pass * TBP + t) * 16 * i * 2;
+      const unsigned voff = xoff[q][h] + (unsigned)((pass * TBP + t) * 16 * i * 2);
 #pragma unroll
       for (int d = 0; d < 4; ++d)
-        xb[buf][t][d] = __builtin_bit_cast(
-            bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, xoff[q][h], sbase + d * 16, 0));
+        xb[buf][t][d] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrcX, voff, d * 16, 0));
     }
   };
 #pragma unroll
@@ -1461,7 +1462,7 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
     return plan;
   const int64_t tiles = (d.o + 15) / 16, chunks = (d.i + 255) / 256, cus = device_compute_units();
   const int64_t cpw = (chunks + WR_WAVES - 1) / WR_WAVES;
-  if (cpw > WR_UNITS_MAX) return plan;
+  if (cpw > WR_UNITS_MAX || (d.bits == 4 && cpw == 3)) return plan;  // (4 bits, three chunks: not instantiated)
   int64_t nt = (tiles + cus - 1) / cus;
   if (nt > WR_UNITS_MAX / cpw) nt = WR_UNITS_MAX / cpw;
   if (d.bits == 8) {  // twice the registers per unit
@@ -1475,7 +1476,6 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
     if (d.bits == 4) {
       if (cpw == 1) { lo = nt == 1 ? 17 : 1; hi = nt >= 3 ? 64 : nt == 2 ? 48 : 40; }
       else if (cpw == 2) { lo = nt == 2 ? 3 : 6; hi = nt == 2 ? 40 : 16; }
-      else if (cpw == 3) hi = 0;
       else { lo = 3; hi = 16; }
       if (few_tiles) { lo = 17; hi = cpw == 1 ? 64 : 0; }
     } else if (d.bits == 3) {
