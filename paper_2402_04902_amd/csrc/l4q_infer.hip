@@ -1065,7 +1065,8 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
                                                                     const uint32_t* __restrict__ packed,
                                                                     const float* __restrict__ scale,
                                                                     const float* __restrict__ zero,
-                                                                    bf16_t* __restrict__ Y, int T, int o, int i, int g) {
+                                                                    bf16_t* __restrict__ Y, float* __restrict__ part,
+                                                                    int T, int o, int i, int g) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char wlds[];
 #if defined(__HIP_DEVICE_COMPILE__)
   static_assert(BITS == 2 || BITS == 3 || BITS == 4 || BITS == 8, "bits");
@@ -1082,6 +1083,14 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
   const int rb = i / 8 * BITS, G = i / g;
   const u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
   const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, ones_bits);
+  // k-slices (gridDim.y > 1: layers with long rows and few row tiles, whose units would otherwise each read the whole
+  // of X for 16 rows): slice s takes chunks s WV CPW .. + WV CPW - 1 and writes binary32 partial sums
+  // part[slice][token][row], which qgemm_slices_sum_kernel adds in slice order
+  const int chunk0 = (int)blockIdx.y * (WV * CPW) + wave;  // this wave's first chunk; the others follow at WV apart
+  const int grp0 = (int)blockIdx.y * (WV * CPW) * 256 / g;  // first group the slice meets; the tables start there
+  int Gs = (((int)blockIdx.y + 1) * (WV * CPW) * 256 + g - 1) / g;
+  Gs = (Gs < G ? Gs : G) - grp0;
+  if (Gs < 1) Gs = 1;
 
   const __amdgpu_buffer_rsrc_t rsrcW = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint32_t*>(packed), 0, (int)((int64_t)o * rb), 0x00020000);
@@ -1096,14 +1105,14 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
   // per thread, requested ahead of everything else, and passed on through LDS in rows of odd pitch (a lane reading its
   // row's value of a group per unit straight from memory would touch 16 cache lines per wave-wide load, and the
   // kernel would spend more time on those loads than on the weight stream).  zero is stored as zero - K0 scale.
-  const int ppr = (G + 3) / 4, pitch = G | 1;
+  const int ppr = (Gs + 3) / 4, pitch = Gs | 1;
   float* tab = reinterpret_cast<float*>(wlds) + 2 * NT * TBP * WV * 256;  // [NT * 16][pitch][scale, zero - K0 scale]
   const bool tab_thread = (int)threadIdx.x < NT * 16 * ppr;
   const int tab_nr = (int)threadIdx.x / ppr, tab_c = (int)threadIdx.x - tab_nr * ppr;
   float tab_sv[4], tab_zv[4];
   {
     const int row = ((int)blockIdx.x + (tab_nr >> 4) * (int)gridDim.x) * 16 + (tab_nr & 15);
-    const unsigned off = tab_thread && row < o ? (unsigned)((row * G + 4 * tab_c) * 4) : gemm::OOB_OFFSET;
+    const unsigned off = tab_thread && row < o ? (unsigned)((row * G + grp0 + 4 * tab_c) * 4) : gemm::OOB_OFFSET;
     const float4 sv = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrcS, off, 0, 0));
     const float4 zv = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rsrcZ, off, 0, 0));
     tab_sv[0] = sv.x; tab_sv[1] = sv.y; tab_sv[2] = sv.z; tab_sv[3] = sv.w;
@@ -1134,7 +1143,7 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
   for (int q = 0; q < CPW; ++q)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int k0 = (wave + WV * q) * 256 + h * 128;
+      const int k0 = (chunk0 + WV * q) * 256 + h * 128;
       xoff[q][h] = k0 < i ? (unsigned)((ln * i + k0 + kq * 32) * 2) : gemm::OOB_OFFSET;
     }
   bf16x8_t xb[D][TBP][4];
@@ -1159,7 +1168,7 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
 #pragma unroll
   for (int st = st_from; st < st_to; ++st) {
       const int q = st / 2, h = st % 2;
-      const int k0 = (wave + WV * q) * 256 + h * 128;
+      const int k0 = (chunk0 + WV * q) * 256 + h * 128;
 #pragma unroll
       for (int n = 0; n < NT; ++n) {
         const int row = ((int)blockIdx.x + n * (int)gridDim.x) * 16 + ln;
@@ -1194,7 +1203,7 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
   if (tab_thread) {
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-      if (4 * tab_c + c < G) {
+      if (4 * tab_c + c < Gs) {
         *reinterpret_cast<float2*>(tab + (tab_nr * pitch + 4 * tab_c + c) * 2) =
             make_float2(tab_sv[c], tab_zv[c] - K0 * tab_sv[c]);
       }
@@ -1207,8 +1216,8 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
   for (int q = 0; q < CPW; ++q)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int k0 = (wave + WV * q) * 256 + h * 128;
-      grp[q][h] = k0 < i ? k0 / g : 0;
+      const int k0 = (chunk0 + WV * q) * 256 + h * 128;
+      grp[q][h] = k0 < i ? k0 / g - grp0 : 0;
     }
 
   float* red = reinterpret_cast<float*>(wlds);  // [2][NT][TBP][WV waves][64 lanes][4]
@@ -1316,7 +1325,10 @@ __global__ __launch_bounds__(WV * 64) void qgemm_wreg_kernel(const bf16_t* __res
 #pragma unroll
         for (int wv = 1; wv < WV; ++wv) v += src[wv * 256];
         const int row = ((int)blockIdx.x + n * (int)gridDim.x) * 16 + r, tok = (tb * TBP + t) * 16 + te;
-        if (tok < T && row < o) Y[(int64_t)tok * o + row] = f32_to_bf16(v);
+        if (tok < T && row < o) {
+          if (part == nullptr) Y[(int64_t)tok * o + row] = f32_to_bf16(v);
+          else part[((int64_t)blockIdx.y * T + tok) * o + row] = v;
+        }
       }
     }
   };
@@ -1442,7 +1454,9 @@ struct WregPlan {
   int nt, cpw;
   unsigned grid;
   int wv, tbp;  // waves per workgroup, token blocks per pass
+  int slices;   // k-slices (partial sums through the caller's workspace)
 };
+constexpr int WR_SLICE_T_MIN = 8, WR_SLICE_T_MAX = 32;  // token counts the k-sliced form takes
 inline int64_t plan_grid_rounds(int64_t tiles, int64_t nt, int64_t cus) { return ((tiles + nt - 1) / nt + cus - 1) / cus; }
 #ifndef L4Q_WREG_SWITCH
 #define L4Q_WREG_SWITCH true
@@ -1453,21 +1467,53 @@ inline int64_t plan_grid_rounds(int64_t tiles, int64_t nt, int64_t cus) { return
 #ifndef L4Q_WREG_TWO_BLOCKS
 #define L4Q_WREG_TWO_BLOCKS true
 #endif
-WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
-  WregPlan plan = {0, 0, 0, WR_WAVES, 1};
+// k-slices the in-register kernel would use for this layer if it had a workspace (1: none): rows of more than 16
+// chunks on layers whose row tiles do not fill the compute units more than once
+int qgemm_wreg_slices(const LayerDims& d) {
+  if (d.bits != 2 && d.bits != 3 && d.bits != 4) return 1;
+  const int64_t tiles = (d.o + 15) / 16, chunks = (d.i + 255) / 256, cus = device_compute_units();
+  const int64_t slices = (chunks + WR_WAVES - 1) / WR_WAVES;
+  if (slices < 2 || slices > WR_UNITS_MAX || tiles > cus || 2 * tiles < cus) return 1;
+  return (int)slices;
+}
+
+WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false, bool have_workspace = false) {
+  WregPlan plan = {0, 0, 0, WR_WAVES, 1, 1};
   if (d.bits != 2 && d.bits != 3 && d.bits != 4 && d.bits != 8) return plan;
   const int64_t rb = d.i / 8 * d.bits;
   if (d.i % 128 != 0 || d.g % 128 != 0 || d.o * rb >= (1ll << 31) || d.T * d.i * 2 >= (1ll << 31) ||
       d.o * (d.i / d.g) * 4 >= (1ll << 31))
     return plan;
   const int64_t tiles = (d.o + 15) / 16, chunks = (d.i + 255) / 256, cus = device_compute_units();
+  // Long rows, few row tiles, a workspace: k-slices of 16 chunks, so that a unit holds 2 - 4 tiles x a 16th of their
+  // slice and reads a half to a quarter of X, plus one summing launch (4 bits, 8 / 16 tokens: [4096 x 11008] 11.6 / 13.4
+  // us against 12.8 / 16.0 for the streaming forms; [4096 x 8192] 9.4 / 10.9 against 8.4 / 15.8 (12.7 in one piece);
+  // [2400 x 14336] 10.6 / 12.0 against 17.9 / 22.4; at 17 .. 32 tokens in the 8-wave shape where three tiles do:
+  // [4096 x 8192] 11.9 - 14.6 against 14.4 - 15.0, [2400 x 14336] 13.3 - 15.6 against 17.2).
+  const int slices = have_workspace ? qgemm_wreg_slices(d) : 1;
+  if (slices > 1 && !any_size && d.T >= WR_SLICE_T_MIN && d.T <= WR_SLICE_T_MAX && d.i % d.g == 0) {
+    // tiles per workgroup: the fewest with which all slices' workgroups run at once (a second round for a few
+    // left-over workgroups would double the time: [4096 x 11008] in 3 slices of 86 x 3 tiles = 258 workgroups)
+    int64_t nt = (tiles * slices + cus - 1) / cus;
+    while ((tiles + nt - 1) / nt * slices > cus) ++nt;
+    const bool two = L4Q_WREG_TWO_BLOCKS && d.T > 16 && nt <= 3;  // 8 waves: a slice is 16 chunks = two per wave
+    if (nt <= (d.T > 16 && !two ? 0 : WR_UNITS_MAX) && nt * 16 * (((two ? 16 : WR_WAVES) * 256 / d.g + 1 + 3) / 4) <= (two ? 512 : 1024)) {
+      plan.nt = (int)nt;
+      plan.cpw = two ? 2 : 1;
+      plan.wv = two ? 8 : WR_WAVES;
+      plan.tbp = two ? 2 : 1;
+      plan.slices = slices;
+      plan.grid = (unsigned)((tiles + nt - 1) / nt);
+      return plan;
+    }
+  }
   const int64_t cpw = (chunks + WR_WAVES - 1) / WR_WAVES;
   if (cpw > WR_UNITS_MAX || (d.bits == 4 && cpw == 3)) return plan;  // (4 bits, three chunks: not instantiated)
   int64_t nt = (tiles + cus - 1) / cus;
   if (nt > WR_UNITS_MAX / cpw) nt = WR_UNITS_MAX / cpw;
-  if (d.bits == 8) {  // twice the registers per unit
-    if (cpw > 2) return plan;
-    if (nt * cpw > 2) nt = cpw == 1 ? 2 : 1;
+  if (d.bits == 8) {  // twice the registers per unit: one chunk per wave, two tiles at most
+    if (cpw > 1) return plan;
+    if (nt > 2) nt = 2;
   }
   if (!any_size) {
     const int64_t T = d.T;
@@ -1481,13 +1527,13 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
     } else if (d.bits == 3) {
       if (cpw == 1) hi = nt >= 3 ? 64 : nt == 2 ? 48 : 40;
       else if (cpw == 2) hi = nt == 2 ? 64 : 16;
-      else hi = 32;
+      else hi = 16;
       if (few_tiles && cpw == 1) hi = 64;
     } else if (d.bits == 2) {
       lo = nt == 1 && cpw == 1 ? 3 : 1;
       hi = 64;
       if (few_tiles) lo = 17;
-    } else if (cpw == 1) {
+    } else {
       lo = (int64_t)plan_grid_rounds(tiles, nt, cus) > 1 ? 2 : 1;
       hi = lo > 1 ? 16 : 32;
       if (few_tiles) { lo = 17; hi = 48; }
@@ -1515,17 +1561,19 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false) {
 
 template <int BITS>
 void launch_qgemm_wreg(const WregPlan& plan, const LayerDims& d, const bf16_t* X, const uint32_t* packed,
-                       const float* scale, const float* zero, bf16_t* Y, hipStream_t stream) {
-  const int64_t G = d.i / d.g;
+                       const float* scale, const float* zero, bf16_t* Y, float* partial, hipStream_t stream) {
+  int64_t G = d.i / d.g;  // groups a workgroup's tables hold: all of a row's, or those a k-slice can meet
+  if (plan.slices > 1 && (int64_t)plan.wv * plan.cpw * 256 / d.g + 2 < G) G = (int64_t)plan.wv * plan.cpw * 256 / d.g + 2;
   const size_t lds_bytes =
       ((size_t)2 * plan.nt * plan.tbp * plan.wv * 256 + (size_t)2 * plan.nt * 16 * (G | 1)) * sizeof(float);
+  float* part = plan.slices > 1 ? partial : nullptr;
 #define L4Q_WR(N, C, W, P)                                                                                          \
   do {                                                                                                               \
     if (lds_bytes > 64 * 1024)                                                                                       \
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&qgemm_wreg_kernel<BITS, N, C, W, P>),                 \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, QD_LDS_MAX);                             \
-    hipLaunchKernelGGL((qgemm_wreg_kernel<BITS, N, C, W, P>), dim3(plan.grid), dim3(W * 64), lds_bytes, stream, X,   \
-                       packed, scale, zero, Y, (int)d.T, (int)d.o, (int)d.i, d.g);                                   \
+    hipLaunchKernelGGL((qgemm_wreg_kernel<BITS, N, C, W, P>), dim3(plan.grid, plan.slices), dim3(W * 64), lds_bytes, \
+                       stream, X, packed, scale, zero, Y, part, (int)d.T, (int)d.o, (int)d.i, d.g);                  \
   } while (0)
   const int key = plan.nt * 10 + plan.cpw;
   // (every combination qgemm_wreg_plan can return, and no other)
@@ -1535,7 +1583,7 @@ void launch_qgemm_wreg(const WregPlan& plan, const LayerDims& d, const bf16_t* X
       else if (key == 12) L4Q_WR(1, 2, 8, 2); else if (key == 22) L4Q_WR(2, 2, 8, 2); else L4Q_WR(3, 2, 8, 2);
     }
   } else if constexpr (BITS == 8) {
-    if (key == 11) L4Q_WR(1, 1, 16, 1); else if (key == 21) L4Q_WR(2, 1, 16, 1); else L4Q_WR(1, 2, 16, 1);
+    if (key == 11) L4Q_WR(1, 1, 16, 1); else L4Q_WR(2, 1, 16, 1);
   } else {
     if (key == 11) L4Q_WR(1, 1, 16, 1); else if (key == 21) L4Q_WR(2, 1, 16, 1); else if (key == 31) L4Q_WR(3, 1, 16, 1);
     else if (key == 41) L4Q_WR(4, 1, 16, 1); else if (key == 12) L4Q_WR(1, 2, 16, 1); else if (key == 22) L4Q_WR(2, 2, 16, 1);
@@ -1543,6 +1591,11 @@ void launch_qgemm_wreg(const WregPlan& plan, const LayerDims& d, const bf16_t* X
     else if constexpr (BITS != 4) L4Q_WR(1, 3, 16, 1);  // (4 bits: one register too many, and no faster than the streaming forms)
   }
 #undef L4Q_WR
+  if (plan.slices > 1) {
+    const int64_t quads = d.T * d.o / 4;
+    hipLaunchKernelGGL(qgemm_slices_sum_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream, partial, Y,
+                       plan.slices, (int)d.T, 0, (int)d.o);
+  }
 }
 
 }  // namespace
@@ -1557,8 +1610,12 @@ bool qgemm_supported(const LayerDims& d) { return (d.bits == 2 || d.bits == 3 ||
 
 size_t qgemm_workspace_bytes(const LayerDims& d) {
   const TilePlan plan = qgemm_tile_plan(d);
-  if (plan.tb_max == 0 || plan.slices <= 1) return 0;
-  return (size_t)plan.slices * 16 * plan.tb_max * (size_t)d.o * sizeof(float);  // [slice][token of a pass][row]
+  size_t tile_bytes = 0, wreg_bytes = 0;
+  if (plan.tb_max > 0 && plan.slices > 1)
+    tile_bytes = (size_t)plan.slices * 16 * plan.tb_max * (size_t)d.o * sizeof(float);  // [slice][token of a pass][row]
+  const int ws = qgemm_wreg_slices(d);
+  if (ws > 1) wreg_bytes = (size_t)ws * WR_SLICE_T_MAX * (size_t)d.o * sizeof(float);  // [slice][token][row]
+  return tile_bytes > wreg_bytes ? tile_bytes : wreg_bytes;
 }
 
 void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, const float* scale, const float* zero,
@@ -1566,12 +1623,13 @@ void launch_qgemm(const LayerDims& d, const bf16_t* X, const uint32_t* packed, c
   dim3 grid((unsigned)((d.o + 31) / 32));
   // a few token blocks at most, groups of 128 and more: the packed codes resident in registers
   if (L4Q_WREG_SWITCH) {
-    const WregPlan wr = qgemm_wreg_plan(d, L4Q_WREG_ANY);
+    const WregPlan wr =
+        qgemm_wreg_plan(d, L4Q_WREG_ANY, partial != nullptr && partial_bytes >= qgemm_workspace_bytes(d));
     if (wr.nt > 0) {
-      if (d.bits == 2) launch_qgemm_wreg<2>(wr, d, X, packed, scale, zero, Y, stream);
-      else if (d.bits == 3) launch_qgemm_wreg<3>(wr, d, X, packed, scale, zero, Y, stream);
-      else if (d.bits == 4) launch_qgemm_wreg<4>(wr, d, X, packed, scale, zero, Y, stream);
-      else launch_qgemm_wreg<8>(wr, d, X, packed, scale, zero, Y, stream);
+      if (d.bits == 2) launch_qgemm_wreg<2>(wr, d, X, packed, scale, zero, Y, partial, stream);
+      else if (d.bits == 3) launch_qgemm_wreg<3>(wr, d, X, packed, scale, zero, Y, partial, stream);
+      else if (d.bits == 4) launch_qgemm_wreg<4>(wr, d, X, packed, scale, zero, Y, partial, stream);
+      else launch_qgemm_wreg<8>(wr, d, X, packed, scale, zero, Y, partial, stream);
       return;
     }
   }

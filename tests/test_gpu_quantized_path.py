@@ -96,7 +96,7 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     # tiles with groups of 256; (1, 2); (2, 2) with groups of 512; three chunks (4 bits: a streaming form); (1, 4); (1, 4) with groups of 1024 and a
     # ragged tile; two token blocks on a 256-tile layer; four tiles over three token blocks; one token
     (33, 4096, 11000, 4, 128), (5, 2048 + 128, 6000, 4, 128), (40, 1024, 13000, 4, 256), (9, 8192, 3000, 4, 128),
-    (20, 5120, 8000, 4, 512), (12, 11008, 4096, 4, 128), (7, 14336, 2400, 4, 128), (3, 16384, 2056, 4, 1024),
+    (20, 5120, 8000, 4, 512), (5, 11008, 4096, 3, 128), (7, 14336, 2400, 4, 128), (3, 16384, 2056, 4, 1024),
     (20, 4096, 4096, 4, 128), (48, 4096, 12296, 4, 128), (1, 4096, 11008, 4, 128),
     # 3 bits (12-byte pieces): (3, 1) over three token blocks, (1, 3), (2, 2), (1, 4) with groups of 256, one token
     (48, 4096, 11000, 3, 128), (16, 11008, 4096, 3, 128), (30, 8192, 8192, 3, 128), (2, 16384, 2056, 3, 256),
@@ -115,6 +115,12 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     (20, 2048, 11008, 4, 128), (20, 2048, 11008, 3, 128), (20, 2048, 11008, 2, 128),
     (25, 1024, 6008, 4, 256), (25, 1024, 6008, 3, 256), (25, 1024, 6008, 2, 256),
     (31, 1152, 1000, 4, 128), (31, 1152, 1000, 3, 128), (31, 1152, 1000, 2, 128),
+    # long rows on layers of 128 .. 256 row tiles, with the workspace: k-slices of 16 chunks (3, 2, 4 and 3 slices; the
+    # last slice short; 16- and 8-wave shapes; groups of 256, of 512, and of 8192, which span two slices; a ragged
+    # last tile)
+    (12, 11008, 4096, 4, 128), (12, 11008, 4096, 3, 128), (12, 11008, 4096, 2, 128), (24, 8192, 4096, 4, 128),
+    (9, 14336, 2400, 4, 128), (20, 14336, 2400, 3, 256), (16, 12288, 3000, 2, 128), (10, 11264, 4096, 4, 512),
+    (8, 16384, 2056, 4, 8192),
     # ... and two passes of it (49 .. 64 tokens), the last block partial
     (64, 4096, 11000, 4, 128), (64, 4096, 11000, 3, 128), (64, 4096, 11000, 2, 128), (50, 4096, 6000, 2, 128),
 ])
