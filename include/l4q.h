@@ -175,7 +175,7 @@ int l4q_export_packed(const l4q_desc* desc, const void* W0, const void* A, const
  * the packed weights are streamed once per pass of at most 64 tokens (32 or 48 for some shapes), so the
  * cost grows with T beyond that.
  * workspace (device memory, 256-byte aligned) is optional: NULL / 0 is always accepted.  Layers with few output
- * rows and long rows run faster at more than 16 tokens (3-bit layers: also below) when given
+ * rows and long rows run faster from about 8 tokens on when given
  * l4q_quantized_forward_workspace_bytes() of it
  * (the row is then cut into k-slices over the compute units, whose partial sums are added in a fixed order);
  * a workspace smaller than that is ignored.  The result does not depend on the stream's other work, but with and

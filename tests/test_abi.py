@@ -116,7 +116,8 @@ def test_quantized_forward_workspace_query_and_argument_checks(lib):
     assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow3), ctypes.byref(n)) == 0
     assert n.value > 0 and n.value % (4096 * 4) == 0          # 3 bits: k-slices of whole three-stage units
     narrow2 = binding.make_desc(LayerSpec("down2", 64, 11008, 4096, 16, 32.0, 2, 128, DTYPE_BF16))
-    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow2), ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow2), ctypes.byref(n)) == 0
+    assert n.value == 3 * 32 * 4096 * 4                       # 2 bits: the in-register form's three k-slices, 32 tokens
     f32 = binding.make_desc(LayerSpec("f", 64, 11008, 4096, 16, 32.0, 4, 128, DTYPE_F32))
     assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(f32), ctypes.byref(n)) == 0 and n.value == 0
     assert lib.l4q_quantized_forward_workspace_bytes(ctypes.byref(narrow), None) == -1
