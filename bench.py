@@ -223,6 +223,15 @@ def main() -> int:
         packs.append(pk)
     qfws = [torch.empty(max(256, binding.l4q_quantized_forward_workspace_bytes(l.desc)), dtype=torch.uint8,
                        device="cuda:0") for l in layers]
+    def run_ahead():
+        """About a millisecond of GPU work that moves no data, behind which the host queues the timed launches."""
+        spin = getattr(torch.cuda, "_sleep", None)
+        if spin is not None:
+            spin(3_000_000)
+        else:
+            for _ in range(5):
+                layers[0].forward()
+
     def time_decode(descs_, xs_, packs_, ys_, wss_, tok):
         """Both layers back to back (the pair figure), then each layer's launch on its own: the packed weights, scale
         and zero, and the activations in and out are the algorithmic bytes; 8 TB/s is the roofline."""
@@ -242,7 +251,7 @@ def main() -> int:
             # call): a spinning kernel goes first, untimed, so that the host runs ahead and the timed launches are
             # queued back to back by the time the GPU reaches the first event.  (The same 22.5 MB of codes per layer
             # are read by every launch: they are served by the 256 MB memory-side cache, not HBM, after the first.)
-            torch.cuda._sleep(3_000_000)
+            run_ahead()
             ev0.record()
             for _ in range(50):
                 for k in ks:
@@ -273,7 +282,7 @@ def main() -> int:
         for c in copies:
             binding.l4q_quantized_forward(d1, x1, c, layers[k].scale, layers[k].zero, y1, qfws[k])
         torch.cuda.synchronize()
-        torch.cuda._sleep(3_000_000)
+        run_ahead()
         ev0.record()
         for rep in range(4):
             for c in copies:
