@@ -88,6 +88,33 @@ def test_quantized_forward_random_tile_shapes(k, T, i, o, bits, g):
     test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
 
 
+def _random_in_register_cases(count=24, seed=355):
+    """Seeded draw over the domain of the in-register form: every code width, power-of-two groups from 128 up to the
+    row length, rows of 1 .. 64 chunks of 256 (with half chunks), 128 .. 16800 output rows in steps of 8 (one to four
+    tiles per workgroup, ragged last tiles, layers too small to fill the chip), 1 .. 64 tokens around the block and
+    pass boundaries; at most 48 M weights
+    so that the oracle stays fast.  The library picks the form (and its shape) per case; with the workspace the k-sliced
+    forms run as well."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        bits = int(rng.choice([2, 3, 4, 4, 8]))
+        i = 128 * int(rng.integers(1, 129))
+        o = 8 * int(rng.integers(16, 2101))
+        if o * i > 48_000_000:
+            continue
+        gs = [g for g in (128, 256, 512, 1024, 2048, 4096, 8192) if i % g == 0]
+        g = int(rng.choice(gs))
+        T = int(rng.choice([1, 2, 3, 5, 8, 9, 12, 15, 16, 17, 20, 24, 31, 32, 33, 40, 49, 56, 64]))
+        cases.append((len(cases), T, i, o, bits, g))
+    return cases
+
+
+@pytest.mark.parametrize("k,T,i,o,bits,g", _random_in_register_cases())
+def test_quantized_forward_random_in_register_shapes(k, T, i, o, bits, g):
+    test_quantized_forward_matches_oracle_and_training_forward(T, i, o, bits, g)
+
+
 @pytest.mark.parametrize("T,i,o,bits,g", [
     # Shapes and batches the weights-in-registers form takes (groups of 128 and more, a few token blocks), one per
     # combination of row tiles per workgroup (1 .. 4: up to 4096 / 8192 / 12288 / more rows on 256 compute units) and
