@@ -1518,21 +1518,31 @@ WregPlan qgemm_wreg_plan(const LayerDims& d, bool any_size = false, bool have_wo
   if (!any_size) {
     const int64_t T = d.T;
     const bool few_tiles = 2 * tiles < cus;  // (the streaming forms split k further over the idle units)
+    // More workgroups than compute units (13B / 70B-class projections; us at 4 / 16 / 24 / 40 tokens): the later rounds
+    // do not overlap the first one's latency, and the streaming forms catch up beyond a token block -
+    // 4 bits [28672 x 8192] 39.5 / 55.9 / 76.8 / 105 against 46.6 / 67.4 / 76.0 / 98.7, [13824 x 5120] 18.0 / 22.8 /
+    // 31.5 / 42.7 against 18.9 / 23.1 / 26.0 / 33.6, [5120 x 13824] (4 chunks per wave) 23.3 / 36.2 against 20.7 / 37.7;
+    // 3 bits [13824 x 5120] 19.6 / 24.3 / 34.6 / 46.5 against 26.8 / 26.9 / 28.8 / 40.0;
+    // 2 bits [5120 x 13824] 22.7 / 35.0 / 51.4 / 76.2 against 22.8 / 36.1 / 39.7 / 57.4, one token 17 - 37 against 12 - 30.
+    const bool many = plan_grid_rounds(tiles, nt, cus) > 1;
     int64_t lo = 1, hi = 0;
     if (d.bits == 4) {
       if (cpw == 1) { lo = nt == 1 ? 17 : 1; hi = nt >= 3 ? 64 : nt == 2 ? 48 : 40; }
       else if (cpw == 2) { lo = nt == 2 ? 3 : 6; hi = nt == 2 ? 40 : 16; }
       else { lo = 3; hi = 16; }
       if (few_tiles) { lo = 17; hi = cpw == 1 ? 64 : 0; }
+      if (many) hi = cpw >= 3 ? 0 : hi < 16 ? hi : 16;
     } else if (d.bits == 3) {
       if (cpw == 1) hi = nt >= 3 ? 64 : nt == 2 ? 48 : 40;
       else if (cpw == 2) hi = nt == 2 ? 64 : 16;
       else hi = 16;
       if (few_tiles && cpw == 1) hi = 64;
+      if (many) hi = cpw >= 3 ? 8 : hi < 16 ? hi : 16;
     } else if (d.bits == 2) {
       lo = nt == 1 && cpw == 1 ? 3 : 1;
       hi = 64;
       if (few_tiles) lo = 17;
+      if (many) { lo = 2; if (cpw >= 3) hi = 16; }
     } else {
       lo = (int64_t)plan_grid_rounds(tiles, nt, cus) > 1 ? 2 : 1;
       hi = lo > 1 ? 16 : 32;
