@@ -266,7 +266,7 @@ def main() -> int:
         out_["per_layer"] = {k: v for k, v in res.items() if k != "both_layers"}
         return out_
 
-    for tok in (1, 16, 64):
+    for tok in (1, 16, 32, 64):
         descs = [binding.make_desc(l.spec.with_(tokens=tok)) for l in layers]
         xs = [l.X[:tok] for l in layers]
         ys = [l.Y[:tok] for l in layers]
